@@ -1,0 +1,147 @@
+/*
+ * w4a8.h -- C ABI of the MI355X (gfx950) W4A8 linear-layer library.
+ *
+ * The library implements the inference hot path of a W4A8 quantised linear
+ * layer as described in arXiv 2311.09550 ("A Speed Odyssey for Deployable
+ * Quantization of LLMs"): activations quantised per token to signed 8 bit,
+ * weights quantised per output channel to signed 4 bit with no group scales,
+ * integer GEMM with int32 accumulation, one dequantisation after the GEMM
+ * (Sec. 4.2, Eq. (6),(7); Sec. 5.3 "Fast Mixed-Precision GEMM").
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers are DEVICE pointers unless the name ends in _host.
+ *   - Matrices are dense row-major with no padding between rows.
+ *       X   : M x K        (Fig. 2 caption: the activation is M x K)
+ *       Wp  : N x K/2      packed weights, N = output dimension (Table 5 caption)
+ *       O   : M x N
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls are asynchronous on that stream; the library never synchronises,
+ *     allocates or frees device memory.  The caller owns every buffer.
+ *   - Inputs and outputs must not alias.  Device buffers must be 16-byte
+ *     aligned (any hipMalloc / torch allocation is).
+ *   - Return value: W4A8_OK (0) or a negative W4A8_ERR_* code.  When an error
+ *     is returned nothing has been launched and no output was touched.
+ *   - Shape contract: M, N >= 1; K >= 32, K % 32 == 0 (a packed row is a
+ *     multiple of 16 bytes) and K <= 65536.  The upper bound keeps the
+ *     sixteen-fold accumulator of the sign-bit trick (Sec. 5.3) inside int32
+ *     even for activations equal to -128 and weights equal to -8.
+ */
+#ifndef W4A8_H
+#define W4A8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define W4A8_OK 0
+#define W4A8_ERR_NULL (-1)      /* a required pointer is NULL                          */
+#define W4A8_ERR_SHAPE (-2)     /* M, N, K outside the shape contract above            */
+#define W4A8_ERR_ALIGN (-3)     /* a device pointer is not 16-byte aligned             */
+#define W4A8_ERR_WORKSPACE (-4) /* workspace missing or smaller than required          */
+#define W4A8_ERR_LAUNCH (-5)    /* the HIP runtime rejected the launch                 */
+#define W4A8_ERR_VALUE (-6)     /* host helper: a weight code outside [-8, 7]          */
+#define W4A8_ERR_ARG (-7)       /* an option (tiling id, split count) is out of range  */
+
+#define W4A8_MAX_K 65536
+
+/* Library version: major*10000 + minor*100 + patch. */
+int w4a8_version(void);
+
+/* Static, never-NULL description of an error code. */
+const char *w4a8_strerror(int err);
+
+/*
+ * Per-token activation quantisation (Sec. 3 "Per tensor vs. Per token";
+ * Eq. (2) with zero point 0; Table 1 row RTN_pt).
+ * For every row m:  amax = max_k |X[m][k]|,  s_a[m] = amax / 127 (fp32 division),
+ * Xq[m][k] = clamp(round_half_even(X[m][k] / s_a[m]), -127, 127).
+ * A row of zeros yields s_a[m] = 0 and zero codes.  Non-finite inputs are
+ * outside the contract.
+ *   x_fp16 [M][K] IEEE binary16      in
+ *   xq     [M][K] int8               out
+ *   s_a    [M]    fp32               out
+ */
+int w4a8_quantize_act(const void *x_fp16, int8_t *xq, float *s_a, int M, int K, void *stream);
+
+/*
+ * Bytes of workspace w4a8_gemm / w4a8_gemm_acc_i32 need for this shape (a pure
+ * function of the shape, 0 for an invalid one).  The workspace holds split-K
+ * partial sums and per-tile arrival counters.  It must be zero-filled once
+ * before its first use; every call leaves the counters at zero again, so the
+ * same buffer can be reused by later calls ON THE SAME STREAM.  Calls that may
+ * overlap in time (different streams) need different workspaces.
+ */
+size_t w4a8_gemm_workspace_bytes(int M, int N, int K);
+
+/*
+ * The W4A8 GEMM with fused dequantisation (Sec. 5.3; Eq. (6),(7)):
+ *   O[m][n] = fp16( float( sum_k Xq[m][k] * Wq[n][k] ) * (s_a[m] * s_w[n]) )
+ * where Wq[n][k] in [-8,7] is the signed value of the nibble stored in
+ * wp[n][k/2] (low nibble for even k, high nibble for odd k; App. A.1: the low
+ * four bits of the two's complement are what is packed).  The sum is exact
+ * (int32); the scale product is rounded to fp32, multiplied by the fp32 value
+ * of the sum and rounded once to fp16 (round to nearest even, overflow to inf).
+ *   xq  [M][K]   int8 (any value in [-128,127])  in
+ *   s_a [M]      fp32                            in
+ *   wp  [N][K/2] uint8                           in, immutable during the call
+ *   s_w [N]      fp32 (the paper's s)            in
+ *   out_fp16 [M][N] IEEE binary16                out
+ */
+int w4a8_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w,
+              void *out_fp16, int M, int N, int K,
+              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Same contraction, raw result: acc[m][n] = sum_k Xq[m][k] * Wq[n][k] as int32
+ * (the division by 16 that undoes the high-nibble placement is already applied).
+ * For tests and debugging.
+ */
+int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, int N, int K,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * As the two calls above, with the tiling forced instead of chosen from the
+ * shape.  For tuning sweeps and for tests that must cover every tiling at
+ * every shape.  `tiling` is one of W4A8_TILING_*; `split_k` >= 1 is the number
+ * of K slices whose partial sums are combined through the workspace (0 = let
+ * the library choose).  Exactly one of out_fp16 / acc_i32 must be non-NULL
+ * (s_a and s_w may be NULL when acc_i32 is requested).
+ */
+#define W4A8_TILING_AUTO 0
+#define W4A8_TILING_DECODE 1  /* weight-streaming tiling for small M (M <= 64)        */
+#define W4A8_TILING_PREFILL 2 /* LDS-staged 128 x 256 tiling for large M              */
+int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w,
+                    void *out_fp16, int32_t *acc_i32, int M, int N, int K,
+                    int tiling, int split_k,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Offline weight preparation on the device (Sec. 5.1 Eq. (8),(9) with 4 bits
+ * and clipping strengths gamma = beta = 1, followed by the packing of App. A.1):
+ *   s_w[n] = max_k |W[n][k]| / 7,  Wq = clamp(round_half_even(W / s_w), -8, 7),
+ *   wp[n][j] = (Wq[n][2j] & 15) | ((Wq[n][2j+1] & 15) << 4).
+ *   w_fp16 [N][K] in, wp [N][K/2] out, s_w [N] out.
+ */
+int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, int K, void *stream);
+
+/*
+ * Glue between the gate/up GEMM and the down GEMM of a LLaMA MLP:
+ *   h[m][i] = fp16( silu(gate_up[m][i]) * gate_up[m][I + i] ),  fp32 arithmetic.
+ *   gate_up_fp16 [M][2I] in, h_fp16 [M][I] out.  I % 8 == 0.
+ */
+int w4a8_silu_mul(const void *gate_up_fp16, void *h_fp16, int M, int I, void *stream);
+
+/*
+ * Host-side packing of already quantised weights (App. A.1; no GPU needed).
+ *   wq_host [N][K] int8 codes in [-8,7]  ->  wp_host [N][K/2].
+ * Returns W4A8_ERR_VALUE if a code is out of range, W4A8_ERR_SHAPE if K is odd.
+ */
+int w4a8_pack_weights_host(const int8_t *wq_host, uint8_t *wp_host, int N, int K);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W4A8_H */

@@ -1,0 +1,204 @@
+"""Thin Python binding of the MI355X W4A8 library (``libw4a8.so``).
+
+Only argument marshalling happens here: torch supplies device memory and the
+current HIP stream, every step of the path runs in the HIP kernels behind the C
+ABI declared in ``include/w4a8.h``.  There is no CPU fallback: if the library
+has not been built (``python -m paper_2311_09550_amd.build`` or
+``__graft_entry__.build()``), the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libw4a8.so")
+
+TILING_AUTO, TILING_DECODE, TILING_PREFILL = 0, 1, 2
+
+_lib = None
+
+
+class W4A8Error(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"w4a8 error {code}: {what}")
+        self.code = code
+
+
+def lib():
+    """Load libw4a8.so (once).  Fails loudly when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build the HIP library first "
+                "(python -m paper_2311_09550_amd.build); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.w4a8_version.restype = i
+        L.w4a8_strerror.restype = ctypes.c_char_p
+        L.w4a8_strerror.argtypes = [i]
+        L.w4a8_quantize_act.argtypes = [vp, vp, vp, i, i, vp]
+        L.w4a8_gemm_workspace_bytes.restype = sz
+        L.w4a8_gemm_workspace_bytes.argtypes = [i, i, i]
+        L.w4a8_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, sz, vp]
+        L.w4a8_gemm_acc_i32.argtypes = [vp, vp, vp, i, i, i, vp, sz, vp]
+        L.w4a8_gemm_tuned.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+        L.w4a8_quantize_weights.argtypes = [vp, vp, vp, i, i, vp]
+        L.w4a8_silu_mul.argtypes = [vp, vp, i, i, vp]
+        L.w4a8_pack_weights_host.argtypes = [vp, vp, i, i]
+        for name in ("w4a8_quantize_act", "w4a8_gemm", "w4a8_gemm_acc_i32", "w4a8_gemm_tuned",
+                     "w4a8_quantize_weights", "w4a8_silu_mul", "w4a8_pack_weights_host"):
+            getattr(L, name).restype = i
+        _lib = L
+    return _lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise W4A8Error(code, lib().w4a8_strerror(code).decode())
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream():
+    return ctypes.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, what):
+    torch = _torch()
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{what}: expected a contiguous device tensor of {dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def w4a8_version() -> int:
+    return int(lib().w4a8_version())
+
+
+def w4a8_strerror(code: int) -> str:
+    return lib().w4a8_strerror(code).decode()
+
+
+def w4a8_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().w4a8_gemm_workspace_bytes(M, N, K))
+
+
+_workspaces = {}
+
+
+def workspace(M: int, N: int, K: int, device=None):
+    """A zero-filled workspace tensor large enough for (M, N, K), cached per device and stream."""
+    torch = _torch()
+    device = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+    need = max(w4a8_gemm_workspace_bytes(M, N, K), 256)
+    key = (device.index, torch.cuda.current_stream(device).cuda_stream)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.zeros(need, dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
+
+
+def w4a8_quantize_act(x, xq=None, s_a=None):
+    """fp16 [M][K] -> (int8 [M][K], fp32 [M])."""
+    torch = _torch()
+    M, K = x.shape
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device) if xq is None else xq
+    s_a = torch.empty((M,), dtype=torch.float32, device=x.device) if s_a is None else s_a
+    _check(lib().w4a8_quantize_act(_dev(x, torch.float16, "x"), _dev(xq, torch.int8, "xq"),
+                                   _dev(s_a, torch.float32, "s_a"), M, K, _stream()))
+    return xq, s_a
+
+
+def w4a8_gemm(xq, s_a, wp, s_w, out=None, ws=None):
+    """int8 [M][K], fp32 [M], uint8 [N][K/2], fp32 [N] -> fp16 [M][N]."""
+    torch = _torch()
+    M, K = xq.shape
+    N = wp.shape[0]
+    if wp.shape[1] * 2 != K or s_a.shape != (M,) or s_w.shape != (N,):
+        raise ValueError("shape mismatch")
+    out = torch.empty((M, N), dtype=torch.float16, device=xq.device) if out is None else out
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    ws = workspace(M, N, K, xq.device) if ws is None else ws
+    _check(lib().w4a8_gemm(_dev(xq, torch.int8, "xq"), _dev(s_a, torch.float32, "s_a"), _dev(wp, torch.uint8, "wp"),
+                           _dev(s_w, torch.float32, "s_w"), _dev(out, torch.float16, "out"), M, N, K,
+                           _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
+    return out
+
+
+def w4a8_gemm_acc_i32(xq, wp, acc=None, ws=None):
+    """int8 [M][K], uint8 [N][K/2] -> int32 [M][N] raw sums."""
+    torch = _torch()
+    M, K = xq.shape
+    N = wp.shape[0]
+    if wp.shape[1] * 2 != K:
+        raise ValueError("shape mismatch")
+    acc = torch.empty((M, N), dtype=torch.int32, device=xq.device) if acc is None else acc
+    if acc.shape != (M, N):
+        raise ValueError("acc shape mismatch")
+    ws = workspace(M, N, K, xq.device) if ws is None else ws
+    _check(lib().w4a8_gemm_acc_i32(_dev(xq, torch.int8, "xq"), _dev(wp, torch.uint8, "wp"), _dev(acc, torch.int32, "acc"),
+                                   M, N, K, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
+    return acc
+
+
+def w4a8_gemm_tuned(xq, s_a, wp, s_w, tiling: int, split_k: int = 0, want_acc: bool = False, out=None, ws=None):
+    """Forced tiling / split count; returns fp16 [M][N], or int32 [M][N] when want_acc."""
+    torch = _torch()
+    M, K = xq.shape
+    N = wp.shape[0]
+    if wp.shape[1] * 2 != K:
+        raise ValueError("shape mismatch")
+    ws = workspace(M, N, K, xq.device) if ws is None else ws
+    if want_acc:
+        out = torch.empty((M, N), dtype=torch.int32, device=xq.device) if out is None else out
+        o16, o32 = None, _dev(out, torch.int32, "acc")
+        sa = None if s_a is None else _dev(s_a, torch.float32, "s_a")
+        sw = None if s_w is None else _dev(s_w, torch.float32, "s_w")
+    else:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device) if out is None else out
+        o16, o32 = _dev(out, torch.float16, "out"), None
+        sa, sw = _dev(s_a, torch.float32, "s_a"), _dev(s_w, torch.float32, "s_w")
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    _check(lib().w4a8_gemm_tuned(_dev(xq, torch.int8, "xq"), sa, _dev(wp, torch.uint8, "wp"), sw, o16, o32, M, N, K,
+                                 tiling, split_k, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
+    return out
+
+
+def w4a8_quantize_weights(w, wp=None, s_w=None):
+    """fp16 [N][K] -> (uint8 [N][K/2] packed int4, fp32 [N])."""
+    torch = _torch()
+    N, K = w.shape
+    wp = torch.empty((N, K // 2), dtype=torch.uint8, device=w.device) if wp is None else wp
+    s_w = torch.empty((N,), dtype=torch.float32, device=w.device) if s_w is None else s_w
+    _check(lib().w4a8_quantize_weights(_dev(w, torch.float16, "w"), _dev(wp, torch.uint8, "wp"),
+                                       _dev(s_w, torch.float32, "s_w"), N, K, _stream()))
+    return wp, s_w
+
+
+def w4a8_silu_mul(gate_up, h=None):
+    """fp16 [M][2I] -> fp16 [M][I]."""
+    torch = _torch()
+    M, I2 = gate_up.shape
+    I = I2 // 2
+    h = torch.empty((M, I), dtype=torch.float16, device=gate_up.device) if h is None else h
+    _check(lib().w4a8_silu_mul(_dev(gate_up, torch.float16, "gate_up"), _dev(h, torch.float16, "h"), M, I, _stream()))
+    return h
+
+
+def w4a8_pack_weights_host(wq):
+    """numpy int8 [N][K] codes in [-8,7] -> numpy uint8 [N][K/2] (host helper, no GPU)."""
+    import numpy as np
+    wq = np.ascontiguousarray(wq)
+    if wq.dtype != np.int8 or wq.ndim != 2:
+        raise TypeError("wq: expected a 2-D int8 array")
+    N, K = wq.shape
+    wp = np.empty((N, K // 2), np.uint8)
+    _check(lib().w4a8_pack_weights_host(wq.ctypes.data_as(ctypes.c_void_p), wp.ctypes.data_as(ctypes.c_void_p), N, K))
+    return wp

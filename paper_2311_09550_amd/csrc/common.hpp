@@ -1,0 +1,76 @@
+// Internal device helpers shared by the gfx950 kernels of the W4A8 library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace w4a8 {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+
+// D(16x16,int32) += A(16x64,int8) * B(64x16,int8).
+// Operand layout on a 64-lane wave: lane l supplies row (l & 15) of A and column
+// (l & 15) of B, 16 consecutive-in-register bytes of K group (l >> 4).  Lane l
+// receives D[4*(l >> 4) + r][l & 15] in register r.  Which 16 values of k a K
+// group stands for is the same for A and B, so any assignment of k to
+// (group, byte) may be used as long as both operands follow it.
+__device__ __forceinline__ v4i mfma_i8_16x16x64(v4i a, v4i b, v4i c) {
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+
+// Signed int4 -> signed int8 without a subtraction (Sec. 5.3 "Reusing the sign
+// bit", App. A.1): each stored nibble is moved into the high half of a byte, so
+// the byte reads as 16 times the weight.  One packed word holds k = 0..7
+// (low nibble of byte j is k = 2j, high nibble is k = 2j+1):
+//   even = bytes {16 w0, 16 w2, 16 w4, 16 w6},  odd = bytes {16 w1, 16 w3, 16 w5, 16 w7}.
+__device__ __forceinline__ void sint4_to_s8x16(unsigned w, int &even, int &odd) {
+    even = (int)((w << 4) & 0xF0F0F0F0u);
+    odd = (int)(w & 0xF0F0F0F0u);
+}
+
+// Two packed words (k = 0..15 of a lane's K group) -> one MFMA operand whose
+// registers hold k = {0,2,4,6}, {1,3,5,7}, {8,10,12,14}, {9,11,13,15}.
+__device__ __forceinline__ v4i w_operand(unsigned w0, unsigned w1) {
+    v4i r;
+    int e, o;
+    sint4_to_s8x16(w0, e, o);
+    r.x = e;
+    r.y = o;
+    sint4_to_s8x16(w1, e, o);
+    r.z = e;
+    r.w = o;
+    return r;
+}
+
+// 16 consecutive int8 activations (k = 0..15) reordered to the k order of
+// w_operand: bytes {0,2,4,6}, {1,3,5,7} of the first eight, then of the second eight.
+__device__ __forceinline__ v4i x_operand(v4u x) {
+    v4i r;
+    r.x = (int)__builtin_amdgcn_perm(x.y, x.x, 0x06040200u);
+    r.y = (int)__builtin_amdgcn_perm(x.y, x.x, 0x07050301u);
+    r.z = (int)__builtin_amdgcn_perm(x.w, x.z, 0x06040200u);
+    r.w = (int)__builtin_amdgcn_perm(x.w, x.z, 0x07050301u);
+    return r;
+}
+
+// Dequantisation after the GEMM (Eq. (6),(7)): acc16 is sixteen times the true
+// sum; the arithmetic shift restores it exactly (its low four bits are zero).
+__device__ __forceinline__ float dequant(int acc16, float s_a, float s_w) {
+    float s_ij = s_a * s_w;
+    return (float)(acc16 >> 4) * s_ij;
+}
+
+__device__ __forceinline__ unsigned short f32_to_f16_bits(float v) {
+    return __half_as_ushort(__float2half_rn(v));
+}
+
+__device__ __forceinline__ unsigned pack_f16x2(float lo, float hi) {
+    return (unsigned)f32_to_f16_bits(lo) | ((unsigned)f32_to_f16_bits(hi) << 16);
+}
+
+}  // namespace w4a8

@@ -17,3 +17,15 @@ def oracle():
     import oracle as _oracle
     _oracle.build()
     return _oracle
+
+
+@pytest.fixture(scope="session")
+def gpu():
+    """torch on cuda:0 with the HIP library loaded; the tests using it are marked gpu."""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2311_09550_amd as w4a8
+    w4a8.lib()  # raises if the HIP library is missing: there is no fallback to test
+    torch.cuda.set_device(0)
+    return torch

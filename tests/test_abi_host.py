@@ -1,0 +1,104 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header
+declares, validates arguments before touching the GPU, and its host packing
+helper agrees with the oracle.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2311_09550_amd as w4a8
+from paper_2311_09550_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "w4a8.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(w4a8.LIB_PATH):
+        from paper_2311_09550_amd.build import build_library
+        build_library(force=True)
+    return w4a8.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(w4a8_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(L):
+    syms = declared_symbols()
+    assert {"w4a8_quantize_act", "w4a8_gemm", "w4a8_gemm_acc_i32", "w4a8_gemm_workspace_bytes",
+            "w4a8_pack_weights_host", "w4a8_strerror", "w4a8_version"} <= set(syms)
+    for s in syms:
+        assert hasattr(L, s), s
+
+
+def test_version_and_strerror(L):
+    assert L.w4a8_version() >= 100
+    seen = set()
+    for code in range(0, -8, -1):
+        msg = w4a8.w4a8_strerror(code)
+        assert msg and msg not in seen
+        seen.add(msg)
+    assert "unknown" in w4a8.w4a8_strerror(-99)
+
+
+def test_workspace_bytes_is_a_pure_function_of_shape(L):
+    assert w4a8.w4a8_gemm_workspace_bytes(16, 5120, 5120) == w4a8.w4a8_gemm_workspace_bytes(16, 5120, 5120) > 0
+    assert w4a8.w4a8_gemm_workspace_bytes(0, 16, 32) == 0
+    assert w4a8.w4a8_gemm_workspace_bytes(1, 16, 48) == 0          # K % 32 != 0
+    assert w4a8.w4a8_gemm_workspace_bytes(1, 16, 65536 + 32) == 0  # beyond the int32-safe K
+
+
+def test_argument_validation_happens_before_any_launch(L):
+    # fake, aligned, non-NULL "device" addresses: validation must reject these calls without dereferencing anything
+    p = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    null = ctypes.c_void_p(0)
+    big = ctypes.c_size_t(1 << 40)
+    g = L.w4a8_gemm
+    assert g(null, p, p, p, p, 1, 16, 32, p, big, null) == -1
+    assert g(p, p, p, p, null, 1, 16, 32, p, big, null) == -1
+    assert g(p, p, p, p, p, 0, 16, 32, p, big, null) == -2
+    assert g(p, p, p, p, p, 1, 0, 32, p, big, null) == -2
+    assert g(p, p, p, p, p, 1, 16, 16, p, big, null) == -2
+    assert g(p, p, p, p, p, 1, 16, 48, p, big, null) == -2
+    assert g(p, p, p, p, p, 1, 16, 65536 + 32, p, big, null) == -2
+    assert g(odd, p, p, p, p, 1, 16, 32, p, big, null) == -3
+    assert g(p, p, odd, p, p, 1, 16, 32, p, big, null) == -3
+    # a forced split needs a workspace
+    t = L.w4a8_gemm_tuned
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 1, 2, null, 0, null) == -4
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 1, 2, p, 16, null) == -4
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 7, 0, p, big, null) == -7      # unknown tiling
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 1, 99, p, big, null) == -7     # split out of range
+    assert t(p, p, p, p, p, null, 65, 16, 1024, 1, 0, p, big, null) == -7     # decode tiling is for M <= 64
+    assert t(p, p, p, p, p, p, 1, 16, 1024, 0, 0, p, big, null) == -1         # both outputs given
+    assert t(p, p, p, p, null, null, 1, 16, 1024, 0, 0, p, big, null) == -1   # no output given
+    q = L.w4a8_quantize_act
+    assert q(null, p, p, 1, 32, null) == -1
+    assert q(p, p, p, 0, 32, null) == -2
+    assert q(p, p, p, 1, 40, null) == -2
+    assert q(odd, p, p, 1, 32, null) == -3
+    assert L.w4a8_quantize_weights(p, p, null, 4, 32, null) == -1
+    assert L.w4a8_quantize_weights(p, p, p, 4, 33, null) == -2
+    assert L.w4a8_silu_mul(p, null, 1, 8, null) == -1
+    assert L.w4a8_silu_mul(p, p, 1, 12, null) == -2
+
+
+def test_host_packing_matches_oracle_and_rejects_bad_codes(L, oracle):
+    _, wq, _, _ = synth.uniform_codes(2, 64, 96)
+    assert np.array_equal(w4a8.w4a8_pack_weights_host(wq), oracle.pack_w4(wq))
+    # all 256 nibble pairs
+    pairs = np.array([[a, c] for a in range(-8, 8) for c in range(-8, 8)], np.int8).reshape(1, -1)
+    assert np.array_equal(w4a8.w4a8_pack_weights_host(pairs), oracle.pack_w4(pairs))
+    # the paper's worked value: -7 is stored as nibble 1001
+    assert w4a8.w4a8_pack_weights_host(np.array([[-7, 0]], np.int8))[0, 0] == 0b1001
+    bad = wq.copy(); bad[3, 5] = 8
+    with pytest.raises(w4a8.W4A8Error) as e:
+        w4a8.w4a8_pack_weights_host(bad)
+    assert e.value.code == -6

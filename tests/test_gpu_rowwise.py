@@ -1,0 +1,98 @@
+"""GPU parity of the row-wise kernels (activation quantiser, weight quantiser +
+packer, SiLU*up glue) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import paper_2311_09550_amd as w4a8
+from paper_2311_09550_amd import synth
+
+from parity import assert_equal_bits, SUBNORMAL_STEP, FP16_MIN_NORMAL, REL_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _quant_act_gpu(torch, x):
+    xq, s_a = w4a8.w4a8_quantize_act(torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    return xq.cpu().numpy(), s_a.cpu().numpy()
+
+
+@pytest.mark.parametrize("M,K", [(1, 32), (3, 96), (1, 4096), (16, 5120), (5, 11008), (33, 13824), (2, 16384),
+                                 (2, 16416), (3, 28672), (1, 65536), (257, 1024)])
+def test_quantize_act_bit_exact(gpu, oracle, M, K):
+    x = synth.activations_fp16(M, K, tag=11)
+    xq, s_a = _quant_act_gpu(gpu, x)
+    xq_o, s_o = oracle.quantize_act(x)
+    assert_equal_bits(s_a.view(np.uint32), s_o.view(np.uint32), f"s_a M={M} K={K}")
+    assert_equal_bits(xq, xq_o, f"xq M={M} K={K}")
+
+
+def test_quantize_act_ties_zero_rows_and_scales(gpu, oracle):
+    K = 256
+    g = synth.rng(920)
+    x = (g.standard_normal((12, K)) * 3).astype(np.float16)
+    x[0, :] = 0                                       # all-zero token
+    x[1, :] = 0; x[1, 7] = np.float16(-3.0)           # single non-zero
+    x[2, :10] = np.array([127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5, 126.5, -126.5], np.float16)
+    x[2, 10:] = 0                                     # scale exactly 1: ties decide the codes
+    x[3, :] = np.float16(6e-8)                        # smallest subnormal everywhere
+    x[4, :] = np.float16(65504.0); x[4, 1] = np.float16(-65504.0)
+    x[5, :] *= np.float16(1e-3)
+    x[6, :] *= np.float16(300.0)
+    xq, s_a = _quant_act_gpu(gpu, x)
+    xq_o, s_o = oracle.quantize_act(x)
+    assert_equal_bits(s_a.view(np.uint32), s_o.view(np.uint32), "s_a")
+    assert_equal_bits(xq, xq_o, "xq")
+    assert list(xq[2, :10]) == [127, 0, 2, 2, 0, -2, -2, 4, 126, -126]
+    assert s_a[0] == 0 and not xq[0].any()
+
+
+def test_quantize_act_where_division_and_reciprocal_differ(gpu, oracle):
+    """Rows on which x * (1/s) would give another code than x / s (Eq. (2) divides)."""
+    g = synth.rng(904)
+    rows = []
+    for _ in range(400):
+        x = (g.standard_normal(256) * g.uniform(0.1, 30)).astype(np.float16)
+        xf = x.astype(np.float32)
+        s = np.float32(np.abs(xf).max() / np.float32(127.0))
+        if (np.rint(xf / s) != np.rint(xf * (np.float32(1.0) / s))).any():
+            rows.append(x)
+    assert len(rows) >= 3
+    x = np.stack(rows)
+    xq, s_a = _quant_act_gpu(gpu, x)
+    xq_o, s_o = oracle.quantize_act(x)
+    assert_equal_bits(s_a.view(np.uint32), s_o.view(np.uint32), "s_a")
+    assert_equal_bits(xq, xq_o, "xq")
+
+
+@pytest.mark.parametrize("N,K", [(1, 32), (7, 96), (64, 4096), (33, 5120), (4, 28672)])
+def test_quantize_weights_bit_exact(gpu, oracle, N, K):
+    w = synth.weights_fp16(N, K)
+    if N > 2:
+        w[1, :] = 0
+        w[2, 0] = np.float16(-1.0)
+    wp, s_w = w4a8.w4a8_quantize_weights(gpu.from_numpy(w).cuda())
+    gpu.cuda.synchronize()
+    wq_o, s_o = oracle.quantize_weights_rtn(w)
+    assert_equal_bits(s_w.cpu().numpy().view(np.uint32), s_o.view(np.uint32), "s_w")
+    assert_equal_bits(wp.cpu().numpy(), oracle.pack_w4(wq_o), "wp")
+
+
+@pytest.mark.parametrize("M,I", [(1, 8), (3, 104), (16, 13824), (130, 1024)])
+def test_silu_mul_close(gpu, oracle, M, I):
+    g = synth.rng(921, M, I)
+    gu = (g.standard_normal((M, 2 * I)) * 4).astype(np.float16)
+    gu[0, 0] = 0
+    gu[0, 1] = np.float16(-65504.0)
+    gu[0, 2] = np.float16(65504.0); gu[0, I + 2] = np.float16(1.0)
+    gu[0, 3] = np.float16(-20.0)
+    h = w4a8.w4a8_silu_mul(gpu.from_numpy(gu).cuda())
+    gpu.cuda.synchronize()
+    y64, _ = oracle.silu_mul(gu)
+    o = h.cpu().numpy().astype(np.float64)
+    finite = np.abs(y64) < 65520.0
+    assert np.all(np.isinf(o[~finite])) and np.all(np.isfinite(o[finite]))
+    err = np.abs(o - y64)
+    normal = finite & (np.abs(y64) >= FP16_MIN_NORMAL)
+    assert np.all(err[normal] <= REL_TOL * np.abs(y64[normal]))
+    assert np.all(err[finite & ~normal] <= SUBNORMAL_STEP)
