@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A8 linear path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: the
+linear stack of one LLaMA-13B-shaped decoder layer at M = 1024 tokens (the
+context-decoding case), i.e. four per-token activation quantisations, the four
+W4A8 GEMMs with fused dequantisation (QKV 15360x5120, O 5120x5120, gate+up
+27648x5120, down 5120x13824) and the SiLU*up glue in front of the down
+projection: nine kernel launches on one stream.  `value` is the integer GEMM
+work of a step (2*M*N*K summed over the four linears) divided by the step time.
+
+The same run also reports the decode side of the metric (M = 1, 4, 16 on the same
+four shapes, weights rotated through more than the last-level cache so every byte
+comes from HBM), a roofline object for the dominant kernel and the CPU oracle's
+throughput on a bounded sample of the workload.
+
+All inputs are seeded synthetic tensors generated on the host and resident in
+HBM before the timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak, published (5.0 POP/s)
+LAST_LEVEL_CACHE_BYTES = 256 << 20
+
+
+def gemm_bytes(M, N, K):
+    """Algorithmic HBM bytes of one W4A8 GEMM: packed weights + int8 activations + both scale vectors + fp16 output."""
+    return N * K // 2 + M * K + 4 * M + 4 * N + 2 * M * N
+
+
+def gemm_ops(M, N, K):
+    return 2 * M * N * K
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--M", type=int, default=1024, help="tokens per step (default: the 1024-token context)")
+    ap.add_argument("--no-decode", action="store_true", help="skip the M=1,4,16 weight-streaming measurements")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+class LayerStack:
+    """Device buffers of one 13B-shaped decoder layer's linears and the nine launches of a step."""
+
+    def __init__(self, torch, w4a8, synth, M, model="13b"):
+        self.torch, self.w4a8, self.M = torch, w4a8, M
+        self.shapes = synth.LLAMA_SHAPES[model]
+        dev = "cuda"
+        self.wp, self.s_w = {}, {}
+        for name, (N, K) in self.shapes.items():
+            w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).to(dev)
+            self.wp[name], self.s_w[name] = w4a8.w4a8_quantize_weights(w)   # offline weight preparation, on the GPU
+            del w
+        H = self.shapes["qkv"][1]
+        I = self.shapes["down"][1]
+        # fp16 inputs of the three linears that are fed from outside the stack (attention itself is not modelled)
+        self.h = torch.from_numpy(synth.activations_fp16(M, H, config_id=3, tag=1)).to(dev)
+        self.attn = torch.from_numpy(synth.activations_fp16(M, H, config_id=3, tag=2)).to(dev)
+        self.h2 = torch.from_numpy(synth.activations_fp16(M, H, config_id=3, tag=3)).to(dev)
+        e = lambda *s, dt: torch.empty(s, dtype=dt, device=dev)
+        self.xq_h, self.sa_h = e(M, H, dt=torch.int8), e(M, dt=torch.float32)
+        self.xq_i, self.sa_i = e(M, I, dt=torch.int8), e(M, dt=torch.float32)
+        self.out = {name: e(M, N, dt=torch.float16) for name, (N, K) in self.shapes.items()}
+        self.act = e(M, I, dt=torch.float16)
+        self.ws = w4a8.workspace(M, max(N for N, _ in self.shapes.values()), max(K for _, K in self.shapes.values()))
+        self.gemm_events = []   # (name, start, stop) around GEMM launches, filled when record=True
+
+    def _gemm(self, name, xq, sa, record):
+        t, w = self.torch, self.w4a8
+        if record:
+            a, b = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+            a.record()
+        w.w4a8_gemm(xq, sa, self.wp[name], self.s_w[name], out=self.out[name], ws=self.ws)
+        if record:
+            b.record()
+            self.gemm_events.append((name, a, b))
+
+    def step(self, record=False):
+        w = self.w4a8
+        w.w4a8_quantize_act(self.h, self.xq_h, self.sa_h)
+        self._gemm("qkv", self.xq_h, self.sa_h, record)
+        w.w4a8_quantize_act(self.attn, self.xq_h, self.sa_h)
+        self._gemm("o", self.xq_h, self.sa_h, record)
+        w.w4a8_quantize_act(self.h2, self.xq_h, self.sa_h)
+        self._gemm("gate_up", self.xq_h, self.sa_h, record)
+        w.w4a8_silu_mul(self.out["gate_up"], self.act)
+        w.w4a8_quantize_act(self.act, self.xq_i, self.sa_i)
+        self._gemm("down", self.xq_i, self.sa_i, record)
+
+    def ops_per_step(self):
+        return sum(gemm_ops(self.M, N, K) for N, K in self.shapes.values())
+
+
+def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=40):
+    """Weight-streaming GEMMs: every launch reads a different copy of the weights, the copies together
+    exceeding the last-level cache three times, so the weights come from HBM.  Per-launch time is the
+    average over a back-to-back batch between two events on the launch stream (dispatch gaps included)."""
+    rows = []
+    for name, (N, K) in synth.LLAMA_SHAPES[model].items():
+        w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).cuda()
+        wp, s_w = w4a8.w4a8_quantize_weights(w)
+        del w
+        wbytes = N * K // 2
+        copies = max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wbytes) + 1)
+        wps = [wp] + [wp.clone() for _ in range(copies - 1)]
+        for M in Ms:
+            x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
+            xq, s_a = w4a8.w4a8_quantize_act(x)
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            ws = w4a8.workspace(M, N, K)
+            for i in range(copies):
+                w4a8.w4a8_gemm(xq, s_a, wps[i], s_w, out=out, ws=ws)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n = iters * copies
+            a.record()
+            for i in range(n):
+                w4a8.w4a8_gemm(xq, s_a, wps[i % copies], s_w, out=out, ws=ws)
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / n
+            by = gemm_bytes(M, N, K)
+            rows.append({"linear": name, "M": M, "N": N, "K": K, "us": round(us, 3),
+                         "GBps": round(by / us / 1e3, 1), "hbm_frac": round(by / us / 1e3 / HBM_PEAK_GBS, 4),
+                         "weight_copies": copies})
+        del wps, wp
+        torch.cuda.empty_cache()
+    return rows
+
+
+def cpu_baseline(synth, M, target_seconds):
+    """The CPU oracle, as it stands, on the first rows of the same step (all four linears, complete N and K)."""
+    import numpy as np
+    import oracle
+    shapes = synth.LLAMA_SHAPES["13b"]
+    macs_per_row = sum(N * K for N, K in shapes.values())
+    # probe speed on 8 rows of the smallest linear, then size the sample
+    N, K = shapes["o"]
+    xq, wq, s_a, s_w = synth.uniform_codes(8, N, K, config_id=9)
+    wp = oracle.pack_w4(wq)
+    t0 = time.perf_counter()
+    oracle.gemm(xq, s_a, wp, s_w)
+    rate = 8 * N * K / (time.perf_counter() - t0)
+    rows = int(max(8, min(M, target_seconds * rate / macs_per_row)))
+    rows -= rows % 8
+    prepared = {}
+    for name, (N, K) in shapes.items():
+        wq, s_w = oracle.quantize_weights_rtn(synth.weights_fp16(N, K, config_id=3))
+        prepared[name] = (oracle.pack_w4(wq), s_w)
+    H = shapes["qkv"][1]
+    xs = [synth.activations_fp16(M, H, config_id=3, tag=t)[:rows] for t in (1, 2, 3)]
+    t0 = time.perf_counter()
+    out = None
+    for name, x in zip(("qkv", "o", "gate_up"), xs):
+        xq, s_a = oracle.quantize_act(x)
+        _, _, out = oracle.gemm(xq, s_a, *prepared[name])
+    _, act = oracle.silu_mul(out)
+    xq, s_a = oracle.quantize_act(act)
+    oracle.gemm(xq, s_a, *prepared["down"])
+    dt = time.perf_counter() - t0
+    ops = 2 * rows * macs_per_row
+    return {"value": round(ops / dt / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {rows} of {M} token rows through all four 13B linears (quantise, GEMM, epilogue, SiLU*up), "
+                      f"{dt:.1f} s of CPU time",
+            "seconds": round(dt, 2)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2311_09550_amd as w4a8
+    from paper_2311_09550_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: the W4A8 path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    w4a8.lib()
+    torch.cuda.set_device(0)
+    M = args.M
+    stack = LayerStack(torch, w4a8, synth, M)
+    for _ in range(args.warmup):
+        stack.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stack.step(record=True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tops = stack.ops_per_step() / (elapsed / args.steps) / 1e12
+
+    # dominant kernel: the LDS-staged GEMM; average launch duration over the timed region from events on its stream
+    per = {}
+    for name, a, b in stack.gemm_events:
+        per.setdefault(name, []).append(a.elapsed_time(b) * 1e3)
+    gemm_us = {k: sum(v) / len(v) for k, v in per.items()}
+    launches = sum(len(v) for v in per.values())
+    avg_us = sum(sum(v) for v in per.values()) / launches
+    ops_per_launch = stack.ops_per_step() / len(per)
+    achieved = ops_per_launch / avg_us / 1e6   # TOPS
+    roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": None,
+                "kernel": "gemm_prefill_kernel", "avg_launch_us": round(avg_us, 2),
+                "per_linear_us": {k: round(v, 2) for k, v in gemm_us.items()},
+                "per_linear_tops": {k: round(gemm_ops(M, *stack.shapes[k]) / v / 1e6, 1) for k, v in gemm_us.items()}}
+
+    result = {
+        "metric": "W4A8 GEMM TOPS + HBM GB/s vs roofline, LLaMA-13B shapes, M=1..1024",
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"LLaMA-13B-shaped decoder-layer linear stack (QKV, O, gate+up, down), M={M} tokens: "
+                               "4 per-token int8 quantisations + 4 W4A8 GEMMs with fused dequant + SiLU*up",
+                   "M": M, "linears": {k: list(v) for k, v in stack.shapes.items()}, "launches_per_step": 9},
+        "gemm_share_of_step": round(sum(gemm_us.values()) / (ms_per_step * 1e3), 4),
+        "roofline": roofline,
+    }
+    del stack
+    torch.cuda.empty_cache()
+    if not args.no_decode:
+        rows = time_decode(torch, w4a8, synth)
+        result["decode"] = rows
+        worst = min(rows, key=lambda r: r["hbm_frac"])
+        best = max(rows, key=lambda r: r["hbm_frac"])
+        mean_us = sum(r["us"] for r in rows) / len(rows)
+        mean_bytes = sum(gemm_bytes(r["M"], r["N"], r["K"]) for r in rows) / len(rows)
+        result["roofline_decode"] = {"bound": "hbm", "achieved": round(mean_bytes / mean_us / 1e3, 1), "peak": HBM_PEAK_GBS,
+                                     "unit": "GB/s", "frac": round(mean_bytes / mean_us / 1e3 / HBM_PEAK_GBS, 4),
+                                     "traffic": None, "kernel": "gemm_decode_kernel",
+                                     "worst": worst, "best": best}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(synth, M, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -40,10 +40,10 @@ extern "C" {
 #define W4A8_ERR_NULL (-1)      /* a required pointer is NULL                          */
 #define W4A8_ERR_SHAPE (-2)     /* M, N, K outside the shape contract above            */
 #define W4A8_ERR_ALIGN (-3)     /* a device pointer is not 16-byte aligned             */
-#define W4A8_ERR_WORKSPACE (-4) /* workspace missing or smaller than required          */
+#define W4A8_ERR_WORKSPACE (-4) /* workspace smaller than w4a8_gemm_workspace_bytes()  */
 #define W4A8_ERR_LAUNCH (-5)    /* the HIP runtime rejected the launch                 */
 #define W4A8_ERR_VALUE (-6)     /* host helper: a weight code outside [-8, 7]          */
-#define W4A8_ERR_ARG (-7)       /* an option (tiling id, split count) is out of range  */
+#define W4A8_ERR_ARG (-7)       /* tiling id or variant not available for the shape    */
 
 #define W4A8_MAX_K 65536
 
@@ -67,12 +67,13 @@ const char *w4a8_strerror(int err);
 int w4a8_quantize_act(const void *x_fp16, int8_t *xq, float *s_a, int M, int K, void *stream);
 
 /*
- * Bytes of workspace w4a8_gemm / w4a8_gemm_acc_i32 need for this shape (a pure
- * function of the shape, 0 for an invalid one).  The workspace holds split-K
- * partial sums and per-tile arrival counters.  It must be zero-filled once
- * before its first use; every call leaves the counters at zero again, so the
- * same buffer can be reused by later calls ON THE SAME STREAM.  Calls that may
- * overlap in time (different streams) need different workspaces.
+ * Bytes of scratch memory w4a8_gemm / w4a8_gemm_acc_i32 / w4a8_gemm_tuned need
+ * for this shape: a pure function of the shape.  The present tilings combine
+ * their partial sums in LDS and need none, so this returns 0 and the
+ * `workspace` argument of the calls below may be NULL; callers that size and
+ * pass a buffer from this function stay correct if a later tiling needs one.
+ * A workspace, when one is required, must not be shared by calls that may
+ * overlap in time (different streams).
  */
 size_t w4a8_gemm_workspace_bytes(int M, int N, int K);
 
@@ -105,17 +106,23 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
 /*
  * As the two calls above, with the tiling forced instead of chosen from the
  * shape.  For tuning sweeps and for tests that must cover every tiling at
- * every shape.  `tiling` is one of W4A8_TILING_*; `split_k` >= 1 is the number
- * of K slices whose partial sums are combined through the workspace (0 = let
- * the library choose).  Exactly one of out_fp16 / acc_i32 must be non-NULL
- * (s_a and s_w may be NULL when acc_i32 is requested).
+ * every shape.  `tiling` is one of W4A8_TILING_*.  `variant` refines it
+ * (0 = library default, W4A8_ERR_ARG if not available for the shape):
+ *   DECODE_RESIDENT: waves * 100000 + workgroups, waves in {8, 16} (0 = default),
+ *                    workgroups = size of the persistent grid (0 = default);
+ *   DECODE_STREAM:   row_tiles * 100 + waves, row_tiles in {1, 2}, waves in {4, 8};
+ *   PREFILL:         must be 0.
+ * Exactly one of out_fp16 / acc_i32 must be non-NULL (s_a and s_w may be NULL
+ * when acc_i32 is requested).
  */
 #define W4A8_TILING_AUTO 0
-#define W4A8_TILING_DECODE 1  /* weight-streaming tiling for small M (M <= 64)        */
-#define W4A8_TILING_PREFILL 2 /* LDS-staged 128 x 256 tiling for large M              */
+#define W4A8_TILING_DECODE_RESIDENT 1 /* persistent weight-streaming kernel, activations kept in registers:
+                                         M <= 16 with K <= 16384, or M <= 32 with K <= 8192              */
+#define W4A8_TILING_DECODE_STREAM 2   /* general weight-streaming kernel, M <= 64                         */
+#define W4A8_TILING_PREFILL 3         /* LDS-staged 128 x 256 output tiles for large M                    */
 int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w,
                     void *out_fp16, int32_t *acc_i32, int M, int N, int K,
-                    int tiling, int split_k,
+                    int tiling, int variant,
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*

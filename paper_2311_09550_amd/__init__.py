@@ -14,7 +14,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw4a8.so")
 
-TILING_AUTO, TILING_DECODE, TILING_PREFILL = 0, 1, 2
+TILING_AUTO, TILING_DECODE_RESIDENT, TILING_DECODE_STREAM, TILING_PREFILL = 0, 1, 2, 3
 
 _lib = None
 
@@ -147,8 +147,8 @@ def w4a8_gemm_acc_i32(xq, wp, acc=None, ws=None):
     return acc
 
 
-def w4a8_gemm_tuned(xq, s_a, wp, s_w, tiling: int, split_k: int = 0, want_acc: bool = False, out=None, ws=None):
-    """Forced tiling / split count; returns fp16 [M][N], or int32 [M][N] when want_acc."""
+def w4a8_gemm_tuned(xq, s_a, wp, s_w, tiling: int, variant: int = 0, want_acc: bool = False, out=None, ws=None):
+    """Forced tiling / variant; returns fp16 [M][N], or int32 [M][N] when want_acc."""
     torch = _torch()
     M, K = xq.shape
     N = wp.shape[0]
@@ -167,7 +167,7 @@ def w4a8_gemm_tuned(xq, s_a, wp, s_w, tiling: int, split_k: int = 0, want_acc: b
     if out.shape != (M, N):
         raise ValueError("out shape mismatch")
     _check(lib().w4a8_gemm_tuned(_dev(xq, torch.int8, "xq"), sa, _dev(wp, torch.uint8, "wp"), sw, o16, o32, M, N, K,
-                                 tiling, split_k, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
+                                 tiling, variant, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
     return out
 
 

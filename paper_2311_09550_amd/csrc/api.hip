@@ -10,12 +10,7 @@ namespace {
 
 using namespace w4a8;
 
-constexpr int kMaxSplits = 8;
 constexpr int kDecodeMaxM = 64;
-// Arrival counters live in a region of fixed size at the start of the workspace, so that the partial sums
-// of one shape can never land on the counters of another shape sharing the same buffer.
-constexpr size_t kCounterRegion = 65536;
-constexpr int kMaxCounters = (int)(kCounterRegion / sizeof(int));
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -24,80 +19,101 @@ inline int check_gemm_shape(int M, int N, int K) {
     return W4A8_OK;
 }
 
+// Compute units of the current device (256 on MI355X); queried once.
+int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
 struct Plan {
     int tiling;
-    int splits;
     DecodeShape decode;
 };
 
-// Tiling choice.  Small M streams the weights once (HBM bound): pick the row
-// tile count and K split so that the launch has a few workgroups per compute
-// unit, each with enough bytes to keep loads in flight.  Large M goes to the
-// LDS-staged tiling (matrix-core bound).
-Plan choose_plan(int M, int N, int K, int tiling, int split_k) {
-    Plan pl{};
-    pl.tiling = tiling;
-    if (tiling == W4A8_TILING_AUTO) pl.tiling = M <= kDecodeMaxM ? W4A8_TILING_DECODE : W4A8_TILING_PREFILL;
-    pl.splits = 1;
-    if (pl.tiling == W4A8_TILING_DECODE) {
-        const int mt = (M + 15) / 16;
-        pl.decode.row_tiles = M <= 8 ? 1 : 2;
-        pl.decode.waves = (mt >= 4 && pl.decode.row_tiles == 2) ? 4 : 8;
-        const int row_blocks = (N + 16 * pl.decode.row_tiles - 1) / (16 * pl.decode.row_tiles);
-        const int ks_total = (K + 127) / 128;
-        int s = 1;
-        if (split_k > 0) {
-            s = split_k;
-        } else {
-            const int target = 768;  // about three workgroups per compute unit
-            s = (target + row_blocks - 1) / row_blocks;
-            // keep at least two k steps per wave in a slice
-            const int max_by_k = ks_total / (2 * pl.decode.waves);
-            if (s > max_by_k) s = max_by_k;
-        }
-        if (s > kMaxSplits) s = kMaxSplits;
-        if (s > ks_total) s = ks_total;
-        if (row_blocks > kMaxCounters) s = 1;  // more row blocks than counters: such a launch needs no split
-        if (s < 1) s = 1;
-        pl.splits = s;
+// Shape of the persistent decode kernel for (M, K): 8 waves while a wave's k steps stay few (fewer
+// registers per wave, two workgroups per compute unit), else 16 waves.  Returns false when the
+// activations of a wave would not fit in registers.
+bool resident_shape(int M, int N, int K, int waves, int grid, DecodeShape *out) {
+    const int ks_total = (K + 127) / 128;
+    DecodeShape s{};
+    s.resident = true;
+    if (waves == 0) waves = (M <= 16 && ks_total <= 40) ? 8 : 16;
+    s.waves = waves;
+    s.x_steps = (ks_total + waves - 1) / waves;
+    // as many workgroups as fit on the chip at once, each with the same share of the output channels
+    if (grid <= 0) grid = compute_units();  // measured: one workgroup per compute unit streams fastest
+    int rows = ((N + grid - 1) / grid + 3) & ~3;
+    if (rows < 4) rows = 4;
+    s.rows_per_wg = rows;
+    if (!decode_resident_supported(M, N, K, s)) return false;
+    *out = s;
+    return true;
+}
+
+// Tiling choice.  Small M streams the weights once (HBM bound); large M goes to the LDS-staged tiling
+// (matrix-core bound).  `variant` refines a forced tiling (see w4a8.h); 0 lets the library choose.
+int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
+    pl->tiling = tiling;
+    if (tiling == W4A8_TILING_AUTO) {
+        if (M > kDecodeMaxM)
+            pl->tiling = W4A8_TILING_PREFILL;
+        else
+            pl->tiling = resident_shape(M, N, K, 0, 0, &pl->decode) ? W4A8_TILING_DECODE_RESIDENT : W4A8_TILING_DECODE_STREAM;
     }
-    return pl;
+    if (pl->tiling == W4A8_TILING_DECODE_RESIDENT) {
+        if (M > kDecodeMaxM) return W4A8_ERR_ARG;
+        if (!resident_shape(M, N, K, variant / 100000, variant % 100000, &pl->decode)) return W4A8_ERR_ARG;
+    } else if (pl->tiling == W4A8_TILING_DECODE_STREAM) {
+        if (M > kDecodeMaxM) return W4A8_ERR_ARG;
+        const int mt = (M + 15) / 16;
+        DecodeShape s{};
+        s.resident = false;
+        s.row_tiles = variant ? variant / 100 : (M <= 8 ? 1 : 2);
+        s.waves = variant ? variant % 100 : ((mt >= 4 && s.row_tiles == 2) ? 4 : 8);
+        if ((s.row_tiles != 1 && s.row_tiles != 2) || (s.waves != 4 && s.waves != 8)) return W4A8_ERR_ARG;
+        if (mt == 4 && s.row_tiles == 2 && s.waves == 8) return W4A8_ERR_ARG;  // would not fit in LDS
+        pl->decode = s;
+    } else if (variant != 0) {
+        return W4A8_ERR_ARG;
+    }
+    return W4A8_OK;
 }
 
 int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w, void *out_fp16, int32_t *acc_i32,
-             int M, int N, int K, int tiling, int split_k, void *workspace, size_t workspace_bytes, void *stream) {
+             int M, int N, int K, int tiling, int variant, void *stream) {
     const bool want_acc = acc_i32 != nullptr;
     if ((out_fp16 != nullptr) == want_acc) return W4A8_ERR_NULL;  // exactly one output
     if (!xq || !wp) return W4A8_ERR_NULL;
     if (!want_acc && (!s_a || !s_w)) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, N, K)) return e;
-    if (tiling < W4A8_TILING_AUTO || tiling > W4A8_TILING_PREFILL) return W4A8_ERR_ARG;
-    if (split_k < 0 || split_k > kMaxSplits) return W4A8_ERR_ARG;
-    if (tiling == W4A8_TILING_DECODE && M > kDecodeMaxM) return W4A8_ERR_ARG;
-    if (misaligned(xq) || misaligned(wp) || misaligned(out_fp16) || misaligned(acc_i32) || misaligned(workspace) ||
-        (s_w && misaligned(s_w)))
+    if (tiling < W4A8_TILING_AUTO || tiling > W4A8_TILING_PREFILL || variant < 0) return W4A8_ERR_ARG;
+    if (misaligned(xq) || misaligned(wp) || misaligned(out_fp16) || misaligned(acc_i32) || (s_w && misaligned(s_w)))
         return W4A8_ERR_ALIGN;
 
-    const Plan pl = choose_plan(M, N, K, tiling, split_k);
+    Plan pl{};
+    if (int e = choose_plan(M, N, K, tiling, variant, &pl)) return e;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t err;
-    if (pl.tiling == W4A8_TILING_DECODE) {
+    if (pl.tiling != W4A8_TILING_PREFILL) {
         DecodeArgs a{};
         a.xq = xq; a.s_a = s_a; a.wp = wp; a.s_w = s_w;
         a.out = out_fp16; a.acc_out = acc_i32;
-        a.M = M; a.N = N; a.K = K; a.splits = pl.splits;
-        if (pl.splits > 1) {
-            const size_t need = kCounterRegion + (size_t)pl.splits * M * N * sizeof(int);
-            if (!workspace || workspace_bytes < need) return W4A8_ERR_WORKSPACE;
-            a.counters = static_cast<int *>(workspace);
-            a.partials = reinterpret_cast<int *>(static_cast<char *>(workspace) + kCounterRegion);
-        }
+        a.M = M; a.N = N; a.K = K;
+        a.rows_per_wg = pl.decode.rows_per_wg;
         err = launch_gemm_decode(a, want_acc, pl.decode, st);
     } else {
         PrefillArgs a{};
         a.xq = xq; a.s_a = s_a; a.wp = wp; a.s_w = s_w;
         a.out = out_fp16; a.acc_out = acc_i32;
-        a.M = M; a.N = N; a.K = K; a.splits = 1;
+        a.M = M; a.N = N; a.K = K;
         a.tiles_m = (M + kPrefillBM - 1) / kPrefillBM;
         a.tiles_n = (N + kPrefillBN - 1) / kPrefillBN;
         err = launch_gemm_prefill(a, want_acc, st);
@@ -117,10 +133,10 @@ const char *w4a8_strerror(int err) {
         case W4A8_ERR_NULL: return "a required pointer is NULL (or both / neither output given)";
         case W4A8_ERR_SHAPE: return "shape outside the contract: M,N >= 1, 32 <= K <= 65536, K % 32 == 0";
         case W4A8_ERR_ALIGN: return "device pointer not 16-byte aligned";
-        case W4A8_ERR_WORKSPACE: return "workspace missing or too small (see w4a8_gemm_workspace_bytes)";
+        case W4A8_ERR_WORKSPACE: return "workspace smaller than w4a8_gemm_workspace_bytes reports";
         case W4A8_ERR_LAUNCH: return "HIP rejected the kernel launch";
         case W4A8_ERR_VALUE: return "weight code outside [-8, 7]";
-        case W4A8_ERR_ARG: return "tiling id or split count out of range for this shape";
+        case W4A8_ERR_ARG: return "tiling id or variant not available for this shape";
         default: return "unknown w4a8 error code";
     }
 }
@@ -134,27 +150,29 @@ int w4a8_quantize_act(const void *x_fp16, int8_t *xq, float *s_a, int M, int K, 
 }
 
 size_t w4a8_gemm_workspace_bytes(int M, int N, int K) {
-    if (check_gemm_shape(M, N, K) != W4A8_OK) return 0;
-    if (M > kDecodeMaxM) return 0;
-    return kCounterRegion + (size_t)kMaxSplits * M * N * sizeof(int);
+    (void)M; (void)N; (void)K;
+    return 0;  // no tiling needs scratch memory: partial sums meet in LDS
 }
 
 int w4a8_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w, void *out_fp16, int M, int N, int K,
               void *workspace, size_t workspace_bytes, void *stream) {
+    (void)workspace; (void)workspace_bytes;
     if (!out_fp16) return W4A8_ERR_NULL;
-    return run_gemm(xq, s_a, wp, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_AUTO, 0, workspace, workspace_bytes, stream);
+    return run_gemm(xq, s_a, wp, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_AUTO, 0, stream);
 }
 
 int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, int N, int K, void *workspace,
                       size_t workspace_bytes, void *stream) {
+    (void)workspace; (void)workspace_bytes;
     if (!acc) return W4A8_ERR_NULL;
-    return run_gemm(xq, nullptr, wp, nullptr, nullptr, acc, M, N, K, W4A8_TILING_AUTO, 0, workspace, workspace_bytes, stream);
+    return run_gemm(xq, nullptr, wp, nullptr, nullptr, acc, M, N, K, W4A8_TILING_AUTO, 0, stream);
 }
 
 int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w, void *out_fp16,
-                    int32_t *acc_i32, int M, int N, int K, int tiling, int split_k, void *workspace, size_t workspace_bytes,
+                    int32_t *acc_i32, int M, int N, int K, int tiling, int variant, void *workspace, size_t workspace_bytes,
                     void *stream) {
-    return run_gemm(xq, s_a, wp, s_w, out_fp16, acc_i32, M, N, K, tiling, split_k, workspace, workspace_bytes, stream);
+    (void)workspace; (void)workspace_bytes;
+    return run_gemm(xq, s_a, wp, s_w, out_fp16, acc_i32, M, N, K, tiling, variant, stream);
 }
 
 int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, int K, void *stream) {

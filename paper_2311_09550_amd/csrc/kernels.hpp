@@ -13,17 +13,21 @@ struct DecodeArgs {
     const float *s_w;    // [N]
     void *out;           // fp16 [M][N]
     int *acc_out;        // int32 [M][N]
-    int *counters;       // one arrival counter per row block (split-K only)
-    int *partials;       // [splits][M][N] sixteen-fold partial sums (split-K only)
     int M, N, K;
-    int splits;
+    int rows_per_wg;     // resident kernel: output channels per workgroup (multiple of 4)
 };
+
+constexpr int kResidentMaxRows = 4096;  // channels per workgroup whose scales fit the resident kernel's LDS staging
 
 struct DecodeShape {
-    int row_tiles;  // 16-row weight tiles per wave: 1, 2 or 4
-    int waves;      // waves per workgroup: 4 or 8
+    bool resident;  // persistent kernel with register-resident activations, else the general streaming kernel
+    int waves;      // waves per workgroup: resident 8 or 16, streaming 4 or 8
+    int x_steps;    // resident: k steps per wave = ceil(ceil(K/128) / waves)
+    int rows_per_wg;  // resident: output channels per persistent workgroup, a multiple of 4
+    int row_tiles;  // streaming: 16-row weight tiles per wave, 1 or 2
 };
 
+bool decode_resident_supported(int M, int N, int K, const DecodeShape &s);
 hipError_t launch_gemm_decode(const DecodeArgs &p, bool acc_out, const DecodeShape &s, hipStream_t stream);
 
 struct PrefillArgs {
@@ -33,10 +37,7 @@ struct PrefillArgs {
     const float *s_w;
     void *out;
     int *acc_out;
-    int *counters;   // one arrival counter per output tile (split-K only)
-    int *partials;   // [splits][tiles][128*256] sixteen-fold partial sums (split-K only)
     int M, N, K;
-    int splits;
     int tiles_m, tiles_n;
 };
 

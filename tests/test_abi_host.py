@@ -48,10 +48,9 @@ def test_version_and_strerror(L):
 
 
 def test_workspace_bytes_is_a_pure_function_of_shape(L):
-    assert w4a8.w4a8_gemm_workspace_bytes(16, 5120, 5120) == w4a8.w4a8_gemm_workspace_bytes(16, 5120, 5120) > 0
-    assert w4a8.w4a8_gemm_workspace_bytes(0, 16, 32) == 0
-    assert w4a8.w4a8_gemm_workspace_bytes(1, 16, 48) == 0          # K % 32 != 0
-    assert w4a8.w4a8_gemm_workspace_bytes(1, 16, 65536 + 32) == 0  # beyond the int32-safe K
+    # partial sums meet in LDS: no tiling needs scratch memory, for valid and invalid shapes alike
+    for shape in [(16, 5120, 5120), (1024, 27648, 5120), (0, 16, 32), (1, 16, 48)]:
+        assert w4a8.w4a8_gemm_workspace_bytes(*shape) == w4a8.w4a8_gemm_workspace_bytes(*shape) == 0
 
 
 def test_argument_validation_happens_before_any_launch(L):
@@ -70,13 +69,14 @@ def test_argument_validation_happens_before_any_launch(L):
     assert g(p, p, p, p, p, 1, 16, 65536 + 32, p, big, null) == -2
     assert g(odd, p, p, p, p, 1, 16, 32, p, big, null) == -3
     assert g(p, p, odd, p, p, 1, 16, 32, p, big, null) == -3
-    # a forced split needs a workspace
     t = L.w4a8_gemm_tuned
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 1, 2, null, 0, null) == -4
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 1, 2, p, 16, null) == -4
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 7, 0, p, big, null) == -7      # unknown tiling
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 1, 99, p, big, null) == -7     # split out of range
-    assert t(p, p, p, p, p, null, 65, 16, 1024, 1, 0, p, big, null) == -7     # decode tiling is for M <= 64
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 7, 0, p, big, null) == -7       # unknown tiling
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 2, 303, p, big, null) == -7     # stream: 3 row tiles / 3 waves do not exist
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 3, 5, p, big, null) == -7       # prefill has no variants
+    assert t(p, p, p, p, p, null, 65, 16, 1024, 2, 0, p, big, null) == -7      # decode tilings are for M <= 64
+    assert t(p, p, p, p, p, null, 65, 16, 1024, 1, 0, p, big, null) == -7
+    assert t(p, p, p, p, p, null, 16, 16, 32768, 1, 0, p, big, null) == -7     # resident: activations would not fit in registers
+    assert t(p, p, p, p, p, null, 48, 16, 1024, 1, 0, p, big, null) == -7      # resident: M <= 32 only
     assert t(p, p, p, p, p, p, 1, 16, 1024, 0, 0, p, big, null) == -1         # both outputs given
     assert t(p, p, p, p, null, null, 1, 16, 1024, 0, 0, p, big, null) == -1   # no output given
     q = L.w4a8_quantize_act

@@ -11,7 +11,7 @@ from parity import assert_equal_bits, assert_fp16_close
 
 pytestmark = pytest.mark.gpu
 
-DECODE, PREFILL = w4a8.TILING_DECODE, w4a8.TILING_PREFILL
+RESIDENT, STREAM, PREFILL = w4a8.TILING_DECODE_RESIDENT, w4a8.TILING_DECODE_STREAM, w4a8.TILING_PREFILL
 
 
 def _codes(M, N, K, tag=1):
@@ -19,14 +19,14 @@ def _codes(M, N, K, tag=1):
     return xq, wq, s_a, s_w
 
 
-def _run_both(torch, oracle, xq, wq, s_a, s_w, tiling, split_k, what):
+def _run_both(torch, oracle, xq, wq, s_a, s_w, tiling, variant, what):
     """Run the forced tiling on the GPU (raw sums and fp16 output) and compare with the oracle."""
     wp = oracle.pack_w4(wq)
     acc_o, y32, _ = oracle.gemm(xq, s_a, wp, s_w)
     d = dict(xq=torch.from_numpy(xq).cuda(), s_a=torch.from_numpy(s_a).cuda(),
              wp=torch.from_numpy(wp).cuda(), s_w=torch.from_numpy(s_w).cuda())
-    acc = w4a8.w4a8_gemm_tuned(d["xq"], None, d["wp"], None, tiling, split_k, want_acc=True)
-    out = w4a8.w4a8_gemm_tuned(d["xq"], d["s_a"], d["wp"], d["s_w"], tiling, split_k)
+    acc = w4a8.w4a8_gemm_tuned(d["xq"], None, d["wp"], None, tiling, variant, want_acc=True)
+    out = w4a8.w4a8_gemm_tuned(d["xq"], d["s_a"], d["wp"], d["s_w"], tiling, variant)
     torch.cuda.synchronize()
     assert_equal_bits(acc.cpu().numpy(), acc_o, what + " acc")
     assert_fp16_close(out.cpu().numpy(), y32, acc_o, what + " out")
@@ -51,39 +51,71 @@ def test_config1_full_parity(gpu, oracle):
 
 
 @pytest.mark.parametrize("M", [1, 2, 3, 5, 7, 8, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64])
-def test_decode_tiling_all_m(gpu, oracle, M):
+def test_stream_tiling_all_m(gpu, oracle, M):
     xq, wq, s_a, s_w = _codes(M, 200, 1056, tag=30)
-    _run_both(gpu, oracle, xq, wq, s_a, s_w, DECODE, 0, f"decode M={M}")
+    _run_both(gpu, oracle, xq, wq, s_a, s_w, STREAM, 0, f"stream M={M}")
+
+
+@pytest.mark.parametrize("variant", [104, 108, 204, 208])
+@pytest.mark.parametrize("M", [3, 16, 40, 64])
+def test_stream_tiling_variants(gpu, oracle, M, variant):
+    if M > 48 and variant == 208:
+        pytest.skip("4 column tiles x 2 row tiles x 8 waves exceeds LDS; the library rejects it")
+    xq, wq, s_a, s_w = _codes(M, 328, 2080, tag=34)
+    _run_both(gpu, oracle, xq, wq, s_a, s_w, STREAM, variant, f"stream variant={variant} M={M}")
 
 
 @pytest.mark.parametrize("N,K", [(1, 32), (16, 32), (17, 64), (24, 96), (1000, 128), (1001, 160), (30, 4128),
-                                 (4096, 1024), (520, 11008)])
+                                 (4096, 1024), (520, 11008), (40, 28672)])
 @pytest.mark.parametrize("M", [1, 16, 37])
-def test_decode_tiling_ragged_shapes(gpu, oracle, M, N, K):
+def test_stream_tiling_ragged_shapes(gpu, oracle, M, N, K):
     xq, wq, s_a, s_w = _codes(M, N, K, tag=31)
-    _run_both(gpu, oracle, xq, wq, s_a, s_w, DECODE, 0, f"decode M={M} N={N} K={K}")
+    _run_both(gpu, oracle, xq, wq, s_a, s_w, STREAM, 0, f"stream M={M} N={N} K={K}")
 
 
-@pytest.mark.parametrize("split_k", [1, 2, 3, 5, 8])
-@pytest.mark.parametrize("M,N,K", [(1, 256, 4096), (16, 1000, 2080), (33, 130, 5120), (4, 64, 128)])
-def test_decode_split_k(gpu, oracle, M, N, K, split_k):
-    xq, wq, s_a, s_w = _codes(M, N, K, tag=32)
-    _run_both(gpu, oracle, xq, wq, s_a, s_w, DECODE, split_k, f"decode split={split_k} M={M} N={N} K={K}")
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 7, 8, 15, 16])
+@pytest.mark.parametrize("N,K", [(1, 32), (16, 32), (17, 64), (24, 96), (1000, 128), (1001, 160), (30, 4128), (4096, 1024),
+                                 (8200, 2048), (520, 5120), (300, 11008), (520, 13824), (40, 16384)])
+def test_resident_tiling_m_up_to_16(gpu, oracle, M, N, K):
+    xq, wq, s_a, s_w = _codes(M, N, K, tag=35)
+    _run_both(gpu, oracle, xq, wq, s_a, s_w, RESIDENT, 0, f"resident M={M} N={N} K={K}")
 
 
-def test_decode_workspace_is_left_reusable(gpu, oracle):
-    """Arrival counters return to zero: the same workspace serves call after call, sizes varying."""
+@pytest.mark.parametrize("M", [17, 24, 31, 32])
+@pytest.mark.parametrize("N,K", [(16, 32), (1001, 160), (520, 5120), (700, 8192), (30, 4128)])
+def test_resident_tiling_m_up_to_32(gpu, oracle, M, N, K):
+    xq, wq, s_a, s_w = _codes(M, N, K, tag=36)
+    _run_both(gpu, oracle, xq, wq, s_a, s_w, RESIDENT, 0, f"resident M={M} N={N} K={K}")
+
+
+@pytest.mark.parametrize("waves,grid", [(8, 1), (8, 7), (8, 512), (16, 1), (16, 3), (16, 100), (16, 256), (16, 4096)])
+@pytest.mark.parametrize("M,N,K", [(1, 5120, 512), (16, 1000, 2080), (9, 130, 5120)])
+def test_resident_tiling_grid_and_wave_variants(gpu, oracle, M, N, K, waves, grid):
+    """Any persistent grid size gives the same bits: few workgroups walk many row blocks each, many walk one."""
+    xq, wq, s_a, s_w = _codes(M, N, K, tag=37)
+    if -(-N // grid) > 4096:
+        # more than 4096 output channels per workgroup are refused (their scales are staged in LDS)
+        with pytest.raises(w4a8.W4A8Error) as e:
+            w4a8.w4a8_gemm_tuned(gpu.from_numpy(xq).cuda(), None, gpu.from_numpy(oracle.pack_w4(wq)).cuda(), None,
+                                 RESIDENT, waves * 100000 + grid, want_acc=True)
+        assert e.value.code == -7
+        return
+    _run_both(gpu, oracle, xq, wq, s_a, s_w, RESIDENT, waves * 100000 + grid, f"resident {waves}w grid={grid} M={M} N={N} K={K}")
+
+
+def test_back_to_back_calls_share_nothing(gpu, oracle):
+    """Calls of different shapes in a row on one stream, no synchronisation in between."""
     t = gpu
-    ws = t.zeros(w4a8.w4a8_gemm_workspace_bytes(16, 1024, 4096), dtype=t.uint8, device="cuda")
-    for i, (M, N, K, split) in enumerate([(16, 1024, 4096, 4), (3, 520, 2048, 8), (1, 48, 512, 3), (16, 1024, 4096, 2), (2, 4096, 1024, 2)]):
+    jobs = []
+    for i, (M, N, K) in enumerate([(16, 1024, 4096), (3, 520, 2048), (1, 48, 512), (16, 1024, 4096), (40, 4096, 1024),
+                                   (200, 300, 1024)]):
         xq, wq, s_a, s_w = _codes(M, N, K, tag=33 + i)
         wp = oracle.pack_w4(wq)
-        acc_o = oracle.gemm_acc_i32(xq, wp)
-        acc = w4a8.w4a8_gemm_tuned(t.from_numpy(xq).cuda(), None, t.from_numpy(wp).cuda(), None, DECODE, split,
-                                   want_acc=True, ws=ws)
-        t.cuda.synchronize()
-        assert_equal_bits(acc.cpu().numpy(), acc_o, f"call {i}")
-    assert not ws[:65536].any().item()   # the counter region at the start of the workspace
+        jobs.append((t.from_numpy(xq).cuda(), t.from_numpy(wp).cuda(), oracle.gemm_acc_i32(xq, wp)))
+    accs = [w4a8.w4a8_gemm_acc_i32(dx, dw) for dx, dw, _ in jobs for _ in range(2)]
+    t.cuda.synchronize()
+    for i, acc in enumerate(accs):
+        assert_equal_bits(acc.cpu().numpy(), jobs[i // 2][2], f"call {i}")
 
 
 @pytest.mark.parametrize("M", [1, 17, 64, 65, 127, 128, 129, 300])
@@ -99,7 +131,7 @@ def test_prefill_tiling_ragged_shapes(gpu, oracle, M, N, K):
     _run_both(gpu, oracle, xq, wq, s_a, s_w, PREFILL, 0, f"prefill M={M} N={N} K={K}")
 
 
-@pytest.mark.parametrize("tiling,M", [(DECODE, 2), (DECODE, 40), (PREFILL, 130)])
+@pytest.mark.parametrize("tiling,M", [(STREAM, 2), (STREAM, 40), (PREFILL, 130)])
 def test_extreme_codes_at_max_k_do_not_overflow(gpu, oracle, tiling, M):
     """a = -128, w = -8 along all of K = 65536: the sixteen-fold sum is 2^30, inside int32 (Sec. 5.3)."""
     K, N = 65536, 48
