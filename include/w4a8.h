@@ -111,7 +111,8 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
  *   DECODE_RESIDENT: waves * 100000 + workgroups, waves in {8, 16} (0 = default),
  *                    workgroups = size of the persistent grid (0 = default);
  *   DECODE_STREAM:   row_tiles * 100 + waves, row_tiles in {1, 2}, waves in {4, 8};
- *   PREFILL:         must be 0.
+ *   PREFILL:         output tile (rows of X x channels): 1 = 128 x 256 as 1 x 4 waves, 2 = 128 x 128,
+ *                    3 = 128 x 160, 4 = 128 x 256 as 2 x 2 waves.
  * Exactly one of out_fp16 / acc_i32 must be non-NULL (s_a and s_w may be NULL
  * when acc_i32 is requested).
  */
@@ -119,7 +120,7 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
 #define W4A8_TILING_DECODE_RESIDENT 1 /* persistent weight-streaming kernel, activations kept in registers:
                                          M <= 16 with K <= 16384, or M <= 32 with K <= 8192              */
 #define W4A8_TILING_DECODE_STREAM 2   /* general weight-streaming kernel, M <= 64                         */
-#define W4A8_TILING_PREFILL 3         /* LDS-staged 128 x 256 output tiles for large M                    */
+#define W4A8_TILING_PREFILL 3         /* LDS-staged output tiles on 32x32x32 int8 MFMA, for large M       */
 int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w,
                     void *out_fp16, int32_t *acc_i32, int M, int N, int K,
                     int tiling, int variant,

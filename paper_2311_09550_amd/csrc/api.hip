@@ -36,6 +36,7 @@ int compute_units() {
 struct Plan {
     int tiling;
     DecodeShape decode;
+    int prefill_tile;
 };
 
 // Shape of the persistent decode kernel for (M, K): 8 waves while a wave's k steps stay few (fewer
@@ -81,8 +82,9 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
         if ((s.row_tiles != 1 && s.row_tiles != 2) || (s.waves != 4 && s.waves != 8)) return W4A8_ERR_ARG;
         if (mt == 4 && s.row_tiles == 2 && s.waves == 8) return W4A8_ERR_ARG;  // would not fit in LDS
         pl->decode = s;
-    } else if (variant != 0) {
-        return W4A8_ERR_ARG;
+    } else {
+        if (variant < 0 || variant > kPrefillTile128x256Square) return W4A8_ERR_ARG;
+        pl->prefill_tile = variant ? variant : kPrefillTile128x256;
     }
     return W4A8_OK;
 }
@@ -113,10 +115,8 @@ int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float 
         PrefillArgs a{};
         a.xq = xq; a.s_a = s_a; a.wp = wp; a.s_w = s_w;
         a.out = out_fp16; a.acc_out = acc_i32;
-        a.M = M; a.N = N; a.K = K;
-        a.tiles_m = (M + kPrefillBM - 1) / kPrefillBM;
-        a.tiles_n = (N + kPrefillBN - 1) / kPrefillBN;
-        err = launch_gemm_prefill(a, want_acc, st);
+        a.M = M; a.N = N; a.K = K; a.ldc = N;
+        err = launch_gemm_prefill(a, want_acc, pl.prefill_tile, st);
     }
     return err == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
 }

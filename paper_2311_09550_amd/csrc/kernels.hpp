@@ -37,15 +37,19 @@ struct PrefillArgs {
     const float *s_w;
     void *out;
     int *acc_out;
-    int M, N, K;
+    int M, N, K;       // extent of this launch (a slice of the whole problem when that exceeds 32-bit byte offsets)
+    int ldc;           // row stride of out / acc_out in elements (the full N)
     int tiles_m, tiles_n;
 };
 
-constexpr int kPrefillBM = 128;
-constexpr int kPrefillBN = 256;
 constexpr int kPrefillBK = 128;
+// output tile shapes (rows of X x output channels) of the LDS-staged kernel
+constexpr int kPrefillTile128x256 = 1;
+constexpr int kPrefillTile128x128 = 2;
+constexpr int kPrefillTile128x160 = 3;
+constexpr int kPrefillTile128x256Square = 4;  // 128 x 256 with 2 x 2 waves of 64 x 128 (1 uses 1 x 4 waves of 128 x 64)
 
-hipError_t launch_gemm_prefill(const PrefillArgs &p, bool acc_out, hipStream_t stream);
+hipError_t launch_gemm_prefill(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
 
 hipError_t launch_quantize_act(const void *x, int8_t *xq, float *s_a, int M, int K, hipStream_t stream);
 hipError_t launch_quantize_weights(const void *w, uint8_t *wp, float *s_w, int N, int K, hipStream_t stream);

@@ -72,7 +72,7 @@ def test_argument_validation_happens_before_any_launch(L):
     t = L.w4a8_gemm_tuned
     assert t(p, p, p, p, p, null, 1, 16, 1024, 7, 0, p, big, null) == -7       # unknown tiling
     assert t(p, p, p, p, p, null, 1, 16, 1024, 2, 303, p, big, null) == -7     # stream: 3 row tiles / 3 waves do not exist
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 3, 5, p, big, null) == -7       # prefill has no variants
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 3, 9, p, big, null) == -7       # prefill: unknown tile id
     assert t(p, p, p, p, p, null, 65, 16, 1024, 2, 0, p, big, null) == -7      # decode tilings are for M <= 64
     assert t(p, p, p, p, p, null, 65, 16, 1024, 1, 0, p, big, null) == -7
     assert t(p, p, p, p, p, null, 16, 16, 32768, 1, 0, p, big, null) == -7     # resident: activations would not fit in registers

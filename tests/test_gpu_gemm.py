@@ -118,17 +118,22 @@ def test_back_to_back_calls_share_nothing(gpu, oracle):
         assert_equal_bits(acc.cpu().numpy(), jobs[i // 2][2], f"call {i}")
 
 
+PREFILL_TILES = [1, 2, 3, 4]   # 128 x 256 (1 x 4 waves), 128 x 128, 128 x 160, 128 x 256 (2 x 2 waves)
+
+
+@pytest.mark.parametrize("tile", PREFILL_TILES)
 @pytest.mark.parametrize("M", [1, 17, 64, 65, 127, 128, 129, 300])
-def test_prefill_tiling_all_m(gpu, oracle, M):
+def test_prefill_tiling_all_m(gpu, oracle, M, tile):
     xq, wq, s_a, s_w = _codes(M, 520, 1056, tag=40)
-    _run_both(gpu, oracle, xq, wq, s_a, s_w, PREFILL, 0, f"prefill M={M}")
+    _run_both(gpu, oracle, xq, wq, s_a, s_w, PREFILL, tile, f"prefill tile={tile} M={M}")
 
 
 @pytest.mark.parametrize("M,N,K", [(130, 1, 32), (128, 255, 64), (256, 256, 96), (100, 257, 128), (200, 1001, 160),
                                    (70, 1000, 4128), (1024, 512, 1024), (384, 300, 5120)])
-def test_prefill_tiling_ragged_shapes(gpu, oracle, M, N, K):
+@pytest.mark.parametrize("tile", PREFILL_TILES)
+def test_prefill_tiling_ragged_shapes(gpu, oracle, M, N, K, tile):
     xq, wq, s_a, s_w = _codes(M, N, K, tag=41)
-    _run_both(gpu, oracle, xq, wq, s_a, s_w, PREFILL, 0, f"prefill M={M} N={N} K={K}")
+    _run_both(gpu, oracle, xq, wq, s_a, s_w, PREFILL, tile, f"prefill tile={tile} M={M} N={N} K={K}")
 
 
 @pytest.mark.parametrize("tiling,M", [(STREAM, 2), (STREAM, 40), (PREFILL, 130)])
