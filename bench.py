@@ -107,10 +107,11 @@ class LayerStack:
         return sum(gemm_ops(self.M, N, K) for N, K in self.shapes.values())
 
 
-def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=40):
+def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
     """Weight-streaming GEMMs: every launch reads a different copy of the weights, the copies together
     exceeding the last-level cache three times, so the weights come from HBM.  Per-launch time is the
-    average over a back-to-back batch between two events on the launch stream (dispatch gaps included)."""
+    average over back-to-back batches replayed from a HIP graph, between two events on the launch stream
+    (the gaps between dependent kernels are included)."""
     rows = []
     for name, (N, K) in synth.LLAMA_SHAPES[model].items():
         w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).cuda()
@@ -124,17 +125,26 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=40):
             xq, s_a = w4a8.w4a8_quantize_act(x)
             out = torch.empty((M, N), dtype=torch.float16, device="cuda")
             ws = w4a8.workspace(M, N, K)
-            for i in range(copies):
+            for i in range(min(copies, 4)):
                 w4a8.w4a8_gemm(xq, s_a, wps[i], s_w, out=out, ws=ws)
             torch.cuda.synchronize()
+            # One graph holds a back-to-back batch of launches (a decode loop is replayed from a graph as well; launching
+            # each 5-15 us kernel from Python would time the interpreter, not the GPU).
+            n = max(copies, 24)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(n):
+                    w4a8.w4a8_gemm(xq, s_a, wps[i % copies], s_w, out=out, ws=ws)
+            graph.replay()
+            torch.cuda.synchronize()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            n = iters * copies
             a.record()
-            for i in range(n):
-                w4a8.w4a8_gemm(xq, s_a, wps[i % copies], s_w, out=out, ws=ws)
+            for _ in range(iters):
+                graph.replay()
             b.record()
             torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / n
+            us = a.elapsed_time(b) * 1e3 / (n * iters)
+            del graph
             by = gemm_bytes(M, N, K)
             rows.append({"linear": name, "M": M, "N": N, "K": K, "us": round(us, 3),
                          "GBps": round(by / us / 1e3, 1), "hbm_frac": round(by / us / 1e3 / HBM_PEAK_GBS, 4),

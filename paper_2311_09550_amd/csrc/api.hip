@@ -59,6 +59,29 @@ bool resident_shape(int M, int N, int K, int waves, int grid, DecodeShape *out) 
     return true;
 }
 
+// Output tile of the LDS-staged kernel.  A launch runs in rounds of as many workgroups as the chip holds at once,
+// so the estimate is rounds x tile area / relative efficiency of the tile shape (measured on LLaMA-13B shapes): the
+// big tile does the most work per byte staged, the smaller ones fill the chip when N is small.
+int choose_prefill_tile(int M, int N) {
+    struct Option { int id, bm, bn, per_cu; double eff; };
+    const Option options[] = {{kPrefillTile128x256, 128, 256, 2, 1.00},
+                              {kPrefillTile128x160, 128, 160, 2, 0.82},
+                              {kPrefillTile128x128, 128, 128, 3, 0.78}};
+    const int cus = compute_units();
+    int best = kPrefillTile128x256;
+    double best_cost = 0;
+    for (const Option &o : options) {
+        const long long tiles = (long long)((M + o.bm - 1) / o.bm) * ((N + o.bn - 1) / o.bn);
+        const long long slots = (long long)cus * o.per_cu;
+        const long long full = tiles / slots, rest = tiles % slots;
+        // a partial last round costs at least half a round: its workgroups no longer share their compute unit
+        const double rounds = (double)full + (rest == 0 ? 0.0 : (rest * 2 <= slots ? 0.5 : (double)rest / slots * 0.5 + 0.5));
+        const double cost = rounds * o.bm * o.bn * o.per_cu / o.eff;
+        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = o.id; }
+    }
+    return best;
+}
+
 // Tiling choice.  Small M streams the weights once (HBM bound); large M goes to the LDS-staged tiling
 // (matrix-core bound).  `variant` refines a forced tiling (see w4a8.h); 0 lets the library choose.
 int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
@@ -84,7 +107,7 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
         pl->decode = s;
     } else {
         if (variant < 0 || variant > kPrefillTile128x256Square) return W4A8_ERR_ARG;
-        pl->prefill_tile = variant ? variant : kPrefillTile128x256;
+        pl->prefill_tile = variant ? variant : choose_prefill_tile(M, N);
     }
     return W4A8_OK;
 }

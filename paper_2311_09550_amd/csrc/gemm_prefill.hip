@@ -148,39 +148,56 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_kernel(PrefillAr
     const int a_row0 = wm * (32 * MTW) + idx;
     const int b_row0 = wn * (32 * NTW) + idx;
 
+    // A k step of 128 is four MFMA steps of 32: step j = 2s + h.  Lane group g holds the 32 weights of 16-byte chunk
+    // (2s + g) of the packed row; their halves h = 0, 1 feed one MFMA step each, against activation chunk 2*(2s+g)+h.
+    // The LDS reads run one MFMA step ahead of the MFMAs that use them, and the hand-over to the next k step (LDS
+    // store, barrier, first reads from the new buffer) sits in front of the last MFMA step, whose operands are already
+    // in registers: LDS latency and the barrier are covered by matrix work instead of being waited for.
+    auto read_x = [&](v4i(&dst)[MTW], int buf, int j) {
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+            dst[mt] = *(const v4i *)(&lds_a[buf][a_slot(a_row0 + 32 * mt, 2 * (2 * (j >> 1) + g) + (j & 1))]);
+    };
+    auto read_w = [&](v4u(&dst)[NTW], int buf, int s) {
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) dst[t] = *(const v4u *)(&lds_b[buf][b_slot(b_row0 + 32 * t, 2 * s + g)]);
+    };
+    auto mfma_step = [&](const v4i(&x)[MTW], const v4u(&w)[NTW], int h) {
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) {
+            const v4i wop = h == 0 ? w_operand(w[t].x, w[t].y) : w_operand(w[t].z, w[t].w);
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt) acc[mt][t] = mfma_i8_32x32x32(wop, x[mt], acc[mt][t]);
+        }
+    };
+
     load_global(0);
     store_lds(0);
     __syncthreads();
 
+    v4i x0[MTW], x1[MTW];
+    v4u w0[NTW], w1[NTW];
+    read_x(x0, 0, 0);
+    read_w(w0, 0, 0);
     int buf = 0;
     for (int kt = 0; kt < kt_total; ++kt) {
         const bool more = kt + 1 < kt_total;
         if (more) load_global(kt + 1);
 
-        // A k step of 128 is four MFMA steps of 32.  Lane group g holds the 32 weights of 16-byte chunk (2s + g) of
-        // the packed row, s = 0, 1; their halves h = 0, 1 feed one MFMA each, against activation chunk 2*(2s+g)+h.
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            v4u wpk[NTW];
-#pragma unroll
-            for (int t = 0; t < NTW; ++t) wpk[t] = *(const v4u *)(&lds_b[buf][b_slot(b_row0 + 32 * t, 2 * s + g)]);
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                v4i xop[MTW];
-#pragma unroll
-                for (int mt = 0; mt < MTW; ++mt)
-                    xop[mt] = *(const v4i *)(&lds_a[buf][a_slot(a_row0 + 32 * mt, 2 * (2 * s + g) + h)]);
-#pragma unroll
-                for (int t = 0; t < NTW; ++t) {
-                    const v4i wop = h == 0 ? w_operand(wpk[t].x, wpk[t].y) : w_operand(wpk[t].z, wpk[t].w);
-#pragma unroll
-                    for (int mt = 0; mt < MTW; ++mt) acc[mt][t] = mfma_i8_32x32x32(wop, xop[mt], acc[mt][t]);
-                }
-            }
+        read_x(x1, buf, 1);
+        mfma_step(x0, w0, 0);  // step 0
+        read_x(x0, buf, 2);
+        read_w(w1, buf, 1);
+        mfma_step(x1, w0, 1);  // step 1
+        read_x(x1, buf, 3);
+        mfma_step(x0, w1, 0);  // step 2
+        if (more) {
+            store_lds(buf ^ 1);
+            __syncthreads();
+            read_x(x0, buf ^ 1, 0);
+            read_w(w0, buf ^ 1, 0);
         }
-
-        if (more) store_lds(buf ^ 1);
-        __syncthreads();
+        mfma_step(x1, w1, 1);  // step 3
         buf ^= 1;
     }
 
