@@ -143,6 +143,16 @@ int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, in
 int w4a8_silu_mul(const void *gate_up_fp16, void *h_fp16, int M, int I, void *stream);
 
 /*
+ * The glue above fused with the per-token quantiser that follows it in a LLaMA MLP (the kind of fusion across
+ * operators the paper's engine relies on, Sec. 6.1): h is formed as in w4a8_silu_mul, kept on chip, and quantised
+ * exactly as w4a8_quantize_act would quantise it.  The result equals
+ *   w4a8_silu_mul(gate_up, h); w4a8_quantize_act(h, xq, s_a)
+ * bit for bit, without h going to memory.
+ *   gate_up_fp16 [M][2I] in, xq [M][I] int8 out, s_a [M] out.  I follows the K contract (I % 32 == 0, I <= 65536).
+ */
+int w4a8_silu_mul_quantize(const void *gate_up_fp16, int8_t *xq, float *s_a, int M, int I, void *stream);
+
+/*
  * Host-side packing of already quantised weights (App. A.1; no GPU needed).
  *   wq_host [N][K] int8 codes in [-8,7]  ->  wp_host [N][K/2].
  * Returns W4A8_ERR_VALUE if a code is out of range, W4A8_ERR_SHAPE if K is odd.

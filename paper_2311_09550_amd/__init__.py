@@ -46,9 +46,10 @@ def lib():
         L.w4a8_gemm_tuned.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
         L.w4a8_quantize_weights.argtypes = [vp, vp, vp, i, i, vp]
         L.w4a8_silu_mul.argtypes = [vp, vp, i, i, vp]
+        L.w4a8_silu_mul_quantize.argtypes = [vp, vp, vp, i, i, vp]
         L.w4a8_pack_weights_host.argtypes = [vp, vp, i, i]
         for name in ("w4a8_quantize_act", "w4a8_gemm", "w4a8_gemm_acc_i32", "w4a8_gemm_tuned",
-                     "w4a8_quantize_weights", "w4a8_silu_mul", "w4a8_pack_weights_host"):
+                     "w4a8_quantize_weights", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host"):
             getattr(L, name).restype = i
         _lib = L
     return _lib
@@ -190,6 +191,18 @@ def w4a8_silu_mul(gate_up, h=None):
     h = torch.empty((M, I), dtype=torch.float16, device=gate_up.device) if h is None else h
     _check(lib().w4a8_silu_mul(_dev(gate_up, torch.float16, "gate_up"), _dev(h, torch.float16, "h"), M, I, _stream()))
     return h
+
+
+def w4a8_silu_mul_quantize(gate_up, xq=None, s_a=None):
+    """fp16 [M][2I] -> (int8 [M][I], fp32 [M]): SiLU*up and the per-token quantiser in one pass."""
+    torch = _torch()
+    M, I2 = gate_up.shape
+    I = I2 // 2
+    xq = torch.empty((M, I), dtype=torch.int8, device=gate_up.device) if xq is None else xq
+    s_a = torch.empty((M,), dtype=torch.float32, device=gate_up.device) if s_a is None else s_a
+    _check(lib().w4a8_silu_mul_quantize(_dev(gate_up, torch.float16, "gate_up"), _dev(xq, torch.int8, "xq"),
+                                        _dev(s_a, torch.float32, "s_a"), M, I, _stream()))
+    return xq, s_a
 
 
 def w4a8_pack_weights_host(wq):

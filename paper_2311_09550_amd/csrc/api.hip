@@ -214,6 +214,15 @@ int w4a8_silu_mul(const void *gate_up_fp16, void *h_fp16, int M, int I, void *st
                                                                                                           : W4A8_ERR_LAUNCH;
 }
 
+int w4a8_silu_mul_quantize(const void *gate_up_fp16, int8_t *xq, float *s_a, int M, int I, void *stream) {
+    if (!gate_up_fp16 || !xq || !s_a) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(M, 1, I)) return e;  // I is the K of the GEMM that consumes xq
+    if (misaligned(gate_up_fp16) || misaligned(xq)) return W4A8_ERR_ALIGN;
+    return launch_silu_mul_quantize(gate_up_fp16, xq, s_a, M, I, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? W4A8_OK
+               : W4A8_ERR_LAUNCH;
+}
+
 int w4a8_pack_weights_host(const int8_t *wq_host, uint8_t *wp_host, int N, int K) {
     if (!wq_host || !wp_host) return W4A8_ERR_NULL;
     if (N < 1 || K < 2 || (K & 1)) return W4A8_ERR_SHAPE;

@@ -1,6 +1,7 @@
 // Row-wise kernels around the GEMM: the per-token activation quantiser, the
-// offline per-channel weight quantiser + packer, and the SiLU*up glue.
-// All three are one pass over HBM; a workgroup owns one row.
+// offline per-channel weight quantiser + packer, the SiLU*up glue, and the
+// glue fused with the quantiser that follows it.  All are one pass over HBM;
+// a workgroup owns one row.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -12,18 +13,21 @@ constexpr int kRowThreads = 256;
 constexpr int kCache = 8;  // 16-byte chunks a thread keeps in registers between the two passes (K <= 16384)
 
 __device__ __forceinline__ float half_bits_to_float(unsigned short h) { return __half2float(__ushort_as_half(h)); }
+__device__ __forceinline__ float lo_half(unsigned w) { return half_bits_to_float((unsigned short)(w & 0xFFFFu)); }
+__device__ __forceinline__ float hi_half(unsigned w) { return half_bits_to_float((unsigned short)(w >> 16)); }
 
 // absolute maximum of eight fp16 values held in four words
 __device__ __forceinline__ float absmax8(v4u c, float m) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        m = fmaxf(m, fabsf(half_bits_to_float((unsigned short)(c[j] & 0xFFFFu))));
-        m = fmaxf(m, fabsf(half_bits_to_float((unsigned short)(c[j] >> 16))));
+        m = fmaxf(m, fabsf(lo_half(c[j])));
+        m = fmaxf(m, fabsf(hi_half(c[j])));
     }
     return m;
 }
 
 // maximum over the workgroup; every thread gets the result
+template <int THREADS = kRowThreads>
 __device__ __forceinline__ float block_max(float v, float *scratch) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
@@ -32,22 +36,76 @@ __device__ __forceinline__ float block_max(float v, float *scratch) {
     __syncthreads();
     float m = scratch[0];
 #pragma unroll
-    for (int w = 1; w < kRowThreads / 64; ++w) m = fmaxf(m, scratch[w]);
+    for (int w = 1; w < THREADS / 64; ++w) m = fmaxf(m, scratch[w]);
     return m;
 }
 
-// Eq. (2) with zero point 0: divide by the scale in fp32 (IEEE division), round half to even, clamp.
-__device__ __forceinline__ int quant_code(float x, float scale, float lo, float hi) {
-    float q = __fdiv_rn(x, scale);
-    q = rintf(q);
-    q = fminf(fmaxf(q, lo), hi);
-    return (int)q;
+// Symmetric quantisation of one row (Eq. (2) with zero point 0): code = clamp(rne(fl32(x / scale)), lo, hi).
+//
+// The definition divides.  A correctly rounded fp32 division costs about ten instructions, so the common case
+// takes a shortcut that provably gives the same integer: with r = fl32(1/scale) and q' = fl32(x * r),
+// |q' - x/scale| <= |x/scale| * (2^-23 + 2^-48) < 1.6e-5 for |x/scale| <= 128, and the definition's quotient
+// fl32(x/scale) lies within 3.9e-6 of x/scale.  So when q' is at least 1e-4 away from the nearest half-integer,
+// both quotients round to the same integer; otherwise (about 2 in 10^4 elements, or rows whose quotients are
+// exact halves) the eight values of the chunk are redone with the division.
+struct RowQuantizer {
+    float scale, recip, lo, hi;
+    __device__ __forceinline__ RowQuantizer(float amax, float qmax, float lo_, float hi_) : lo(lo_), hi(hi_) {
+        scale = __fdiv_rn(amax, qmax);
+        recip = __fdiv_rn(1.0f, scale);  // unused when amax == 0
+    }
+    __device__ __forceinline__ void codes8(const float (&x)[8], int (&q)[8]) const {
+        bool near_tie = false;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float qp = x[j] * recip;
+            const float n = rintf(qp);
+            near_tie |= fabsf(qp - n) > 0.5f - 1e-4f;
+            q[j] = (int)fminf(fmaxf(n, lo), hi);
+        }
+        if (near_tie) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = (int)fminf(fmaxf(rintf(__fdiv_rn(x[j], scale)), lo), hi);
+        }
+    }
+};
+
+__device__ __forceinline__ void halves8(v4u v, float (&x)[8]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        x[2 * j] = lo_half(v[j]);
+        x[2 * j + 1] = hi_half(v[j]);
+    }
+}
+
+__device__ __forceinline__ v2u pack_i8x8(const int (&q)[8]) {
+    v2u o;
+    o.x = (q[0] & 255) | ((q[1] & 255) << 8) | ((q[2] & 255) << 16) | ((unsigned)(q[3] & 255) << 24);
+    o.y = (q[4] & 255) | ((q[5] & 255) << 8) | ((q[6] & 255) << 16) | ((unsigned)(q[7] & 255) << 24);
+    return o;
+}
+
+// fp16( silu(gate) * up ) for eight gate / up pairs, fp32 arithmetic, as four words of two fp16 each
+__device__ __forceinline__ v4u silu_mul8(v4u gv, v4u uv) {
+    v4u o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float y[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const float gt = e ? hi_half(gv[j]) : lo_half(gv[j]);
+            const float up = e ? hi_half(uv[j]) : lo_half(uv[j]);
+            y[e] = __fdiv_rn(gt, 1.0f + expf(-gt)) * up;
+        }
+        o[j] = pack_f16x2(y[0], y[1]);
+    }
+    return o;
 }
 
 }  // namespace
 
 // Per-token symmetric int8 quantisation (Sec. 3 "per token"; Eq. (2), z = 0).
-__global__ __launch_bounds__(kRowThreads) void quantize_act_kernel(const uint16_t *__restrict__ x, int8_t *__restrict__ xq,
+__global__ __launch_bounds__(kRowThreads, 8) void quantize_act_kernel(const uint16_t *__restrict__ x, int8_t *__restrict__ xq,
                                                                    float *__restrict__ s_a, int K) {
     __shared__ float scratch[kRowThreads / 64];
     const int m = blockIdx.x;
@@ -66,22 +124,19 @@ __global__ __launch_bounds__(kRowThreads) void quantize_act_kernel(const uint16_
     for (int c = threadIdx.x + kCache * kRowThreads; c < chunks; c += kRowThreads) amax = absmax8(src[c], amax);
     amax = block_max(amax, scratch);
 
-    const float scale = __fdiv_rn(amax, 127.0f);
-    if (threadIdx.x == 0) s_a[m] = scale;  // amax == 0 gives scale 0
+    const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
+    if (threadIdx.x == 0) s_a[m] = rq.scale;  // amax == 0 gives scale 0
     const bool zero_row = amax == 0.f;
 
     v2u *dst = (v2u *)(xq + (size_t)m * K);
     auto emit = [&](int c, v4u v) {
         v2u o = v2u{0, 0};
         if (!zero_row) {
+            float xf[8];
             int q[8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                q[2 * j] = quant_code(half_bits_to_float((unsigned short)(v[j] & 0xFFFFu)), scale, -127.f, 127.f);
-                q[2 * j + 1] = quant_code(half_bits_to_float((unsigned short)(v[j] >> 16)), scale, -127.f, 127.f);
-            }
-            o.x = (q[0] & 255) | ((q[1] & 255) << 8) | ((q[2] & 255) << 16) | ((unsigned)(q[3] & 255) << 24);
-            o.y = (q[4] & 255) | ((q[5] & 255) << 8) | ((q[6] & 255) << 16) | ((unsigned)(q[7] & 255) << 24);
+            halves8(v, xf);
+            rq.codes8(xf, q);
+            o = pack_i8x8(q);
         }
         dst[c] = o;
     };
@@ -95,7 +150,7 @@ __global__ __launch_bounds__(kRowThreads) void quantize_act_kernel(const uint16_
 
 // Per-output-channel symmetric int4 round-to-nearest (Eq. (8),(9), 4 bits, gamma = beta = 1)
 // followed by the nibble packing of App. A.1 (low nibble = even k).
-__global__ __launch_bounds__(kRowThreads) void quantize_weights_kernel(const uint16_t *__restrict__ w, uint8_t *__restrict__ wp,
+__global__ __launch_bounds__(kRowThreads, 8) void quantize_weights_kernel(const uint16_t *__restrict__ w, uint8_t *__restrict__ wp,
                                                                        float *__restrict__ s_w, int K) {
     __shared__ float scratch[kRowThreads / 64];
     const int n = blockIdx.x;
@@ -106,21 +161,20 @@ __global__ __launch_bounds__(kRowThreads) void quantize_weights_kernel(const uin
     for (int c = threadIdx.x; c < chunks; c += kRowThreads) amax = absmax8(src[c], amax);
     amax = block_max(amax, scratch);
 
-    const float scale = __fdiv_rn(amax, 7.0f);
-    if (threadIdx.x == 0) s_w[n] = scale;
+    const RowQuantizer rq(amax, 7.0f, -8.f, 7.f);
+    if (threadIdx.x == 0) s_w[n] = rq.scale;
     const bool zero_row = amax == 0.f;
 
     unsigned *dst = (unsigned *)(wp + (size_t)n * (K >> 1));
     for (int c = threadIdx.x; c < chunks; c += kRowThreads) {
-        const v4u v = src[c];
         unsigned o = 0;
         if (!zero_row) {
+            float xf[8];
+            int q[8];
+            halves8(src[c], xf);
+            rq.codes8(xf, q);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int q0 = quant_code(half_bits_to_float((unsigned short)(v[j] & 0xFFFFu)), scale, -8.f, 7.f);
-                const int q1 = quant_code(half_bits_to_float((unsigned short)(v[j] >> 16)), scale, -8.f, 7.f);
-                o |= (unsigned)((q0 & 15) | ((q1 & 15) << 4)) << (8 * j);
-            }
+            for (int j = 0; j < 4; ++j) o |= (unsigned)((q[2 * j] & 15) | ((q[2 * j + 1] & 15) << 4)) << (8 * j);
         }
         dst[c] = o;
     }
@@ -134,19 +188,61 @@ __global__ __launch_bounds__(kRowThreads) void silu_mul_kernel(const uint16_t *_
     if (c >= (I >> 3)) return;
     const v4u gv = *((const v4u *)(gate_up + (size_t)m * 2 * I) + c);
     const v4u uv = *((const v4u *)(gate_up + (size_t)m * 2 * I + I) + c);
-    v4u o;
+    *((v4u *)(h + (size_t)m * I) + c) = silu_mul8(gv, uv);
+}
+
+// The glue and the quantiser behind it in one pass: h = fp16(silu(gate) * up) is formed in registers (the same
+// arithmetic as silu_mul_kernel, so the same fp16 bits), then quantised per token exactly as quantize_act_kernel
+// would quantise it.  The fp16 intermediate never goes to memory.  A row is spread over 1024 threads so that a
+// thread holds at most two chunks of h (I <= 16384); longer rows recompute h in the second pass.
+constexpr int kFusedThreads = 1024;
+constexpr int kFusedCache = 2;
+
+__global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const uint16_t *__restrict__ gate_up,
+                                                                          int8_t *__restrict__ xq, float *__restrict__ s_a,
+                                                                          int I) {
+    __shared__ float scratch[kFusedThreads / 64];
+    const int m = blockIdx.x;
+    const int chunks = I >> 3;
+    const v4u *gate = (const v4u *)(gate_up + (size_t)m * 2 * I);
+    const v4u *up = (const v4u *)(gate_up + (size_t)m * 2 * I + I);
+
+    v4u cache[kFusedCache];
+    float amax = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        float y[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const float gt = half_bits_to_float((unsigned short)(e ? gv[j] >> 16 : gv[j] & 0xFFFFu));
-            const float up = half_bits_to_float((unsigned short)(e ? uv[j] >> 16 : uv[j] & 0xFFFFu));
-            y[e] = __fdiv_rn(gt, 1.0f + expf(-gt)) * up;
-        }
-        o[j] = pack_f16x2(y[0], y[1]);
+    for (int i = 0; i < kFusedCache; ++i) {
+        const int c = threadIdx.x + i * kFusedThreads;
+        cache[i] = v4u{0, 0, 0, 0};
+        if (c < chunks) cache[i] = silu_mul8(gate[c], up[c]);
+        amax = absmax8(cache[i], amax);
     }
-    *((v4u *)(h + (size_t)m * I) + c) = o;
+    for (int c = threadIdx.x + kFusedCache * kFusedThreads; c < chunks; c += kFusedThreads)
+        amax = absmax8(silu_mul8(gate[c], up[c]), amax);
+    amax = block_max<kFusedThreads>(amax, scratch);
+
+    const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
+    if (threadIdx.x == 0) s_a[m] = rq.scale;
+    const bool zero_row = amax == 0.f;
+
+    v2u *dst = (v2u *)(xq + (size_t)m * I);
+    auto emit = [&](int c, v4u v) {
+        v2u o = v2u{0, 0};
+        if (!zero_row) {
+            float xf[8];
+            int q[8];
+            halves8(v, xf);
+            rq.codes8(xf, q);
+            o = pack_i8x8(q);
+        }
+        dst[c] = o;
+    };
+#pragma unroll
+    for (int i = 0; i < kFusedCache; ++i) {
+        const int c = threadIdx.x + i * kFusedThreads;
+        if (c < chunks) emit(c, cache[i]);
+    }
+    for (int c = threadIdx.x + kFusedCache * kFusedThreads; c < chunks; c += kFusedThreads)
+        emit(c, silu_mul8(gate[c], up[c]));
 }
 
 hipError_t launch_quantize_act(const void *x, int8_t *xq, float *s_a, int M, int K, hipStream_t stream) {
@@ -163,6 +259,11 @@ hipError_t launch_silu_mul(const void *gate_up, void *h, int M, int I, hipStream
     const int chunks = I >> 3;
     dim3 grid((chunks + kRowThreads - 1) / kRowThreads, M);
     hipLaunchKernelGGL(silu_mul_kernel, grid, dim3(kRowThreads), 0, stream, (const uint16_t *)gate_up, (uint16_t *)h, I);
+    return hipGetLastError();
+}
+
+hipError_t launch_silu_mul_quantize(const void *gate_up, int8_t *xq, float *s_a, int M, int I, hipStream_t stream) {
+    hipLaunchKernelGGL(silu_mul_quantize_kernel, dim3(M), dim3(kFusedThreads), 0, stream, (const uint16_t *)gate_up, xq, s_a, I);
     return hipGetLastError();
 }
 

@@ -88,6 +88,8 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_quantize_weights(p, p, p, 4, 33, null) == -2
     assert L.w4a8_silu_mul(p, null, 1, 8, null) == -1
     assert L.w4a8_silu_mul(p, p, 1, 12, null) == -2
+    assert L.w4a8_silu_mul_quantize(p, null, p, 1, 32, null) == -1
+    assert L.w4a8_silu_mul_quantize(p, p, p, 1, 24, null) == -2
 
 
 def test_host_packing_matches_oracle_and_rejects_bad_codes(L, oracle):

@@ -96,3 +96,47 @@ def test_silu_mul_close(gpu, oracle, M, I):
     normal = finite & (np.abs(y64) >= FP16_MIN_NORMAL)
     assert np.all(err[normal] <= REL_TOL * np.abs(y64[normal]))
     assert np.all(err[finite & ~normal] <= SUBNORMAL_STEP)
+
+
+@pytest.mark.parametrize("M,I", [(1, 32), (3, 96), (16, 13824), (130, 1024), (2, 16416)])
+def test_silu_mul_quantize_equals_the_two_kernels_and_the_oracle(gpu, oracle, M, I):
+    """Stage-wise parity of the fused glue + quantiser: its codes and scales are those of quantising the GPU's own
+    fp16 intermediate (bit-exact against the oracle's quantiser fed that intermediate)."""
+    g = synth.rng(922, M, I)
+    gu = (g.standard_normal((M, 2 * I)) * 3).astype(np.float16)
+    gu[0, :8] = 0
+    d = gpu.from_numpy(gu).cuda()
+    h = w4a8.w4a8_silu_mul(d)
+    xq2, sa2 = w4a8.w4a8_quantize_act(h)
+    xq, sa = w4a8.w4a8_silu_mul_quantize(d)
+    gpu.cuda.synchronize()
+    assert_equal_bits(xq.cpu().numpy(), xq2.cpu().numpy(), "fused vs two kernels: codes")
+    assert_equal_bits(sa.cpu().numpy().view(np.uint32), sa2.cpu().numpy().view(np.uint32), "fused vs two kernels: scales")
+    xq_o, sa_o = oracle.quantize_act(h.cpu().numpy())
+    assert_equal_bits(xq.cpu().numpy(), xq_o, "codes vs oracle on the GPU's intermediate")
+    assert_equal_bits(sa.cpu().numpy().view(np.uint32), sa_o.view(np.uint32), "scales vs oracle")
+
+
+def test_quantizers_on_adversarial_quotients(gpu, oracle):
+    """Rows built so that many quotients x / s_a sit exactly on, or within an ulp of, a half-integer: the shortcut
+    of the quantiser must fall back to the division there."""
+    g = synth.rng(923)
+    rows = []
+    for amax in (127.0, 63.5, 254.0, 31.75, 1016.0, 0.9921875):
+        s = amax / 127.0
+        ks = g.integers(-126, 127, size=255).astype(np.float64) + 0.5
+        x = np.concatenate([[amax], ks * s]).astype(np.float16)
+        rows.append(x)
+        x2 = x.copy(); x2[1:] = np.nextafter(x2[1:], np.float16(np.inf)); rows.append(x2)
+        x3 = x.copy(); x3[1:] = np.nextafter(x3[1:], np.float16(-np.inf)); rows.append(x3)
+    x = np.stack(rows)
+    xq, s_a = _quant_act_gpu(gpu, x)
+    xq_o, s_o = oracle.quantize_act(x)
+    assert_equal_bits(s_a.view(np.uint32), s_o.view(np.uint32), "s_a")
+    assert_equal_bits(xq, xq_o, "xq")
+    w = np.stack([np.concatenate([[7.0 * sc], (g.integers(-7, 7, size=255) + 0.5) * sc]).astype(np.float16) for sc in (1.0, 0.5, 0.03125, 3.0)])
+    wp, s_w = w4a8.w4a8_quantize_weights(gpu.from_numpy(w).cuda())
+    gpu.cuda.synchronize()
+    wq_o, sw_o = oracle.quantize_weights_rtn(w)
+    assert_equal_bits(s_w.cpu().numpy().view(np.uint32), sw_o.view(np.uint32), "s_w")
+    assert_equal_bits(wp.cpu().numpy(), oracle.pack_w4(wq_o), "wp")
