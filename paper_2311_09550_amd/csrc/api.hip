@@ -106,7 +106,7 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
         if (mt == 4 && s.row_tiles == 2 && s.waves == 8) return W4A8_ERR_ARG;  // would not fit in LDS
         pl->decode = s;
     } else {
-        if (variant < 0 || variant > kPrefillTile128x256Square) return W4A8_ERR_ARG;
+        if (variant < 0 || variant > kPrefillTileMax) return W4A8_ERR_ARG;
         pl->prefill_tile = variant ? variant : choose_prefill_tile(M, N);
     }
     return W4A8_OK;

@@ -287,7 +287,8 @@ hipError_t launch_gemm_prefill(const PrefillArgs &p, bool acc_out, int tile, hip
             if (p.s_w) q.s_w = p.s_w + n0;
             if (p.out) q.out = (unsigned short *)p.out + (size_t)m0 * p.ldc + n0;
             if (p.acc_out) q.acc_out = p.acc_out + (size_t)m0 * p.ldc + n0;
-            const hipError_t e = launch_slice(q, acc_out, tile, stream);
+            const hipError_t e = tile >= kPrefillDma128x256 ? launch_prefill_dma_slice(q, acc_out, tile, stream)
+                                                            : launch_slice(q, acc_out, tile, stream);
             if (e != hipSuccess) return e;
         }
     }

@@ -49,7 +49,15 @@ constexpr int kPrefillTile128x128 = 2;
 constexpr int kPrefillTile128x160 = 3;
 constexpr int kPrefillTile128x256Square = 4;  // 128 x 256 with 2 x 2 waves of 64 x 128 (1 uses 1 x 4 waves of 128 x 64)
 
+// the same tile shapes with operands brought into LDS by LDS-direct buffer loads (four-stage ring)
+constexpr int kPrefillDma128x256 = 5;
+constexpr int kPrefillDma128x256Square = 6;
+constexpr int kPrefillDma128x160 = 7;
+constexpr int kPrefillDma128x128 = 8;
+constexpr int kPrefillTileMax = 8;
+
 hipError_t launch_gemm_prefill(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
+hipError_t launch_prefill_dma_slice(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
 
 hipError_t launch_quantize_act(const void *x, int8_t *xq, float *s_a, int M, int K, hipStream_t stream);
 hipError_t launch_quantize_weights(const void *w, uint8_t *wp, float *s_w, int N, int K, hipStream_t stream);

@@ -118,7 +118,7 @@ def test_back_to_back_calls_share_nothing(gpu, oracle):
         assert_equal_bits(acc.cpu().numpy(), jobs[i // 2][2], f"call {i}")
 
 
-PREFILL_TILES = [1, 2, 3, 4]   # 128 x 256 (1 x 4 waves), 128 x 128, 128 x 160, 128 x 256 (2 x 2 waves)
+PREFILL_TILES = [1, 2, 3, 4, 5, 6, 7, 8]   # register-staged 128x256 (1x4 waves), 128x128, 128x160, 128x256 (2x2 waves); 5..8: the same four shapes, LDS-direct loads
 
 
 @pytest.mark.parametrize("tile", PREFILL_TILES)
