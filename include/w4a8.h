@@ -112,7 +112,10 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
  *                    workgroups = size of the persistent grid (0 = default);
  *   DECODE_STREAM:   row_tiles * 100 + waves, row_tiles in {1, 2}, waves in {4, 8};
  *   PREFILL:         output tile (rows of X x channels): 1 = 128 x 256 as 1 x 4 waves, 2 = 128 x 128,
- *                    3 = 128 x 160, 4 = 128 x 256 as 2 x 2 waves.
+ *                    3 = 128 x 160, 4 = 128 x 256 as 2 x 2 waves (operands staged through registers);
+ *                    5..8 = the shapes of 1, 4, 3, 2 with LDS-direct loads and a four-stage ring;
+ *   PREFILL_TILED:   `wp` is the TILED weight array of w4a8_tile_weights; output tile 1 = 256 x 256 as
+ *                    2 x 4 waves, 2 = 256 x 256 as 4 x 2 waves, 3 = 128 x 256, 4 = 128 x 160, 5 = 128 x 128.
  * Exactly one of out_fp16 / acc_i32 must be non-NULL (s_a and s_w may be NULL
  * when acc_i32 is requested).
  */
@@ -121,10 +124,29 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
                                          M <= 16 with K <= 16384, or M <= 32 with K <= 8192              */
 #define W4A8_TILING_DECODE_STREAM 2   /* general weight-streaming kernel, M <= 64                         */
 #define W4A8_TILING_PREFILL 3         /* LDS-staged output tiles on 32x32x32 int8 MFMA, for large M       */
+#define W4A8_TILING_PREFILL_TILED 4   /* the same over the tiled weight layout (any M; meant for large M)  */
 int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w,
                     void *out_fp16, int32_t *acc_i32, int M, int N, int K,
                     int tiling, int variant,
                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tiled weight layout for large M.  The weights are static, so, like the paper's offline weight format (Sec. 5.3),
+ * they may be reordered once after packing into the order in which the large-M kernel consumes them; every wave
+ * load then moves whole cache lines.  Same codes, same arithmetic, same results as the row-major array.
+ *   Layout of wt: 2048-byte blocks; block (nb, kb), nb = n / 32, kb = k / 128, starts at ((nb * KB) + kb) * 2048
+ *   with KB = ceil(K / 128).  Inside a block the 16-byte chunk (c, r), c = 0..3, r = 0..31, at (c * 32 + r) * 16
+ *   holds the 32 codes k = 128 kb + 32 c .. + 31 of channel 32 nb + r; a dword holds 8 consecutive codes k0..k7
+ *   as nibbles k0 k4 k1 k5 k2 k6 k3 k7 from the lowest to the highest.  Channels >= N and k >= K hold zero codes.
+ * w4a8_tiled_weight_bytes: size of wt in bytes (0 for a shape outside the contract).
+ * w4a8_tile_weights: wp [N][K/2] (device) in -> wt (device, 16-byte aligned, w4a8_tiled_weight_bytes(N, K)) out.
+ * w4a8_gemm_tiled: w4a8_gemm over wt instead of wp (all other arguments as there).  Every M is accepted; the
+ *   kernel behind it is the large-M one, so for M <= 64 w4a8_gemm on the row-major array is the faster call.
+ */
+size_t w4a8_tiled_weight_bytes(int N, int K);
+int w4a8_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, void *stream);
+int w4a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w,
+                    void *out_fp16, int M, int N, int K, void *stream);
 
 /*
  * Offline weight preparation on the device (Sec. 5.1 Eq. (8),(9) with 4 bits

@@ -14,7 +14,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw4a8.so")
 
-TILING_AUTO, TILING_DECODE_RESIDENT, TILING_DECODE_STREAM, TILING_PREFILL = 0, 1, 2, 3
+TILING_AUTO, TILING_DECODE_RESIDENT, TILING_DECODE_STREAM, TILING_PREFILL, TILING_PREFILL_TILED = 0, 1, 2, 3, 4
 
 _lib = None
 
@@ -48,8 +48,13 @@ def lib():
         L.w4a8_silu_mul.argtypes = [vp, vp, i, i, vp]
         L.w4a8_silu_mul_quantize.argtypes = [vp, vp, vp, i, i, vp]
         L.w4a8_pack_weights_host.argtypes = [vp, vp, i, i]
+        L.w4a8_tiled_weight_bytes.restype = sz
+        L.w4a8_tiled_weight_bytes.argtypes = [i, i]
+        L.w4a8_tile_weights.argtypes = [vp, vp, i, i, vp]
+        L.w4a8_gemm_tiled.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp]
         for name in ("w4a8_quantize_act", "w4a8_gemm", "w4a8_gemm_acc_i32", "w4a8_gemm_tuned",
-                     "w4a8_quantize_weights", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host"):
+                     "w4a8_quantize_weights", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host",
+                     "w4a8_tile_weights", "w4a8_gemm_tiled"):
             getattr(L, name).restype = i
         _lib = L
     return _lib
@@ -148,13 +153,18 @@ def w4a8_gemm_acc_i32(xq, wp, acc=None, ws=None):
     return acc
 
 
-def w4a8_gemm_tuned(xq, s_a, wp, s_w, tiling: int, variant: int = 0, want_acc: bool = False, out=None, ws=None):
-    """Forced tiling / variant; returns fp16 [M][N], or int32 [M][N] when want_acc."""
+def w4a8_gemm_tuned(xq, s_a, wp, s_w, tiling: int, variant: int = 0, want_acc: bool = False, out=None, ws=None, N=None):
+    """Forced tiling / variant; returns fp16 [M][N], or int32 [M][N] when want_acc.  With TILING_PREFILL_TILED, wp is
+    the flat tiled array of w4a8_tile_weights and N must be given."""
     torch = _torch()
     M, K = xq.shape
-    N = wp.shape[0]
-    if wp.shape[1] * 2 != K:
-        raise ValueError("shape mismatch")
+    if tiling == TILING_PREFILL_TILED:
+        if N is None or wp.numel() != w4a8_tiled_weight_bytes(N, K):
+            raise ValueError("tiled weights: N missing or array size mismatch")
+    else:
+        N = wp.shape[0]
+        if wp.shape[1] * 2 != K:
+            raise ValueError("shape mismatch")
     ws = workspace(M, N, K, xq.device) if ws is None else ws
     if want_acc:
         out = torch.empty((M, N), dtype=torch.int32, device=xq.device) if out is None else out
@@ -169,6 +179,39 @@ def w4a8_gemm_tuned(xq, s_a, wp, s_w, tiling: int, variant: int = 0, want_acc: b
         raise ValueError("out shape mismatch")
     _check(lib().w4a8_gemm_tuned(_dev(xq, torch.int8, "xq"), sa, _dev(wp, torch.uint8, "wp"), sw, o16, o32, M, N, K,
                                  tiling, variant, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
+    return out
+
+
+def w4a8_tiled_weight_bytes(N: int, K: int) -> int:
+    return int(lib().w4a8_tiled_weight_bytes(N, K))
+
+
+def w4a8_tile_weights(wp, wt=None):
+    """uint8 [N][K/2] packed int4 -> flat uint8 array in the tiled layout for large M."""
+    torch = _torch()
+    N, K = wp.shape[0], wp.shape[1] * 2
+    nbytes = w4a8_tiled_weight_bytes(N, K)
+    if nbytes == 0:
+        _check(-2)
+    wt = torch.empty((nbytes,), dtype=torch.uint8, device=wp.device) if wt is None else wt
+    if wt.numel() != nbytes:
+        raise ValueError("wt size mismatch")
+    _check(lib().w4a8_tile_weights(_dev(wp, torch.uint8, "wp"), _dev(wt, torch.uint8, "wt"), N, K, _stream()))
+    return wt
+
+
+def w4a8_gemm_tiled(xq, s_a, wt, s_w, out=None):
+    """int8 [M][K], fp32 [M], tiled weights of N = len(s_w) channels, fp32 [N] -> fp16 [M][N]."""
+    torch = _torch()
+    M, K = xq.shape
+    N = s_w.shape[0]
+    if wt.numel() != w4a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (N, K)")
+    out = torch.empty((M, N), dtype=torch.float16, device=xq.device) if out is None else out
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    _check(lib().w4a8_gemm_tiled(_dev(xq, torch.int8, "xq"), _dev(s_a, torch.float32, "s_a"), _dev(wt, torch.uint8, "wt"),
+                                 _dev(s_w, torch.float32, "s_w"), _dev(out, torch.float16, "out"), M, N, K, _stream()))
     return out
 
 

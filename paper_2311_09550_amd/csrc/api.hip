@@ -82,6 +82,28 @@ int choose_prefill_tile(int M, int N) {
     return best;
 }
 
+// Output tile of the kernel over the tiled weight layout: the 256 x 256 tile when it fills the chip, else the
+// smaller tile with the fewest rounds.
+int choose_tiled_tile(int M, int N) {
+    struct Option { int id, bm, bn, per_cu; double eff; };
+    const Option options[] = {{kTiled256x256, 256, 256, 1, 1.00},
+                              {kTiled128x256, 128, 256, 2, 0.90},
+                              {kTiled128x160, 128, 160, 2, 0.85},
+                              {kTiled128x128, 128, 128, 2, 0.80}};
+    const int cus = compute_units();
+    int best = kTiled256x256;
+    double best_cost = 0;
+    for (const Option &o : options) {
+        const long long tiles = (long long)((M + o.bm - 1) / o.bm) * ((N + o.bn - 1) / o.bn);
+        const long long slots = (long long)cus * o.per_cu;
+        const long long full = tiles / slots, rest = tiles % slots;
+        const double last = rest == 0 ? 0.0 : (o.per_cu == 1 || rest * 2 > slots ? 1.0 : 0.5);
+        const double cost = ((double)full + last) * o.bm * o.bn * o.per_cu / o.eff;
+        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = o.id; }
+    }
+    return best;
+}
+
 // Tiling choice.  Small M streams the weights once (HBM bound); large M goes to the LDS-staged tiling
 // (matrix-core bound).  `variant` refines a forced tiling (see w4a8.h); 0 lets the library choose.
 int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
@@ -105,6 +127,9 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
         if ((s.row_tiles != 1 && s.row_tiles != 2) || (s.waves != 4 && s.waves != 8)) return W4A8_ERR_ARG;
         if (mt == 4 && s.row_tiles == 2 && s.waves == 8) return W4A8_ERR_ARG;  // would not fit in LDS
         pl->decode = s;
+    } else if (pl->tiling == W4A8_TILING_PREFILL_TILED) {
+        if (variant < 0 || variant > kTiledTileMax) return W4A8_ERR_ARG;
+        pl->prefill_tile = variant ? variant : choose_tiled_tile(M, N);
     } else {
         if (variant < 0 || variant > kPrefillTileMax) return W4A8_ERR_ARG;
         pl->prefill_tile = variant ? variant : choose_prefill_tile(M, N);
@@ -119,7 +144,7 @@ int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float 
     if (!xq || !wp) return W4A8_ERR_NULL;
     if (!want_acc && (!s_a || !s_w)) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, N, K)) return e;
-    if (tiling < W4A8_TILING_AUTO || tiling > W4A8_TILING_PREFILL || variant < 0) return W4A8_ERR_ARG;
+    if (tiling < W4A8_TILING_AUTO || tiling > W4A8_TILING_PREFILL_TILED || variant < 0) return W4A8_ERR_ARG;
     if (misaligned(xq) || misaligned(wp) || misaligned(out_fp16) || misaligned(acc_i32) || (s_w && misaligned(s_w)))
         return W4A8_ERR_ALIGN;
 
@@ -127,7 +152,13 @@ int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float 
     if (int e = choose_plan(M, N, K, tiling, variant, &pl)) return e;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t err;
-    if (pl.tiling != W4A8_TILING_PREFILL) {
+    if (pl.tiling == W4A8_TILING_PREFILL_TILED) {
+        PrefillArgs a{};
+        a.xq = xq; a.s_a = s_a; a.wp = wp; a.s_w = s_w;
+        a.out = out_fp16; a.acc_out = acc_i32;
+        a.M = M; a.N = N; a.K = K; a.ldc = N;
+        err = launch_gemm_prefill_tiled(a, want_acc, pl.prefill_tile, st);
+    } else if (pl.tiling != W4A8_TILING_PREFILL) {
         DecodeArgs a{};
         a.xq = xq; a.s_a = s_a; a.wp = wp; a.s_w = s_w;
         a.out = out_fp16; a.acc_out = acc_i32;
@@ -196,6 +227,24 @@ int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const
                     void *stream) {
     (void)workspace; (void)workspace_bytes;
     return run_gemm(xq, s_a, wp, s_w, out_fp16, acc_i32, M, N, K, tiling, variant, stream);
+}
+
+size_t w4a8_tiled_weight_bytes(int N, int K) {
+    if (check_gemm_shape(1, N, K)) return 0;
+    return tiled_weight_bytes(N, K);
+}
+
+int w4a8_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, void *stream) {
+    if (!wp || !wt) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(1, N, K)) return e;
+    if (misaligned(wp) || misaligned(wt)) return W4A8_ERR_ALIGN;
+    return launch_tile_weights(wp, wt, N, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+}
+
+int w4a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16, int M, int N,
+                    int K, void *stream) {
+    if (!out_fp16) return W4A8_ERR_NULL;
+    return run_gemm(xq, s_a, wt, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_PREFILL_TILED, 0, stream);
 }
 
 int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, int K, void *stream) {

@@ -1,0 +1,396 @@
+// W4A8 GEMM for large M over weights in the tiled layout, and the kernel that produces that layout.
+//
+// Why another layout: for large M the kernel is bound by how fast a compute unit can pull its operand tiles out of
+// L2.  A wave-wide 16-byte-per-lane load that touches 16 or 32 different cache lines (what a k slice of a row-major
+// operand amounts to) moves well under half the bytes per cycle of one that touches 8 whole lines.  The activations
+// can be read in whole lines as they are (a stage is 128 k = one 128-byte line per row).  The packed weights cannot
+// (128 k of a row are 64 bytes), but they are static, so they are reordered once, after quantisation (the paper also
+// fixes the weight format offline, Sec. 5.3), into 2 KB blocks that a stage consumes whole:
+//
+//   block (nb, kb) = output channels 32 nb .. 32 nb + 31, k = 128 kb .. 128 kb + 127, at byte ((nb * KB) + kb) * 2048,
+//                    KB = ceil(K / 128); rows past N and k past K hold zero codes;
+//   inside a block: 16-byte chunk (c, r), c = 0..3, r = 0..31, at (c * 32 + r) * 16 holds the 32 codes
+//                    k = 128 kb + 32 c .. + 31 of channel 32 nb + r;
+//   inside a dword (8 codes k0..k7): nibbles, low to high, hold k0 k4 k1 k5 k2 k6 k3 k7, so that
+//                    (w << 4) & 0xF0F0F0F0 is {16 k0 .. 16 k3} and w & 0xF0F0F0F0 is {16 k4 .. 16 k7} as int8:
+//                    the conversion of Fig. 4(c) then lands in the activations' natural k order and the
+//                    activation bytes need no shuffling at all.
+//
+// The 32 lanes of an MFMA operand read 512 consecutive bytes of a block: no LDS bank conflicts, no swizzle.
+//
+// Kernel structure: a ring of STAGES stages of 128 k in LDS, filled by LDS-direct buffer loads (1 KB per wave
+// instruction: 8 activation rows x 128 B, or half a weight block).  Stage t + STAGES is requested as soon as every
+// wave has taken its last fragment of stage t, so STAGES - 1 stages are in flight while one is being multiplied.
+// One workgroup barrier per stage; fragments for the next MFMA step are always read during the current one.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace w4a8 {
+
+namespace {
+
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+constexpr int kStageK = kTiledBlockK;
+
+__device__ __forceinline__ v16i mfma32(v4i a, v4i b, v16i c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
+
+// Swizzle of the eight 16-byte slots of a 128-byte activation row in LDS: 8 as well as 16 consecutive rows reading
+// the same logical slot fall into different banks.
+__device__ __forceinline__ int fx(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Two dwords of the tiled layout (16 codes) -> one MFMA operand: int8 values 16 * w in the natural k order.
+__device__ __forceinline__ v4i w_operand_tiled(unsigned w0, unsigned w1) {
+    v4i r;
+    r.x = (int)((w0 << 4) & 0xF0F0F0F0u);
+    r.y = (int)(w0 & 0xF0F0F0F0u);
+    r.z = (int)((w1 << 4) & 0xF0F0F0F0u);
+    r.w = (int)(w1 & 0xF0F0F0F0u);
+    return r;
+}
+
+// nibbles k0..k7 of a row-major dword -> k0 k4 k1 k5 k2 k6 k3 k7
+__device__ __forceinline__ unsigned interleave_nibbles(unsigned w) {
+    unsigned lo = w & 0xFFFFu, hi = w >> 16;
+    lo = (lo | (lo << 8)) & 0x00FF00FFu;
+    lo = (lo | (lo << 4)) & 0x0F0F0F0Fu;
+    hi = (hi | (hi << 8)) & 0x00FF00FFu;
+    hi = (hi | (hi << 4)) & 0x0F0F0F0Fu;
+    return lo | (hi << 4);
+}
+
+// One thread per 16-byte chunk of the tiled array.
+__global__ __launch_bounds__(256) void tile_weights_kernel(const uint8_t *__restrict__ wp, uint8_t *__restrict__ wt, int N,
+                                                           int K, int kb_total, long long chunks) {
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= chunks) return;
+    const long long block = q >> 7;
+    const int c = (int)(q & 127) >> 5, r = (int)(q & 31);
+    const long long nb = block / kb_total;
+    const int kb = (int)(block - nb * kb_total);
+    const long long n = nb * 32 + r;
+    const int byte0 = kb * 64 + c * 16;  // within the row of K / 2 bytes
+    v4u v = v4u{0u, 0u, 0u, 0u};
+    if (n < N && byte0 < (K >> 1)) {
+        v = *(const v4u *)(wp + (size_t)n * (size_t)(K >> 1) + byte0);
+        v.x = interleave_nibbles(v.x);
+        v.y = interleave_nibbles(v.y);
+        v.z = interleave_nibbles(v.z);
+        v.w = interleave_nibbles(v.w);
+    }
+    *(v4u *)(wt + (size_t)q * 16) = v;
+}
+
+}  // namespace
+
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT>
+__global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(PrefillArgs p) {
+    constexpr int kWaves = WM * WN;
+    constexpr int BM = 32 * MTW * WM;
+    constexpr int BN = 32 * NTW * WN;
+    constexpr int A_TOTAL = BM / 8;   // wave loads (8 rows x 128 B) of an activation stage
+    constexpr int B_TOTAL = BN / 16;  // wave loads (half a 2 KB block) of a weight stage
+    static_assert(A_TOTAL % kWaves == 0 && (kWaves & 1) == 0, "activation loads must split evenly over an even wave count");
+    constexpr int A_LOADS = A_TOTAL / kWaves;
+    constexpr int B_LOADS = (B_TOTAL + kWaves - 1) / kWaves;
+    constexpr bool kRagged = B_LOADS * kWaves != B_TOTAL;
+    constexpr int kLoads = A_LOADS + B_LOADS;  // per wave and stage, the same for every wave: the waits count on it
+    constexpr int A_STAGE = BM * 128;
+    constexpr int B_STAGE = BN * 64;
+    constexpr int kBBase = STAGES * A_STAGE;
+    constexpr int kSpare = STAGES * (A_STAGE + B_STAGE);  // 1 KB that absorbs the surplus loads of an uneven split
+    static_assert(STAGES >= 2 && (STAGES - 1) * kLoads < 64, "outstanding loads must fit the counter");
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN;
+    const int wn = wave % WN;
+    const int idx = lane & 31;
+    const int g = lane >> 5;
+
+    // XCD-aware tile order: workgroup ids go round-robin over the 8 XCDs; consecutive tiles of one XCD share
+    // their weight panel, so it is fetched into that XCD's L2 once
+    const int total = p.tiles_m * p.tiles_n;
+    const int per_xcd = (total + 7) >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total) return;
+    const int tile_n = logical / p.tiles_m;
+    const int tile_m = logical - tile_n * p.tiles_m;
+    const int bm0 = tile_m * BM;
+    const int bn0 = tile_n * BN;
+
+    const int st_total = (p.K + kStageK - 1) / kStageK;
+    const int k_last = (st_total - 1) * kStageK;
+    const int nb_total = (p.N + 31) >> 5;
+
+    constexpr unsigned kNowhere = 0xFFFFFFF0u;  // beyond every buffer: such a lane fetches nothing and delivers zeros
+    auto make_rsrc = [](const void *base, size_t bytes) {
+        const unsigned long long b = (unsigned long long)base;
+        v4i r;
+        r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)b);
+        r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)((b >> 32) & 0xFFFFu));
+        r.z = __builtin_amdgcn_readfirstlane((int)(unsigned)bytes);
+        r.w = 0x00020000;
+        return r;
+    };
+    const v4i a_rsrc = make_rsrc(p.xq, (size_t)p.M * p.K);
+    const v4i b_rsrc = make_rsrc(p.wp, (size_t)nb_total * st_total * kTiledBlockBytes);
+
+    // Activation wave load L covers rows 8L .. 8L+7: lane -> row 8L + lane/8, physical slot lane%8, which receives
+    // the logical chunk slot ^ fx(row).  With an even wave count fx(row) is the same for all loads of a lane.
+    const int a_chunk = (lane & 7) ^ fx(8 * wave + (lane >> 3));
+    const bool a_last_ok = k_last + a_chunk * 16 < p.K;
+    unsigned a_off[A_LOADS], b_off[B_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
+        const int m = bm0 + 8 * (i * kWaves + wave) + (lane >> 3);
+        a_off[i] = m < p.M ? (unsigned)m * (unsigned)p.K + a_chunk * 16 : kNowhere;
+    }
+    // Weight wave load L covers half L%2 of the tile's 32-channel block L/2.
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) {
+        const int L = i * kWaves + wave;
+        const int nb = (bn0 >> 5) + (L >> 1);
+        b_off[i] = (L < B_TOTAL && nb < nb_total) ? ((unsigned)nb * (unsigned)st_total * 2 + (L & 1)) * 1024u + lane * 16 : kNowhere;
+    }
+
+    // The load is written in assembly on purpose: the compiler orders LDS reads after every LDS-writing load it knows
+    // of (it cannot tell the ring slots apart) and would wait for the stage just requested before each fragment read.
+    // Here the ordering is explicit instead: wait_vmcnt + barrier before a slot is read, barrier before it is refilled.
+    auto dma16 = [](const v4i &rsrc, unsigned lds_addr, unsigned voffset, int soffset) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+                     : "memory", "m0");
+    };
+    const unsigned lds_base = (unsigned)(unsigned long long)(lds_ptr_t)lds;
+    auto issue = [&](int st, int slot) {
+        const bool last = st + 1 >= st_total;
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i)
+            dma16(a_rsrc, __builtin_amdgcn_readfirstlane(lds_base + slot * A_STAGE + (i * kWaves + wave) * 1024),
+                  (last && !a_last_ok) ? kNowhere : a_off[i], st * kStageK);
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i) {
+            const int L = i * kWaves + wave;
+            const unsigned dst = (kRagged && L >= B_TOTAL) ? kSpare : kBBase + slot * B_STAGE + L * 1024;
+            dma16(b_rsrc, __builtin_amdgcn_readfirstlane(lds_base + dst), b_off[i], st * kTiledBlockBytes);
+        }
+    };
+
+    v16i acc[MTW][NTW];
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+        for (int t = 0; t < NTW; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][t][v] = 0;
+
+    // LDS offsets of this lane's fragments inside a stage.  MFMA step j = 0..3 of a stage covers k = 32 j .. 32 j + 31;
+    // lane (idx, g) supplies k = 32 j + 16 g .. + 15: activation chunk 2 j + g of its row, and dwords 2 (j % 2), +1
+    // of weight chunk ... (the weight chunk c = 32 k holds two steps: c = j / 2 ... see read_w).
+    // Steps are numbered so that one weight chunk serves two consecutive steps: step j uses weight chunk
+    // 2 (j / 2) + g, dwords 2 (j % 2) and 2 (j % 2) + 1, i.e. k = 64 (j/2) + 32 g + 16 (j%2) .. + 15, and the
+    // activation chunk with the same k: 4 (j / 2) + 2 g + (j % 2).
+    int xa[4];
+    {
+        const int row = wm * (32 * MTW) + idx;  // rows of the other m tiles differ by 32: same swizzle
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xa[j] = row * 128 + (((4 * (j >> 1) + 2 * g + (j & 1)) ^ fx(row)) << 4);
+    }
+    const int wa = kBBase + wn * (NTW * 2048) + (g * 32 + idx) * 16;
+    auto read_x = [&](v4u(&dst)[MTW], int slot, int j) {
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) dst[mt] = *(const v4u *)(&lds[slot * A_STAGE + xa[j] + mt * 4096]);
+    };
+    auto read_w = [&](v4u(&dst)[NTW], int slot, int s) {
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) dst[t] = *(const v4u *)(&lds[slot * B_STAGE + wa + t * 2048 + s * 1024]);
+    };
+    auto mfma_step = [&](const v4u(&x)[MTW], const v4u(&w)[NTW], int h) {
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) {
+            const v4i wop = h == 0 ? w_operand_tiled(w[t].x, w[t].y) : w_operand_tiled(w[t].z, w[t].w);
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+                acc[mt][t] = mfma32(wop, v4i{(int)x[mt].x, (int)x[mt].y, (int)x[mt].z, (int)x[mt].w}, acc[mt][t]);
+        }
+    };
+
+    // Prologue: the first STAGES stages go out; stage 0 must have landed, in every wave, before the first read.
+    // Loads return in order, so "at most n outstanding" means all but the youngest n have landed; waiting for fewer
+    // than could be allowed is always safe, which is what happens near the end of K.
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s)
+        if (s < st_total) issue(s, s);
+    if (st_total >= STAGES)
+        wait_vmcnt<(STAGES - 1) * kLoads>();
+    else
+        wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+
+    v4u x0[MTW], x1[MTW], w0[NTW], w1[NTW];
+    read_x(x0, 0, 0);
+    read_w(w0, 0, 0);
+    int slot = 0;
+    for (int st = 0; st < st_total; ++st) {
+        const int next = slot + 1 == STAGES ? 0 : slot + 1;
+        read_x(x1, slot, 1);
+        mfma_step(x0, w0, 0);
+        read_x(x0, slot, 2);
+        read_w(w1, slot, 1);
+        mfma_step(x1, w0, 1);
+        read_x(x1, slot, 3);
+        mfma_step(x0, w1, 0);
+        // Every fragment of this stage is in registers once the reads above have returned (the release fence waits
+        // for them), so after the barrier the slot can be refilled; stage st + 1 must be in LDS for every wave.
+        if (st + STAGES <= st_total)
+            wait_vmcnt<(STAGES - 2) * kLoads>();  // stages st + 2 .. st + STAGES - 1 may still be in flight
+        else
+            wait_vmcnt<0>();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        if (st + STAGES < st_total) issue(st + STAGES, slot);
+        if (st + 1 < st_total) {
+            read_x(x0, next, 0);
+            read_w(w0, next, 0);
+        }
+        mfma_step(x1, w1, 1);
+        slot = next;
+    }
+    wait_vmcnt<0>();
+
+    // epilogue: lane holds, per (mt, t, quad), four consecutive n of one m
+    const bool vec_ok = (p.ldc & 3) == 0;
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
+        const int m = bm0 + wm * (32 * MTW) + 32 * mt + idx;
+        if (m >= p.M) continue;
+        const float sa = ACC_OUT ? 0.f : p.s_a[m];
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = bn0 + wn * (32 * NTW) + 32 * t + 8 * q + 4 * g;
+                if (n >= p.N) continue;
+                const v4i s = v4i{acc[mt][t][4 * q], acc[mt][t][4 * q + 1], acc[mt][t][4 * q + 2], acc[mt][t][4 * q + 3]};
+                if (ACC_OUT) {
+                    int *dst = p.acc_out + (size_t)m * p.ldc + n;
+                    const v4i v = v4i{s.x >> 4, s.y >> 4, s.z >> 4, s.w >> 4};  // exact: every sum is a multiple of 16
+                    if (vec_ok && n + 3 < p.N) {
+                        *(v4i *)dst = v;
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (n + j < p.N) dst[j] = v[j];
+                    }
+                } else {
+                    unsigned short *dst = (unsigned short *)p.out + (size_t)m * p.ldc + n;
+                    if (vec_ok && n + 3 < p.N) {
+                        const float4 sw = *(const float4 *)(p.s_w + n);
+                        v2u o;
+                        o.x = pack_f16x2(dequant(s.x, sa, sw.x), dequant(s.y, sa, sw.y));
+                        o.y = pack_f16x2(dequant(s.z, sa, sw.z), dequant(s.w, sa, sw.w));
+                        *(v2u *)dst = o;
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (n + j < p.N) dst[j] = f32_to_f16_bits(dequant(s[j], sa, p.s_w[n + j]));
+                    }
+                }
+            }
+        }
+    }
+}
+
+namespace {
+
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT>
+hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
+    constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
+    constexpr int kLdsBytes = STAGES * (BM * 128 + BN * 64) + 1024;
+    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT>;
+    // more than 64 KB of LDS per workgroup has to be asked for, once per device
+    static bool raised[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!raised[dev]) {
+        const hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        raised[dev] = true;
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN), kLdsBytes, stream, p);
+    return hipGetLastError();
+}
+
+template <int MTW, int NTW, int WM, int WN, int STAGES>
+hipError_t launch_tile(PrefillArgs p, bool acc_out, hipStream_t stream) {
+    constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    const int total = p.tiles_m * p.tiles_n;
+    const dim3 grid(8 * ((total + 7) / 8));
+    return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true>(p, grid, stream)
+                   : launch_one<MTW, NTW, WM, WN, STAGES, false>(p, grid, stream);
+}
+
+}  // namespace
+
+hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream) {
+    // slices keep every byte offset inside the kernel below 2^32; slices of N start on a 32-channel block
+    const long long kMaxBytes = 0xF0000000ll;
+    const long long kb_total = (p.K + kTiledBlockK - 1) / kTiledBlockK;
+    long long m_rows = kMaxBytes / p.K, n_rows = kMaxBytes / (kb_total * (kTiledBlockK / 2));
+    m_rows -= m_rows % 256;
+    n_rows -= n_rows % 1280;  // a multiple of every tile width
+    for (long long n0 = 0; n0 < p.N; n0 += n_rows) {
+        for (long long m0 = 0; m0 < p.M; m0 += m_rows) {
+            PrefillArgs q = p;
+            q.M = (int)((p.M - m0) < m_rows ? (p.M - m0) : m_rows);
+            q.N = (int)((p.N - n0) < n_rows ? (p.N - n0) : n_rows);
+            q.xq = p.xq + (size_t)m0 * p.K;
+            q.wp = p.wp + (size_t)(n0 / 32) * (size_t)kb_total * kTiledBlockBytes;
+            if (p.s_a) q.s_a = p.s_a + m0;
+            if (p.s_w) q.s_w = p.s_w + n0;
+            if (p.out) q.out = (unsigned short *)p.out + (size_t)m0 * p.ldc + n0;
+            if (p.acc_out) q.acc_out = p.acc_out + (size_t)m0 * p.ldc + n0;
+            hipError_t e;
+            switch (tile) {
+                case kTiled256x256: e = launch_tile<4, 2, 2, 4, 3>(q, acc_out, stream); break;
+                case kTiled256x256Square: e = launch_tile<2, 4, 4, 2, 3>(q, acc_out, stream); break;
+                case kTiled128x256: e = launch_tile<4, 2, 1, 4, 2>(q, acc_out, stream); break;
+                case kTiled128x160: e = launch_tile<1, 5, 4, 1, 3>(q, acc_out, stream); break;
+                case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3>(q, acc_out, stream); break;
+                default: e = hipErrorInvalidConfiguration;
+            }
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
+size_t tiled_weight_bytes(int N, int K) {
+    return (size_t)((N + 31) / 32) * (size_t)((K + kTiledBlockK - 1) / kTiledBlockK) * kTiledBlockBytes;
+}
+
+hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream) {
+    const int kb_total = (K + kTiledBlockK - 1) / kTiledBlockK;
+    const long long chunks = (long long)(tiled_weight_bytes(N, K) / 16);
+    const long long blocks = (chunks + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tile_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, wp, wt, N, K, kb_total, chunks);
+    return hipGetLastError();
+}
+
+}  // namespace w4a8

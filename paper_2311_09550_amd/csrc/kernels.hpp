@@ -56,6 +56,21 @@ constexpr int kPrefillDma128x160 = 7;
 constexpr int kPrefillDma128x128 = 8;
 constexpr int kPrefillTileMax = 8;
 
+// Tiled weight layout (see gemm_prefill_tiled.hip): 2 KB blocks of 32 output channels x 128 k
+constexpr int kTiledBlockK = 128;
+constexpr int kTiledBlockBytes = 2048;
+// output tiles of the kernel that reads the tiled layout (PrefillArgs::wp then points to the tiled array)
+constexpr int kTiled256x256 = 1;        // 8 waves of 128 x 64, one workgroup per compute unit
+constexpr int kTiled256x256Square = 2;  // 8 waves of 64 x 128
+constexpr int kTiled128x256 = 3;        // 4 waves of 128 x 64, two-stage ring, two workgroups per compute unit
+constexpr int kTiled128x160 = 4;        // 4 waves of 32 x 160
+constexpr int kTiled128x128 = 5;        // 4 waves of 64 x 64
+constexpr int kTiledTileMax = 5;
+
+size_t tiled_weight_bytes(int N, int K);
+hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream);
+hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
+
 hipError_t launch_gemm_prefill(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
 hipError_t launch_prefill_dma_slice(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
 
