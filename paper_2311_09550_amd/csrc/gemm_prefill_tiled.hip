@@ -371,8 +371,7 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
                 case kTiled256x256Square: e = launch_tile<2, 4, 4, 2, 3>(q, acc_out, stream); break;
                 case kTiled128x256: e = launch_tile<4, 2, 1, 4, 2>(q, acc_out, stream); break;
                 case kTiled128x160: e = launch_tile<1, 5, 4, 1, 3>(q, acc_out, stream); break;
-                case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3>(q, acc_out, stream); break;
-                default: e = hipErrorInvalidConfiguration;
+                case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3>(q, acc_out, stream); break;                default: e = hipErrorInvalidConfiguration;
             }
             if (e != hipSuccess) return e;
         }
