@@ -43,6 +43,14 @@ def gemm_ops(M, N, K):
     return 2 * M * N * K
 
 
+COPY_CALIBRATION_BYTES = 256 << 20
+# L2 fill + write-back bytes per GEMM launch of the default workload (mean over its four linears), from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/gemm_prefill_tiled_13b_traffic.md, each scaled by
+# what the counter reads for the 256 MiB copy of --copy-calibration.  Counters cannot be read from inside this
+# process, so the figure is carried here and reported only for the workload it was measured on.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("13b", 1024): 158.9e6}
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +60,9 @@ def parse_args():
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1,4,16 weight-streaming measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy three times: the dispatch of known size against which "
+                         "hardware traffic counters are scaled")
     return ap.parse_args()
 
 
@@ -204,6 +215,13 @@ def main():
     w4a8.lib()
     torch.cuda.set_device(0)
     M = args.M
+    if args.copy_calibration:
+        src = torch.full((COPY_CALIBRATION_BYTES,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     stack = LayerStack(torch, w4a8, synth, M)
     for _ in range(args.warmup):
         stack.step()
@@ -226,7 +244,9 @@ def main():
     ops_per_launch = stack.ops_per_step() / len(per)
     achieved = ops_per_launch / avg_us / 1e6   # TOPS
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": None,
+                "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(("13b", M)),
+                "traffic_unit": "bytes per launch (L2 fills + write-backs)",
+                "algorithmic_bytes_per_launch": round(sum(gemm_bytes(M, N, K) for N, K in stack.shapes.values()) / len(per)),
                 "kernel": "gemm_prefill_tiled_kernel", "avg_launch_us": round(avg_us, 2),
                 "per_linear_us": {k: round(v, 2) for k, v in gemm_us.items()},
                 "per_linear_tops": {k: round(gemm_ops(M, *stack.shapes[k]) / v / 1e6, 1) for k, v in gemm_us.items()}}
