@@ -245,19 +245,31 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     int slot = 0;
     for (int st = 0; st < st_total; ++st) {
         const int next = slot + 1 == STAGES ? 0 : slot + 1;
+        // The scheduling fences keep each block of LDS reads in front of the MFMA block it overlaps with; left alone
+        // the compiler sinks the reads next to their first use and every step then starts with an exposed LDS wait.
+        // The fragments of step 0 were requested eight MFMAs ago; waiting for them here, before the next reads go
+        // out, costs nothing and spares the wait the compiler would otherwise place behind those reads.
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         read_x(x1, slot, 1);
+        __builtin_amdgcn_sched_barrier(0);
         mfma_step(x0, w0, 0);
+        __builtin_amdgcn_sched_barrier(0);
         read_x(x0, slot, 2);
         read_w(w1, slot, 1);
+        __builtin_amdgcn_sched_barrier(0);
         mfma_step(x1, w0, 1);
+        __builtin_amdgcn_sched_barrier(0);
         read_x(x1, slot, 3);
+        __builtin_amdgcn_sched_barrier(0);
         mfma_step(x0, w1, 0);
+        __builtin_amdgcn_sched_barrier(0);
         // Every fragment of this stage is in registers once the reads above have returned (the release fence waits
         // for them), so after the barrier the slot can be refilled; stage st + 1 must be in LDS for every wave.
         if (st + STAGES <= st_total)
             wait_vmcnt<(STAGES - 2) * kLoads>();  // stages st + 2 .. st + STAGES - 1 may still be in flight
         else
             wait_vmcnt<0>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's last fragment reads of the slot have returned
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
@@ -266,12 +278,76 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
             read_x(x0, next, 0);
             read_w(w0, next, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
         mfma_step(x1, w1, 1);
+        __builtin_amdgcn_sched_barrier(0);
         slot = next;
     }
     wait_vmcnt<0>();
 
-    // epilogue: lane holds, per (mt, t, quad), four consecutive n of one m
+    // Epilogue (Eq. (6),(7)).  A lane holds, per (mt, t, quad), four consecutive n of one m, so storing from the
+    // accumulator layout writes 16 bytes into each of 32 different rows per instruction.  Instead every wave turns
+    // its 32-row slabs around in LDS (the ring is idle now: the last barrier of the loop lies behind every wave's
+    // last fragment read and every load has landed) and stores whole 16-byte runs of 8 channels, 8 or more lanes per
+    // row, i.e. whole cache lines.
+    if (!ACC_OUT && (p.ldc & 7) == 0) {
+        constexpr int kRowBytes = 64 * NTW;        // fp16 bytes of a slab row (32 NTW channels)
+        constexpr int kPitch = kRowBytes + 16;     // padded: rows 16 apart, not 1 apart, share banks
+        constexpr int kChunksPerRow = 4 * NTW;     // 16-byte chunks
+        constexpr int kReads = (32 * kChunksPerRow + 63) / 64;
+        static_assert(kWaves * 32 * kPitch <= STAGES * (A_STAGE + B_STAGE), "slabs must fit the ring");
+        uint8_t *slab = lds + wave * (32 * kPitch);
+        const int n_wave = bn0 + wn * (32 * NTW);
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+            const int m_slab = bm0 + wm * (32 * MTW) + 32 * mt;
+            const int m = m_slab + idx;
+            const float sa = m < p.M ? p.s_a[m] : 0.f;
+#pragma unroll
+            for (int t = 0; t < NTW; ++t) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int nl = 32 * t + 8 * q + 4 * g;
+                    const int n = n_wave + nl;
+                    float4 sw;
+                    if (n + 3 < p.N) {
+                        sw = *(const float4 *)(p.s_w + n);
+                    } else {  // values past N are formed but never stored; keep their scale reads in bounds
+                        const int last = p.N - 1;
+                        sw.x = p.s_w[n < last ? n : last];
+                        sw.y = p.s_w[n + 1 < last ? n + 1 : last];
+                        sw.z = p.s_w[n + 2 < last ? n + 2 : last];
+                        sw.w = p.s_w[last];
+                    }
+                    v2u o;
+                    o.x = pack_f16x2(dequant(acc[mt][t][4 * q], sa, sw.x), dequant(acc[mt][t][4 * q + 1], sa, sw.y));
+                    o.y = pack_f16x2(dequant(acc[mt][t][4 * q + 2], sa, sw.z), dequant(acc[mt][t][4 * q + 3], sa, sw.w));
+                    *(v2u *)(slab + idx * kPitch + nl * 2) = o;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kReads; ++j) {
+                const int c = j * 64 + lane;
+                const int row = c / kChunksPerRow, col = c - row * kChunksPerRow;
+                if (32 * kChunksPerRow % 64 != 0 && row >= 32) continue;
+                const v4u v = *(const v4u *)(slab + row * kPitch + col * 16);
+                const int mm = m_slab + row, n = n_wave + col * 8;
+                if (mm >= p.M || n >= p.N) continue;
+                unsigned short *dst = (unsigned short *)p.out + (size_t)mm * p.ldc + n;
+                if (n + 8 <= p.N) {
+                    *(v4u *)dst = v;
+                } else {
+                    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < p.N) dst[e] = (unsigned short)(w[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        return;
+    }
+
+    // general epilogue: raw sums, or an output pitch that rules out 16-byte stores
     const bool vec_ok = (p.ldc & 3) == 0;
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt) {

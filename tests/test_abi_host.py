@@ -90,6 +90,20 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_silu_mul(p, p, 1, 12, null) == -2
     assert L.w4a8_silu_mul_quantize(p, null, p, 1, 32, null) == -1
     assert L.w4a8_silu_mul_quantize(p, p, p, 1, 24, null) == -2
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 4, 6, p, big, null) == -7       # tiled layout: unknown tile id
+    assert L.w4a8_tile_weights(null, p, 32, 128, null) == -1
+    assert L.w4a8_tile_weights(p, p, 32, 100, null) == -2
+    assert L.w4a8_tile_weights(p, odd, 32, 128, null) == -3
+    assert L.w4a8_gemm_tiled(p, p, p, p, null, 1, 16, 32, null) == -1
+    assert L.w4a8_gemm_tiled(p, p, p, p, p, 1, 16, 48, null) == -2
+
+
+def test_tiled_weight_bytes_counts_whole_blocks(L):
+    f = w4a8.w4a8_tiled_weight_bytes
+    assert f(32, 128) == 2048 and f(1, 32) == 2048 and f(33, 160) == 4 * 2048
+    assert f(15360, 5120) == 15360 * 5120 // 2            # whole blocks: same size as the row-major array
+    assert f(5120, 13824) == 5120 * 13824 // 2
+    assert f(16, 48) == 0 and f(0, 128) == 0              # outside the contract
 
 
 def test_host_packing_matches_oracle_and_rejects_bad_codes(L, oracle):
