@@ -65,7 +65,7 @@ bool resident_shape(int M, int N, int K, int waves, int grid, DecodeShape *out) 
 int choose_prefill_tile(int M, int N) {
     struct Option { int id, bm, bn, per_cu; double eff; };
     const Option options[] = {{kPrefillTile128x256, 128, 256, 2, 1.00},
-                              {kPrefillDma128x160, 128, 160, 2, 0.85},  // the LDS-direct variant is the faster 128 x 160
+                              {kPrefillDma128x160, 128, 160, 2, 0.80},  // the LDS-direct variant is the faster 128 x 160
                               {kPrefillTile128x128, 128, 128, 3, 0.78}};
     const int cus = compute_units();
     int best = kPrefillTile128x256;
@@ -83,15 +83,16 @@ int choose_prefill_tile(int M, int N) {
 }
 
 // Output tile of the kernel over the tiled weight layout, by the same estimate.  Measured on LLaMA-13B shapes at
-// M = 1024 and 4096: two 128 x 256 workgroups per compute unit beat one 256 x 256 workgroup everywhere, so the large
-// tiles stay variants for sweeps; the narrower tiles win when N is too small to fill the chip with 128 x 256.
+// M = 1024 and 4096: one 256 x 256 workgroup per compute unit wins when its tiles fill the chip in whole rounds,
+// two 128 x 256 workgroups otherwise, the narrower tiles when N is too small for either.
 int choose_tiled_tile(int M, int N) {
     struct Option { int id, bm, bn, per_cu; double eff; };
-    const Option options[] = {{kTiled128x256, 128, 256, 2, 1.00},
-                              {kTiled128x160, 128, 160, 2, 0.80},
-                              {kTiled128x128, 128, 128, 2, 0.78}};
+    const Option options[] = {{kTiled256x256, 256, 256, 1, 1.00},
+                              {kTiled128x256, 128, 256, 2, 0.93},
+                              {kTiled128x160, 128, 160, 2, 0.75},
+                              {kTiled128x128, 128, 128, 2, 0.75}};
     const int cus = compute_units();
-    int best = kTiled128x256;
+    int best = kTiled256x256;
     double best_cost = 0;
     for (const Option &o : options) {
         const long long tiles = (long long)((M + o.bm - 1) / o.bm) * ((N + o.bn - 1) / o.bn);

@@ -112,7 +112,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps LDS addresses in scalar registers
     const int wm = wave / WN;
     const int wn = wave % WN;
     const int idx = lane & 31;
@@ -173,18 +173,22 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                      : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
                      : "memory", "m0");
     };
-    const unsigned lds_base = (unsigned)(unsigned long long)(lds_ptr_t)lds;
-    auto issue = [&](int st, int slot) {
+    const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)(lds_ptr_t)lds);
+    // loads j = part, part + parts, ... of the kLoads loads of stage st (activation loads first), into ring slot `slot`
+    auto issue = [&](int st, int slot, int part, int parts) {
         const bool last = st + 1 >= st_total;
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i)
-            dma16(a_rsrc, __builtin_amdgcn_readfirstlane(lds_base + slot * A_STAGE + (i * kWaves + wave) * 1024),
-                  (last && !a_last_ok) ? kNowhere : a_off[i], st * kStageK);
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) {
-            const int L = i * kWaves + wave;
-            const unsigned dst = (kRagged && L >= B_TOTAL) ? kSpare : kBBase + slot * B_STAGE + L * 1024;
-            dma16(b_rsrc, __builtin_amdgcn_readfirstlane(lds_base + dst), b_off[i], st * kTiledBlockBytes);
+        for (int j = 0; j < kLoads; ++j) {
+            if (j % parts != part) continue;
+            if (j < A_LOADS) {
+                dma16(a_rsrc, lds_base + slot * A_STAGE + (j * kWaves + wave) * 1024,
+                      (last && !a_last_ok) ? kNowhere : a_off[j], st * kStageK);
+            } else {
+                const int i = j - A_LOADS;
+                const int L = i * kWaves + wave;
+                const unsigned dst = (kRagged && L >= B_TOTAL) ? kSpare : kBBase + slot * B_STAGE + L * 1024;
+                dma16(b_rsrc, lds_base + dst, b_off[i], st * kTiledBlockBytes);
+            }
         }
     };
 
@@ -227,14 +231,22 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         }
     };
 
-    // Prologue: the first STAGES stages go out; stage 0 must have landed, in every wave, before the first read.
+    // Two schedules.  Ring of two: stage st + 2 can only be requested once stage st has been read, i.e. in one burst
+    // behind the barrier of stage st.  Ring of three or more (kSpread): the slot freed by the barrier of stage st - 1
+    // is refilled with stage st + STAGES - 1 in thirds, between the MFMA blocks of stage st; a burst of loads right
+    // behind the barrier holds up the issuing wave for as long as the address unit needs to take them (measured: a
+    // fifth of the loop time), spread out they cost an issue slot each.
     // Loads return in order, so "at most n outstanding" means all but the youngest n have landed; waiting for fewer
     // than could be allowed is always safe, which is what happens near the end of K.
+    // Measured: spreading pays for the 8-wave tiles (3-4 %); the 4-wave tiles with a ring of three lose 5-15 % to
+    // the shorter look-ahead it implies, so they keep the burst.
+    constexpr bool kSpread = STAGES >= 3 && kWaves >= 8;
+    constexpr int kAhead = kSpread ? STAGES - 1 : STAGES;  // stages requested before the loop starts
 #pragma unroll
-    for (int s = 0; s < STAGES; ++s)
-        if (s < st_total) issue(s, s);
-    if (st_total >= STAGES)
-        wait_vmcnt<(STAGES - 1) * kLoads>();
+    for (int s = 0; s < kAhead; ++s)
+        if (s < st_total) issue(s, s, 0, 1);
+    if (st_total >= kAhead)
+        wait_vmcnt<(kAhead - 1) * kLoads>();
     else
         wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
@@ -245,35 +257,41 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     int slot = 0;
     for (int st = 0; st < st_total; ++st) {
         const int next = slot + 1 == STAGES ? 0 : slot + 1;
+        const int prev = slot == 0 ? STAGES - 1 : slot - 1;
+        const int target = st + STAGES - 1;            // kSpread: the stage requested during this one
+        const bool have_target = kSpread && target < st_total;
         // The scheduling fences keep each block of LDS reads in front of the MFMA block it overlaps with; left alone
         // the compiler sinks the reads next to their first use and every step then starts with an exposed LDS wait.
         // The fragments of step 0 were requested eight MFMAs ago; waiting for them here, before the next reads go
         // out, costs nothing and spares the wait the compiler would otherwise place behind those reads.
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         read_x(x1, slot, 1);
+        if (have_target) issue(target, prev, 0, 3);
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(x0, w0, 0);
         __builtin_amdgcn_sched_barrier(0);
         read_x(x0, slot, 2);
         read_w(w1, slot, 1);
+        if (have_target) issue(target, prev, 1, 3);
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(x1, w0, 1);
         __builtin_amdgcn_sched_barrier(0);
         read_x(x1, slot, 3);
+        if (have_target) issue(target, prev, 2, 3);
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(x0, w1, 0);
         __builtin_amdgcn_sched_barrier(0);
-        // Every fragment of this stage is in registers once the reads above have returned (the release fence waits
-        // for them), so after the barrier the slot can be refilled; stage st + 1 must be in LDS for every wave.
-        if (st + STAGES <= st_total)
-            wait_vmcnt<(STAGES - 2) * kLoads>();  // stages st + 2 .. st + STAGES - 1 may still be in flight
+        // Every fragment of this stage is in registers once the reads above have returned, so after the barrier the
+        // slot can be refilled; stage st + 1 must be in LDS for every wave.
+        if (kSpread ? have_target : st + STAGES <= st_total)
+            wait_vmcnt<(STAGES - 2) * kLoads>();  // the stages behind st + 1 may still be in flight
         else
             wait_vmcnt<0>();
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's last fragment reads of the slot have returned
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-        if (st + STAGES < st_total) issue(st + STAGES, slot);
+        if (!kSpread && st + STAGES < st_total) issue(st + STAGES, slot, 0, 1);
         if (st + 1 < st_total) {
             read_x(x0, next, 0);
             read_w(w0, next, 0);
@@ -447,7 +465,8 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
                 case kTiled256x256Square: e = launch_tile<2, 4, 4, 2, 3>(q, acc_out, stream); break;
                 case kTiled128x256: e = launch_tile<4, 2, 1, 4, 2>(q, acc_out, stream); break;
                 case kTiled128x160: e = launch_tile<1, 5, 4, 1, 3>(q, acc_out, stream); break;
-                case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3>(q, acc_out, stream); break;                default: e = hipErrorInvalidConfiguration;
+                case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3>(q, acc_out, stream); break;
+                default: e = hipErrorInvalidConfiguration;
             }
             if (e != hipSuccess) return e;
         }
