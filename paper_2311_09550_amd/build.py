@@ -13,8 +13,10 @@ SOURCES = ["api.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_prefill_dma.h
 HEADERS = ["common.hpp", "kernels.hpp", os.path.join("..", "..", "include", "w4a8.h")]
 
 # -packed-fp32-ops: keep the compiler from forming packed fp32 VALU instructions.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+# -ffp-contract=off: no fused multiply-adds are formed from separate fp32 operations, as in the build of the CPU
+# oracle; every intermediate the quantisers and epilogues round is then the one their source states.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Xclang", "-target-feature",
+         "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
 def hipcc() -> str:

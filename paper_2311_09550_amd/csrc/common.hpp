@@ -60,12 +60,20 @@ __device__ __forceinline__ v4i x_operand(v4u x) {
 
 // Dequantisation after the GEMM (Eq. (6),(7)): acc16 is sixteen times the true
 // sum; the arithmetic shift restores it exactly (its low four bits are zero).
+// Both products are rounded to fp32 (S_ij = s_a * s_w first, Eq. (7)); the rounding to fp16 follows in
+// f32_to_f16_bits.
 __device__ __forceinline__ float dequant(int acc16, float s_a, float s_w) {
-    float s_ij = s_a * s_w;
+    const float s_ij = s_a * s_w;
     return (float)(acc16 >> 4) * s_ij;
 }
 
+// fp32 -> fp16, round to nearest even, of a FINISHED fp32 value.  The empty asm makes v opaque at this point:
+// otherwise the compiler may merge the multiplication that produced v with the conversion into one mixed-precision
+// FMA (v_fma_mixlo_f16), which rounds the exact product once and lands on the other fp16 neighbour in some tie
+// cases.  Whether it merges depends on the surrounding code, so two kernels with the same source arithmetic could
+// differ in the last bit; the definition is "fp32 value, then one rounding to fp16" (Eq. (6),(7) give an fp32 O).
 __device__ __forceinline__ unsigned short f32_to_f16_bits(float v) {
+    asm("" : "+v"(v));
     return __half_as_ushort(__float2half_rn(v));
 }
 

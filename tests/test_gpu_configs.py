@@ -1,0 +1,168 @@
+"""GPU parity at the full sizes of the LLaMA-70B sweep and of the LLaMA-13B decoder-layer stack, through the C ABI.
+
+The oracle cannot form a whole 4096 x 57344 output in reasonable time, so above M = 64 it checks a seeded sample of
+complete K sums (at least 4096 entries: whole rows of sampled tokens restricted to sampled channels, including the
+first and last tiles), and every size is additionally covered by properties that hold at any size.  The layer stack
+is checked stage by stage: each stage's oracle is fed the GPU's own upstream fp16 tensor, so integers stay bit-exact
+per stage even where an upstream fp16 value differs from the oracle's by an ulp."""
+import numpy as np
+import pytest
+
+import paper_2311_09550_amd as w4a8
+from paper_2311_09550_amd import synth
+
+from parity import assert_equal_bits, assert_fp16_close
+
+pytestmark = pytest.mark.gpu
+
+SHAPES_70B = {"qkv": (10240, 8192), "o": (8192, 8192), "gate_up": (57344, 8192), "down": (8192, 28672)}
+SWEEP_M = [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
+
+
+@pytest.fixture(scope="module")
+def weights_70b(gpu):
+    """Weights of one 70B linear at a time (the largest is 0.9 GB as fp16 on the host): quantised, packed and tiled on
+    the GPU once per shape and reused over the whole M sweep."""
+    cache = {}
+
+    def get(name):
+        if name not in cache:
+            cache.clear()
+            gpu.cuda.empty_cache()
+            N, K = SHAPES_70B[name]
+            w = synth.weights_fp16(N, K, config_id=4)
+            dwp, dsw = w4a8.w4a8_quantize_weights(gpu.from_numpy(w).cuda())
+            dwt = w4a8.w4a8_tile_weights(dwp)
+            cache[name] = (w, dwp, dsw, dwt)
+        return cache[name]
+
+    yield get
+    cache.clear()
+    gpu.cuda.empty_cache()
+
+
+def _sample_rows(M, tag, count=16):
+    g = synth.rng(971, tag, M)
+    rows = np.sort(g.choice(M, size=min(M, count), replace=False))
+    return np.unique(np.concatenate([rows, [0, M - 1]]))
+
+
+def _sample(M, N, tag):
+    g = synth.rng(970, tag, M, N)
+    rows = _sample_rows(M, tag)
+    cols = np.unique(np.concatenate([np.arange(0, 32), np.arange(N - 32, N), g.choice(N, size=320, replace=False)]))
+    return rows, cols
+
+
+@pytest.mark.parametrize("M", SWEEP_M)
+@pytest.mark.parametrize("name", list(SHAPES_70B))
+def test_llama70b_sweep_sampled_parity(gpu, oracle, weights_70b, name, M):
+    t = gpu
+    N, K = SHAPES_70B[name]
+    w, dwp, dsw, dwt = weights_70b(name)
+    x = synth.activations_fp16(M, K, config_id=4, tag=5)
+    dxq, dsa = w4a8.w4a8_quantize_act(t.from_numpy(x).cuda())
+    acc = w4a8.w4a8_gemm_acc_i32(dxq, dwp)
+    out = w4a8.w4a8_gemm(dxq, dsa, dwp, dsw)
+    out_t = w4a8.w4a8_gemm_tiled(dxq, dsa, dwt, dsw)
+    t.cuda.synchronize()
+    rows, cols = _sample(M, N, 1)
+    assert M <= 16 or len(rows) * len(cols) >= 4096
+    ri, ci = t.from_numpy(rows).cuda(), t.from_numpy(cols).cuda()
+    xq_o, s_a_o = oracle.quantize_act(x[rows])
+    wq_o, s_w_o = oracle.quantize_weights_rtn(np.ascontiguousarray(w[cols]))
+    acc_o, y32, _ = oracle.gemm(xq_o, s_a_o, oracle.pack_w4(wq_o), s_w_o)
+    assert_equal_bits(dxq[ri].cpu().numpy(), xq_o, "xq")
+    assert_equal_bits(dsa[ri].cpu().numpy().view(np.uint32), s_a_o.view(np.uint32), "s_a")
+    assert_equal_bits(dsw[ci].cpu().numpy().view(np.uint32), s_w_o.view(np.uint32), "s_w")
+    assert_equal_bits(acc[ri][:, ci].cpu().numpy(), acc_o, "acc sample")
+    assert_fp16_close(out[ri][:, ci].cpu().numpy(), y32, acc_o, "out sample")
+    # the tiled layout holds the same codes and the kernels share their arithmetic: identical fp16 bits everywhere
+    assert bool((out.view(t.int16) == out_t.view(t.int16)).all()), "tiled vs row-major output bits"
+    # property at any size: the fp16 output is the epilogue of the GPU's own integers (checked on a slab of rows)
+    slab = slice(0, min(M, 64))
+    a = acc[slab].cpu().numpy().astype(np.float32)
+    y = a * (dsa[slab].cpu().numpy()[:, None] * dsw.cpu().numpy()[None, :])
+    assert_fp16_close(out[slab].cpu().numpy(), y, None, "epilogue of the first rows")
+
+
+def _check_gemm_stage(t, oracle, what, dxq, dsa, w, dwp, dsw, dwt, out, tag):
+    """One linear of the stack: sampled raw sums and outputs against the oracle fed the GPU's own int8 input."""
+    M, N = out.shape
+    rows, cols = _sample(M, N, tag)
+    ri, ci = t.from_numpy(rows).cuda(), t.from_numpy(cols).cuda()
+    acc = w4a8.w4a8_gemm_acc_i32(dxq, dwp)
+    t.cuda.synchronize()
+    wq_o, s_w_o = oracle.quantize_weights_rtn(np.ascontiguousarray(w[cols]))
+    acc_o, y32, _ = oracle.gemm(dxq[ri].cpu().numpy(), dsa[ri].cpu().numpy(), oracle.pack_w4(wq_o), s_w_o)
+    assert_equal_bits(dsw[ci].cpu().numpy().view(np.uint32), s_w_o.view(np.uint32), what + " s_w")
+    assert_equal_bits(acc[ri][:, ci].cpu().numpy(), acc_o, what + " acc sample")
+    assert_fp16_close(out[ri][:, ci].cpu().numpy(), y32, acc_o, what + " out sample")
+
+
+def _check_quant_stage(t, oracle, what, x_dev, dxq, dsa):
+    """A quantiser of the stack against the oracle fed the GPU's own fp16 input (all rows up to 64, else a sample)."""
+    M = x_dev.shape[0]
+    rows = np.arange(M) if M <= 64 else _sample_rows(M, 7, 48)
+    ri = t.from_numpy(rows).cuda()
+    xq_o, s_a_o = oracle.quantize_act(x_dev[ri].cpu().numpy())
+    assert_equal_bits(dxq[ri].cpu().numpy(), xq_o, what + " xq")
+    assert_equal_bits(dsa[ri].cpu().numpy().view(np.uint32), s_a_o.view(np.uint32), what + " s_a")
+
+
+@pytest.fixture(scope="module")
+def weights_13b(gpu):
+    ws = {}
+    for name, (N, K) in synth.LLAMA_SHAPES["13b"].items():
+        w = synth.weights_fp16(N, K, config_id=5)
+        dwp, dsw = w4a8.w4a8_quantize_weights(gpu.from_numpy(w).cuda())
+        ws[name] = (w, dwp, dsw, w4a8.w4a8_tile_weights(dwp))
+    yield ws
+    ws.clear()
+    gpu.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("M", [1, 16, 128, 1024, 2048])
+def test_llama13b_layer_stack_stage_wise(gpu, oracle, weights_13b, M):
+    """Hidden states -> quantiser -> QKV -> (the Q slice stands in for the attention output) -> quantiser -> O ->
+    quantiser -> gate+up -> SiLU(gate)*up -> quantiser -> down, as the benchmark's step runs it: tiled weights above
+    M = 64, row-major below; the fused SiLU*up + quantiser, checked against the two separate kernels."""
+    t = gpu
+    H = synth.LLAMA_SHAPES["13b"]["qkv"][1]
+
+    def gemm(name, dxq, dsa):
+        w, dwp, dsw, dwt = weights_13b[name]
+        return w4a8.w4a8_gemm_tiled(dxq, dsa, dwt, dsw) if M > 64 else w4a8.w4a8_gemm(dxq, dsa, dwp, dsw)
+
+    h = t.from_numpy(synth.activations_fp16(M, H, config_id=5, tag=1)).cuda()
+    xq1, sa1 = w4a8.w4a8_quantize_act(h)
+    qkv = gemm("qkv", xq1, sa1)
+    attn = qkv[:, :H].contiguous()
+    xq2, sa2 = w4a8.w4a8_quantize_act(attn)
+    o = gemm("o", xq2, sa2)
+    xq3, sa3 = w4a8.w4a8_quantize_act(o)
+    gu = gemm("gate_up", xq3, sa3)
+    xq4, sa4 = w4a8.w4a8_silu_mul_quantize(gu)
+    down = gemm("down", xq4, sa4)
+    act = w4a8.w4a8_silu_mul(gu)
+    xq4b, sa4b = w4a8.w4a8_quantize_act(act)
+    t.cuda.synchronize()
+
+    _check_quant_stage(t, oracle, "quant(h)", h, xq1, sa1)
+    _check_gemm_stage(t, oracle, "qkv", xq1, sa1, *weights_13b["qkv"], qkv, 11)
+    _check_quant_stage(t, oracle, "quant(attn)", attn, xq2, sa2)
+    _check_gemm_stage(t, oracle, "o", xq2, sa2, *weights_13b["o"], o, 12)
+    _check_quant_stage(t, oracle, "quant(o)", o, xq3, sa3)
+    _check_gemm_stage(t, oracle, "gate_up", xq3, sa3, *weights_13b["gate_up"], gu, 13)
+    # glue: fp32 SiLU(gate)*up rounded to fp16, within the fp16 tolerance of the oracle's fp64 value on sampled rows
+    rows = np.arange(M) if M <= 16 else _sample_rows(M, 8)
+    ri = t.from_numpy(rows).cuda()
+    y64, _ = oracle.silu_mul(gu[ri].cpu().numpy())
+    got = act[ri].cpu().numpy().astype(np.float64)
+    big = np.abs(y64) >= 2.0 ** -14
+    assert np.all(np.abs(got - y64)[big] <= 2.0 ** -10 * np.abs(y64)[big])
+    assert np.all(np.abs(got - y64)[~big] <= 2.0 ** -24)
+    assert bool((xq4 == xq4b).all()) and bool((sa4.view(t.int32) == sa4b.view(t.int32)).all()), "fused vs separate glue"
+    _check_quant_stage(t, oracle, "quant(silu*up)", act, xq4, sa4)
+    _check_gemm_stage(t, oracle, "down", xq4, sa4, *weights_13b["down"], down, 14)
+    assert bool(t.isfinite(down).all())
