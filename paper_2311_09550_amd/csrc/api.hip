@@ -92,6 +92,13 @@ int choose_tiled_tile(int M, int N) {
                               {kTiled128x160, 128, 160, 2, 0.75},
                               {kTiled128x128, 128, 128, 2, 0.75}};
     const int cus = compute_units();
+    // Medium M: when not even 128 x 128 tiles occupy three quarters of the compute units, run time is the length of
+    // one workgroup's walk over K, and smaller tiles (more workgroups, each with a shorter stage) shorten it.
+    auto count = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    if (count(128, 128) * 4 < (long long)cus * 3) {
+        if (M <= 32) return kTiled32x128;
+        return count(64, 128) * 4 >= (long long)cus * 3 ? kTiled64x128 : kTiled64x64;
+    }
     int best = kTiled256x256;
     double best_cost = 0;
     for (const Option &o : options) {

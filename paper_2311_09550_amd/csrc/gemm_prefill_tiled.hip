@@ -466,6 +466,9 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
                 case kTiled128x256: e = launch_tile<4, 2, 1, 4, 2>(q, acc_out, stream); break;
                 case kTiled128x160: e = launch_tile<1, 5, 4, 1, 3>(q, acc_out, stream); break;
                 case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3>(q, acc_out, stream); break;
+                case kTiled64x128: e = launch_tile<1, 2, 2, 2, 4>(q, acc_out, stream); break;
+                case kTiled64x64: e = launch_tile<1, 1, 2, 2, 4>(q, acc_out, stream); break;
+                case kTiled32x128: e = launch_tile<1, 1, 1, 4, 4>(q, acc_out, stream); break;
                 default: e = hipErrorInvalidConfiguration;
             }
             if (e != hipSuccess) return e;

@@ -65,7 +65,10 @@ constexpr int kTiled256x256Square = 2;  // 8 waves of 64 x 128
 constexpr int kTiled128x256 = 3;        // 4 waves of 128 x 64, two-stage ring, two workgroups per compute unit
 constexpr int kTiled128x160 = 4;        // 4 waves of 32 x 160
 constexpr int kTiled128x128 = 5;        // 4 waves of 64 x 64
-constexpr int kTiledTileMax = 5;
+constexpr int kTiled64x128 = 6;         // 4 waves of 32 x 64: medium M, where 128-row tiles leave most of the chip idle
+constexpr int kTiled64x64 = 7;          // 4 waves of 32 x 32
+constexpr int kTiled32x128 = 8;         // 4 waves of 32 x 32 side by side
+constexpr int kTiledTileMax = 8;
 
 size_t tiled_weight_bytes(int N, int K);
 hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream);

@@ -12,7 +12,7 @@ from parity import assert_equal_bits, assert_fp16_close
 pytestmark = pytest.mark.gpu
 
 TILED = w4a8.TILING_PREFILL_TILED
-TILES = [1, 2, 3, 4, 5]   # 256 x 256 (2 x 4 waves), 256 x 256 (4 x 2 waves), 128 x 256, 128 x 160, 128 x 128
+TILES = [1, 2, 3, 4, 5, 6, 7, 8]   # 256x256 (2x4 waves), 256x256 (4x2), 128x256, 128x160, 128x128, 64x128, 64x64, 32x128
 
 
 def tiled_layout(wq):
