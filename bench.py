@@ -58,6 +58,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--M", type=int, default=1024, help="tokens per step (default: the 1024-token context)")
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1,4,16 weight-streaming measurements")
+    ap.add_argument("--no-layer-stack", action="store_true", help="skip the graph-replayed layer stack at M=1..2048")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -66,19 +67,31 @@ def parse_args():
     return ap.parse_args()
 
 
-class LayerStack:
-    """Device buffers of one 13B-shaped decoder layer's linears and the nine launches of a step."""
+DECODE_MAX_M = 64   # up to here the row-major array and the weight-streaming kernels, above it the tiled array
 
-    def __init__(self, torch, w4a8, synth, M, model="13b"):
+
+def prepare_weights(torch, w4a8, synth, model="13b"):
+    """Offline weight preparation, on the GPU: quantise, pack (row-major array for small M), reorder (tiled array for
+    large M).  Returns name -> (wp, wt, s_w)."""
+    out = {}
+    for name, (N, K) in synth.LLAMA_SHAPES[model].items():
+        w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).to("cuda")
+        wp, s_w = w4a8.w4a8_quantize_weights(w)
+        out[name] = (wp, w4a8.w4a8_tile_weights(wp), s_w)
+        del w
+    return out
+
+
+class LayerStack:
+    """Device buffers of one 13B-shaped decoder layer's linears and the eight launches of a step."""
+
+    def __init__(self, torch, w4a8, synth, M, weights, model="13b"):
         self.torch, self.w4a8, self.M = torch, w4a8, M
         self.shapes = synth.LLAMA_SHAPES[model]
         dev = "cuda"
-        self.wp, self.s_w = {}, {}
-        for name, (N, K) in self.shapes.items():
-            w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).to(dev)
-            wp, self.s_w[name] = w4a8.w4a8_quantize_weights(w)   # offline weight preparation, on the GPU:
-            self.wp[name] = w4a8.w4a8_tile_weights(wp)            # quantise, pack, reorder for large M
-            del w, wp
+        self.tiled = M > DECODE_MAX_M
+        self.wp = {k: (v[1] if self.tiled else v[0]) for k, v in weights.items()}
+        self.s_w = {k: v[2] for k, v in weights.items()}
         H = self.shapes["qkv"][1]
         I = self.shapes["down"][1]
         # fp16 inputs of the three linears that are fed from outside the stack (attention itself is not modelled)
@@ -96,7 +109,10 @@ class LayerStack:
         if record:
             a, b = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
             a.record()
-        w.w4a8_gemm_tiled(xq, sa, self.wp[name], self.s_w[name], out=self.out[name])
+        if self.tiled:
+            w.w4a8_gemm_tiled(xq, sa, self.wp[name], self.s_w[name], out=self.out[name])
+        else:
+            w.w4a8_gemm(xq, sa, self.wp[name], self.s_w[name], out=self.out[name])
         if record:
             b.record()
             self.gemm_events.append((name, a, b))
@@ -112,8 +128,50 @@ class LayerStack:
         w.w4a8_silu_mul_quantize(self.out["gate_up"], self.xq_i, self.sa_i)   # SiLU*up and its quantiser, one pass
         self._gemm("down", self.xq_i, self.sa_i, record)
 
+    def gemms_only(self):
+        for name, xq, sa in (("qkv", self.xq_h, self.sa_h), ("o", self.xq_h, self.sa_h), ("gate_up", self.xq_h, self.sa_h),
+                             ("down", self.xq_i, self.sa_i)):
+            self._gemm(name, xq, sa, False)
+
     def ops_per_step(self):
         return sum(gemm_ops(self.M, N, K) for N, K in self.shapes.values())
+
+
+def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 16, 128, 1024, 2048), steps_per_graph=8, replays=6):
+    """The decoder layer's linear stack at several M, replayed from a HIP graph (what a serving loop does; at small M
+    the eight launches would otherwise be timed by the interpreter).  Layer time = graph time / steps; the GEMM share
+    is the time of a second graph that holds only the four GEMMs, over the layer time.  One layer's weights (158 MB)
+    stay resident in the last-level cache across replays: the small-M rows are a warm-cache figure, the HBM-bound
+    figure is the `decode` list."""
+    rows = []
+    for M in Ms:
+        stack = LayerStack(torch, w4a8, synth, M, weights)
+        for _ in range(3):
+            stack.step()
+        torch.cuda.synchronize()
+        times = {}
+        for what, fn in (("layer", stack.step), ("gemms", stack.gemms_only)):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for _ in range(steps_per_graph):
+                    fn()
+            graph.replay()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(replays):
+                graph.replay()
+            b.record()
+            torch.cuda.synchronize()
+            times[what] = a.elapsed_time(b) * 1e3 / (replays * steps_per_graph)
+            del graph
+        rows.append({"M": M, "layer_us": round(times["layer"], 2), "gemm_us": round(times["gemms"], 2),
+                     "gemm_share": round(times["gemms"] / times["layer"], 4),
+                     "TOPS": round(stack.ops_per_step() / times["layer"] / 1e6, 2),
+                     "weights": "tiled" if stack.tiled else "row-major"})
+        del stack
+        torch.cuda.empty_cache()
+    return rows
 
 
 def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
@@ -222,7 +280,8 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    stack = LayerStack(torch, w4a8, synth, M)
+    weights = prepare_weights(torch, w4a8, synth)
+    stack = LayerStack(torch, w4a8, synth, M, weights)
     for _ in range(args.warmup):
         stack.step()
     torch.cuda.synchronize()
@@ -264,6 +323,10 @@ def main():
         "roofline": roofline,
     }
     del stack
+    torch.cuda.empty_cache()
+    if not args.no_layer_stack:
+        result["layer_stack"] = time_layer_stack(torch, w4a8, synth, weights)
+    del weights
     torch.cuda.empty_cache()
     if not args.no_decode:
         rows = time_decode(torch, w4a8, synth)
