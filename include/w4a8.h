@@ -159,6 +159,17 @@ int w4a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const
 int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, int K, void *stream);
 
 /*
+ * The same with the clipping strengths of the symmetric weight clipping (Sec. 5.1, Eq. (8),(9)) given per output
+ * channel, e.g. as found by a calibration that is not part of this library:
+ *   s_w[n] = max(|gamma[n] * max_k W[n][k]|, |beta[n] * min_k W[n][k]|) / 7   (fp32: products, max, division)
+ *   Wq     = clamp(round_half_even(W / s_w), -8, 7)     -- values outside the clipped range saturate, -8 occurs.
+ * gamma, beta: fp32 [N] on the device, finite and such that s_w[n] is a normal fp32 or zero; NULL stands for all ones
+ * (with both NULL the result equals w4a8_quantize_weights).
+ */
+int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const float *beta,
+                                  uint8_t *wp, float *s_w, int N, int K, void *stream);
+
+/*
  * Glue between the gate/up GEMM and the down GEMM of a LLaMA MLP:
  *   h[m][i] = fp16( silu(gate_up[m][i]) * gate_up[m][I + i] ),  fp32 arithmetic.
  *   gate_up_fp16 [M][2I] in, h_fp16 [M][I] out.  I % 8 == 0.

@@ -124,6 +124,22 @@ def quantize_weights_rtn(w_half):
     return wq, s_w
 
 
+def quantize_weights_clip(w_half, gamma=None, beta=None):
+    """fp16 [N][K], per-channel clipping strengths (float32 [N] or None = 1) -> (int8 codes in [-8,7], float32 scales)."""
+    w = np.ascontiguousarray(w_half)
+    if w.dtype == np.float16:
+        w = w.view(np.uint16)
+    w = _c(w, np.uint16)
+    N, K = w.shape
+    g = None if gamma is None else _c(np.asarray(gamma, np.float32), np.float32)
+    b = None if beta is None else _c(np.asarray(beta, np.float32), np.float32)
+    wq = np.empty((N, K), np.int8)
+    s_w = np.empty(N, np.float32)
+    _load().oracle_quantize_weights_clip(_p(w), None if g is None else _p(g), None if b is None else _p(b), _p(wq), _p(s_w),
+                                         N, K)
+    return wq, s_w
+
+
 def gemm_acc_i32(xq, wp):
     xq = _c(xq, np.int8)
     wp = _c(wp, np.uint8)

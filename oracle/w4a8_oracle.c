@@ -204,6 +204,40 @@ void oracle_quantize_weights_rtn(const uint16_t *w_half, int8_t *wq, float *s_w,
     }
 }
 
+/* The same with the clipping strengths of Eq. (9) given per output channel:
+ *   S = max(|gamma * max(W_row)|, |beta * min(W_row)|) / 7,  codes = clamp(rne(W / S), -8, 7)   (Eq. (8)).
+ * Values outside the clipped range saturate, so -8 does occur here.  gamma or beta may be NULL (= 1). */
+void oracle_quantize_weights_clip(const uint16_t *w_half, const float *gamma, const float *beta, int8_t *wq, float *s_w,
+                                  int N, int K)
+{
+    for (int n = 0; n < N; ++n) {
+        float wmax = -INFINITY, wmin = INFINITY;
+        for (int k = 0; k < K; ++k) {
+            float v = (float)half_bits_to_double(w_half[(size_t)n * K + k]);
+            if (v > wmax) wmax = v;
+            if (v < wmin) wmin = v;
+        }
+        float g = gamma ? gamma[n] : 1.0f, b = beta ? beta[n] : 1.0f;
+        float up = fabsf(g * wmax), down = fabsf(b * wmin);
+        float top = up > down ? up : down;
+        if (top == 0.0f) {
+            s_w[n] = 0.0f;
+            for (int k = 0; k < K; ++k) wq[(size_t)n * K + k] = 0;
+            continue;
+        }
+        float scale = top / 7.0f;
+        s_w[n] = scale;
+        for (int k = 0; k < K; ++k) {
+            float v = (float)half_bits_to_double(w_half[(size_t)n * K + k]);
+            float q = v / scale;
+            float r = nearbyintf(q);
+            if (r > 7.0f) r = 7.0f;
+            if (r < -8.0f) r = -8.0f;
+            wq[(size_t)n * K + k] = (int8_t)r;
+        }
+    }
+}
+
 /* ------------------------------------------------------------------ GEMM */
 
 /* acc[m][n] = sum_k xq[m][k] * W_q[n][k]   (Eq. (6), the sum inside Dq).

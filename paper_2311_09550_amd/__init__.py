@@ -45,6 +45,7 @@ def lib():
         L.w4a8_gemm_acc_i32.argtypes = [vp, vp, vp, i, i, i, vp, sz, vp]
         L.w4a8_gemm_tuned.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
         L.w4a8_quantize_weights.argtypes = [vp, vp, vp, i, i, vp]
+        L.w4a8_quantize_weights_clipped.argtypes = [vp, vp, vp, vp, vp, i, i, vp]
         L.w4a8_silu_mul.argtypes = [vp, vp, i, i, vp]
         L.w4a8_silu_mul_quantize.argtypes = [vp, vp, vp, i, i, vp]
         L.w4a8_pack_weights_host.argtypes = [vp, vp, i, i]
@@ -53,7 +54,7 @@ def lib():
         L.w4a8_tile_weights.argtypes = [vp, vp, i, i, vp]
         L.w4a8_gemm_tiled.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp]
         for name in ("w4a8_quantize_act", "w4a8_gemm", "w4a8_gemm_acc_i32", "w4a8_gemm_tuned",
-                     "w4a8_quantize_weights", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host",
+                     "w4a8_quantize_weights", "w4a8_quantize_weights_clipped", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host",
                      "w4a8_tile_weights", "w4a8_gemm_tiled"):
             getattr(L, name).restype = i
         _lib = L
@@ -223,6 +224,22 @@ def w4a8_quantize_weights(w, wp=None, s_w=None):
     s_w = torch.empty((N,), dtype=torch.float32, device=w.device) if s_w is None else s_w
     _check(lib().w4a8_quantize_weights(_dev(w, torch.float16, "w"), _dev(wp, torch.uint8, "wp"),
                                        _dev(s_w, torch.float32, "s_w"), N, K, _stream()))
+    return wp, s_w
+
+
+def w4a8_quantize_weights_clipped(w, gamma=None, beta=None, wp=None, s_w=None):
+    """fp16 [N][K], clipping strengths fp32 [N] (None = 1) -> (uint8 [N][K/2] packed int4, fp32 [N])."""
+    torch = _torch()
+    N, K = w.shape
+    wp = torch.empty((N, K // 2), dtype=torch.uint8, device=w.device) if wp is None else wp
+    s_w = torch.empty((N,), dtype=torch.float32, device=w.device) if s_w is None else s_w
+    for v, what in ((gamma, "gamma"), (beta, "beta")):
+        if v is not None and tuple(v.shape) != (N,):
+            raise ValueError(f"{what}: expected {N} values")
+    _check(lib().w4a8_quantize_weights_clipped(_dev(w, torch.float16, "w"),
+                                               None if gamma is None else _dev(gamma, torch.float32, "gamma"),
+                                               None if beta is None else _dev(beta, torch.float32, "beta"),
+                                               _dev(wp, torch.uint8, "wp"), _dev(s_w, torch.float32, "s_w"), N, K, _stream()))
     return wp, s_w
 
 

@@ -263,6 +263,16 @@ int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, in
                                                                                                              : W4A8_ERR_LAUNCH;
 }
 
+int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const float *beta, uint8_t *wp, float *s_w, int N,
+                                  int K, void *stream) {
+    if (!w_fp16 || !wp || !s_w) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(1, N, K)) return e;
+    if (misaligned(w_fp16) || misaligned(wp)) return W4A8_ERR_ALIGN;
+    return launch_quantize_weights_clip(w_fp16, gamma, beta, wp, s_w, N, K, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? W4A8_OK
+               : W4A8_ERR_LAUNCH;
+}
+
 int w4a8_silu_mul(const void *gate_up_fp16, void *h_fp16, int M, int I, void *stream) {
     if (!gate_up_fp16 || !h_fp16) return W4A8_ERR_NULL;
     if (M < 1 || I < 8 || (I % 8) != 0 || M > 65535) return W4A8_ERR_SHAPE;

@@ -79,6 +79,8 @@ hipError_t launch_prefill_dma_slice(const PrefillArgs &p, bool acc_out, int tile
 
 hipError_t launch_quantize_act(const void *x, int8_t *xq, float *s_a, int M, int K, hipStream_t stream);
 hipError_t launch_quantize_weights(const void *w, uint8_t *wp, float *s_w, int N, int K, hipStream_t stream);
+hipError_t launch_quantize_weights_clip(const void *w, const float *gamma, const float *beta, uint8_t *wp, float *s_w, int N,
+                                        int K, hipStream_t stream);
 hipError_t launch_silu_mul(const void *gate_up, void *h, int M, int I, hipStream_t stream);
 hipError_t launch_silu_mul_quantize(const void *gate_up, int8_t *xq, float *s_a, int M, int I, hipStream_t stream);
 

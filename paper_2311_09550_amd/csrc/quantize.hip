@@ -180,6 +180,53 @@ __global__ __launch_bounds__(kRowThreads, 8) void quantize_weights_kernel(const 
     }
 }
 
+// The same with the clipping strengths of Eq. (9) per output channel: S = max(|gamma max(W)|, |beta min(W)|) / 7.
+// Values outside the clipped range saturate at -8 / 7 (Eq. (8)).  gamma / beta may be NULL (= 1).
+__global__ __launch_bounds__(kRowThreads, 8) void quantize_weights_clip_kernel(const uint16_t *__restrict__ w,
+                                                                            const float *__restrict__ gamma,
+                                                                            const float *__restrict__ beta,
+                                                                            uint8_t *__restrict__ wp, float *__restrict__ s_w,
+                                                                            int K) {
+    __shared__ float scratch_hi[kRowThreads / 64];
+    __shared__ float scratch_lo[kRowThreads / 64];
+    const int n = blockIdx.x;
+    const int chunks = K >> 3;
+    const v4u *src = (const v4u *)(w + (size_t)n * K);
+
+    float hi = -INFINITY, neg_lo = -INFINITY;  // max(W) and max(-W) = -min(W)
+    for (int c = threadIdx.x; c < chunks; c += kRowThreads) {
+        float xf[8];
+        halves8(src[c], xf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            hi = fmaxf(hi, xf[j]);
+            neg_lo = fmaxf(neg_lo, -xf[j]);
+        }
+    }
+    hi = block_max(hi, scratch_hi);
+    neg_lo = block_max(neg_lo, scratch_lo);
+    const float g = gamma ? gamma[n] : 1.0f, b = beta ? beta[n] : 1.0f;
+    const float top = fmaxf(fabsf(g * hi), fabsf(b * -neg_lo));
+
+    const RowQuantizer rq(top, 7.0f, -8.f, 7.f);
+    if (threadIdx.x == 0) s_w[n] = rq.scale;
+    const bool zero_row = top == 0.f;
+
+    unsigned *dst = (unsigned *)(wp + (size_t)n * (K >> 1));
+    for (int c = threadIdx.x; c < chunks; c += kRowThreads) {
+        unsigned o = 0;
+        if (!zero_row) {
+            float xf[8];
+            int q[8];
+            halves8(src[c], xf);
+            rq.codes8(xf, q);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o |= (unsigned)((q[2 * j] & 15) | ((q[2 * j + 1] & 15) << 4)) << (8 * j);
+        }
+        dst[c] = o;
+    }
+}
+
 // h = fp16( silu(gate) * up ), gate = columns [0,I), up = columns [I,2I) of a row of gate_up.
 __global__ __launch_bounds__(kRowThreads) void silu_mul_kernel(const uint16_t *__restrict__ gate_up, uint16_t *__restrict__ h,
                                                                int I) {
@@ -252,6 +299,13 @@ hipError_t launch_quantize_act(const void *x, int8_t *xq, float *s_a, int M, int
 
 hipError_t launch_quantize_weights(const void *w, uint8_t *wp, float *s_w, int N, int K, hipStream_t stream) {
     hipLaunchKernelGGL(quantize_weights_kernel, dim3(N), dim3(kRowThreads), 0, stream, (const uint16_t *)w, wp, s_w, K);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_weights_clip(const void *w, const float *gamma, const float *beta, uint8_t *wp, float *s_w, int N,
+                                        int K, hipStream_t stream) {
+    hipLaunchKernelGGL(quantize_weights_clip_kernel, dim3(N), dim3(kRowThreads), 0, stream, (const uint16_t *)w, gamma, beta,
+                       wp, s_w, K);
     return hipGetLastError();
 }
 

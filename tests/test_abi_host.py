@@ -86,6 +86,9 @@ def test_argument_validation_happens_before_any_launch(L):
     assert q(odd, p, p, 1, 32, null) == -3
     assert L.w4a8_quantize_weights(p, p, null, 4, 32, null) == -1
     assert L.w4a8_quantize_weights(p, p, p, 4, 33, null) == -2
+    assert L.w4a8_quantize_weights_clipped(p, null, null, p, null, 4, 32, null) == -1
+    assert L.w4a8_quantize_weights_clipped(p, p, p, p, p, 4, 48, null) == -2
+    assert L.w4a8_quantize_weights_clipped(odd, null, null, p, p, 4, 32, null) == -3
     assert L.w4a8_silu_mul(p, null, 1, 8, null) == -1
     assert L.w4a8_silu_mul(p, p, 1, 12, null) == -2
     assert L.w4a8_silu_mul_quantize(p, null, p, 1, 32, null) == -1

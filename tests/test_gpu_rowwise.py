@@ -78,6 +78,35 @@ def test_quantize_weights_bit_exact(gpu, oracle, N, K):
     assert_equal_bits(wp.cpu().numpy(), oracle.pack_w4(wq_o), "wp")
 
 
+@pytest.mark.parametrize("N,K", [(1, 32), (7, 96), (64, 4096), (33, 5120), (4, 28672)])
+def test_quantize_weights_clipped_bit_exact(gpu, oracle, N, K):
+    """Eq. (8),(9) with per-channel clipping strengths: codes (saturating at -8 / 7) and scales bit-exact."""
+    g = synth.rng(924, N, K)
+    w = synth.weights_fp16(N, K, config_id=8)
+    if N > 2:
+        w[1, :] = 0
+        w[2, 0] = np.float16(-1.0)
+    gamma = g.uniform(0.25, 1.0, N).astype(np.float32)
+    beta = g.uniform(0.25, 1.0, N).astype(np.float32)
+    dw = gpu.from_numpy(w).cuda()
+    for ga, be in ((gamma, beta), (gamma, None), (None, beta), (None, None)):
+        wp, s_w = w4a8.w4a8_quantize_weights_clipped(dw, None if ga is None else gpu.from_numpy(ga).cuda(),
+                                                     None if be is None else gpu.from_numpy(be).cuda())
+        gpu.cuda.synchronize()
+        wq_o, s_o = oracle.quantize_weights_clip(w, ga, be)
+        assert_equal_bits(s_w.cpu().numpy().view(np.uint32), s_o.view(np.uint32), "s_w")
+        assert_equal_bits(wp.cpu().numpy(), oracle.pack_w4(wq_o), "wp")
+    if N >= 33:
+        assert wq_o.min() == -7                      # last pass had no clipping: plain RTN never reaches -8
+        wq_c, _ = oracle.quantize_weights_clip(w, gamma, beta)
+        assert wq_c.min() == -8 and wq_c.max() == 7  # the clipped one saturates
+    # the unclipped call is the plain quantiser
+    wp0, s0 = w4a8.w4a8_quantize_weights(dw)
+    gpu.cuda.synchronize()
+    assert_equal_bits(wp.cpu().numpy(), wp0.cpu().numpy(), "clipped(None, None) vs plain: wp")
+    assert_equal_bits(s_w.cpu().numpy().view(np.uint32), s0.cpu().numpy().view(np.uint32), "clipped(None, None) vs plain: s_w")
+
+
 @pytest.mark.parametrize("M,I", [(1, 8), (3, 104), (16, 13824), (130, 1024)])
 def test_silu_mul_close(gpu, oracle, M, I):
     g = synth.rng(921, M, I)

@@ -353,6 +353,56 @@ def test_weight_rtn_eq8_eq9(oracle):
         assert list(wq[r]) == codes and Fraction(float(s_w[r])) == scale
 
 
+def test_weight_clipping_eq8_eq9_with_strengths(oracle):
+    """Eq. (8),(9) with clipping strengths gamma, beta per channel."""
+    # without strengths it is the plain RTN, bit for bit
+    w = synth.weights_fp16(24, 128)
+    a, sa = oracle.quantize_weights_clip(w)
+    b, sb = oracle.quantize_weights_rtn(w)
+    assert np.array_equal(a, b) and np.array_equal(sa.view(np.uint32), sb.view(np.uint32))
+    ones = np.ones(24, np.float32)
+    c, sc = oracle.quantize_weights_clip(w, ones, ones)
+    assert np.array_equal(c, b) and np.array_equal(sc.view(np.uint32), sb.view(np.uint32))
+
+    # hand-worked row, every value, the scale and every quotient exact: max 1.75, min -3.5, gamma = 1/2, beta = 1/4
+    # => S = max(|0.5 * 1.75|, |0.25 * -3.5|) / 7 = 0.875 / 7 = 1/8; codes = clamp(rne(8 w), -8, 7)
+    row = np.array([[1.75, -3.5, 0.875, 0.4375, -0.4375, 0.0, 0.1875, -0.1875, 0.3125, -0.3125, -0.875, -1.0625, 0.9375,
+                     0.0625]], np.float16)
+    wq, s = oracle.quantize_weights_clip(row, np.float32([0.5]), np.float32([0.25]))
+    assert float(s[0]) == 0.125
+    # 8 w =      14   -28  7  3.5  -3.5 0  1.5 -1.5  2.5 -2.5  -7  -8.5  7.5  0.5   (ties go to the even integer)
+    assert list(wq[0]) == [7, -8, 7, 4, -4, 0, 2, -2, 2, -2, -7, -8, 7, 0]
+
+    # the paper's illustration: a range (-0.4, 0.2) narrowed to about (-0.2, 0.2) by halving beta
+    row = np.array([[-0.4, 0.2, -0.1, 0.1, 0.05, -0.2, -0.3]], np.float16)
+    wq, s = oracle.quantize_weights_clip(row, None, np.float32([0.5]))
+    codes, scale = exact_quantize_row(np.array([0.2], np.float16), 7, -8, 7)      # S = fp16(0.2) / 7
+    assert Fraction(float(s[0])) == scale and codes == [7]
+    assert wq[0, 0] == -8 and wq[0, 1] == 7 and wq[0, 6] == -8 and wq[0, 5] == -7
+    lo, hi = -8 * float(s[0]), 7 * float(s[0])
+    assert -0.23 < lo < -0.22 and abs(hi - 0.2) < 1e-3
+
+    # properties on random rows: saturation outside the clipped range, half-step error inside, exact rational codes
+    g = synth.rng(906)
+    w = synth.weights_fp16(16, 256, config_id=7)
+    gamma = g.uniform(0.3, 1.0, 16).astype(np.float32)
+    beta = g.uniform(0.3, 1.0, 16).astype(np.float32)
+    wq, s = oracle.quantize_weights_clip(w, gamma, beta)
+    wf = w.astype(np.float64)
+    assert wq.min() == -8 and wq.max() == 7
+    inside = (wf >= -8.5 * s[:, None]) & (wf <= 7.5 * s[:, None])
+    err = np.abs(wf - wq * s[:, None].astype(np.float64))
+    assert np.all(err[inside] <= 0.5 * np.broadcast_to(s[:, None], wf.shape)[inside] * (1 + 2.0 ** -20))
+    assert np.all(wq[wf > 7.5 * s[:, None]] == 7) and np.all(wq[wf < -8.5 * s[:, None]] == -8)
+    for r in (0, 9):
+        fr = [Fraction(float(v)) for v in w[r]]
+        up = abs(fp32_round(Fraction(float(gamma[r])) * max(fr)))
+        down = abs(fp32_round(Fraction(float(beta[r])) * min(fr)))
+        scale = fp32_round(max(up, down) / 7)
+        assert Fraction(float(s[r])) == scale
+        assert list(wq[r]) == [int(min(7, max(-8, rne_int(fp32_round(v / scale))))) for v in fr]
+
+
 # --------------------------------------------------------------------- glue
 
 def test_silu_mul_vs_library_and_identities(oracle):
