@@ -173,6 +173,38 @@ def gemm(xq, s_a, wp, s_w):
     return acc, y32, out
 
 
+def gemm_acc_i32_w8(xq, w8):
+    xq = _c(xq, np.int8)
+    w8 = _c(w8, np.int8)
+    M, K = xq.shape
+    N, K2 = w8.shape
+    if K2 != K:
+        raise ValueError("shape mismatch")
+    acc = np.empty((M, N), np.int32)
+    _load().oracle_gemm_acc_i32_w8(_p(xq), _p(w8), _p(acc), M, N, K)
+    return acc
+
+
+def gemm_w8(xq, s_a, w8, s_w):
+    """The W8A8 linear (int8 weight codes [N][K]) -> (acc int32, y32 float32, out float16)."""
+    acc = gemm_acc_i32_w8(xq, w8)
+    y32, out = epilogue(acc, s_a, s_w)
+    return acc, y32, out
+
+
+def quantize_weights_rtn8(w_half):
+    """fp16 [N][K] -> (int8 codes [N][K], float32 scales [N]), scale absmax / 127."""
+    w = np.ascontiguousarray(w_half)
+    if w.dtype == np.float16:
+        w = w.view(np.uint16)
+    w = _c(w, np.uint16)
+    N, K = w.shape
+    wq = np.empty((N, K), np.int8)
+    s_w = np.empty(N, np.float32)
+    _load().oracle_quantize_weights_rtn8(_p(w), _p(wq), _p(s_w), N, K)
+    return wq, s_w
+
+
 def silu_mul(gate_up_half):
     """fp16 [M][2I] -> (y64 float64 [M][I], h float16 [M][I])."""
     g = np.ascontiguousarray(gate_up_half)

@@ -266,6 +266,48 @@ void oracle_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int 
     }
 }
 
+/* The W8A8 counterpart (the paper's own comparison point, Table 4): the same sum with int8 weight codes
+ * w8[N][K] stored one per byte.  |acc| <= 128 * 128 * K, inside int32 for K <= 65536. */
+void oracle_gemm_acc_i32_w8(const int8_t *xq, const int8_t *w8, int32_t *acc, int M, int N, int K)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int m = 0; m < M; ++m) {
+            int32_t s = 0;
+            for (int k = 0; k < K; ++k)
+                s += (int32_t)xq[(size_t)m * K + k] * (int32_t)w8[(size_t)n * K + k];
+            acc[(size_t)m * N + n] = s;
+        }
+    }
+}
+
+/* Per-output-channel symmetric 8-bit round-to-nearest (Eq. (8),(9) with N = 8 bits, gamma = beta = 1):
+ * S = max|W_row| / 127, codes clamped to [-128, 127] (with this S the clamp never acts). */
+void oracle_quantize_weights_rtn8(const uint16_t *w_half, int8_t *wq, float *s_w, int N, int K)
+{
+    for (int n = 0; n < N; ++n) {
+        float top = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            float v = fabsf((float)half_bits_to_double(w_half[(size_t)n * K + k]));
+            if (v > top) top = v;
+        }
+        if (top == 0.0f) {
+            s_w[n] = 0.0f;
+            for (int k = 0; k < K; ++k) wq[(size_t)n * K + k] = 0;
+            continue;
+        }
+        float scale = top / 127.0f;
+        s_w[n] = scale;
+        for (int k = 0; k < K; ++k) {
+            float v = (float)half_bits_to_double(w_half[(size_t)n * K + k]);
+            float r = nearbyintf(v / scale);
+            if (r > 127.0f) r = 127.0f;
+            if (r < -128.0f) r = -128.0f;
+            wq[(size_t)n * K + k] = (int8_t)r;
+        }
+    }
+}
+
 /* y32[m][n] = float(acc[m][n]) * (s_a[m] * s_w[n])   (Eq. (6),(7); Eq. (3), z = 0)
  * out_half  = y32 rounded once to fp16.  Either output pointer may be NULL. */
 void oracle_epilogue(const int32_t *acc, const float *s_a, const float *s_w,

@@ -403,6 +403,68 @@ def test_weight_clipping_eq8_eq9_with_strengths(oracle):
         assert list(wq[r]) == [int(min(7, max(-8, rne_int(fp32_round(v / scale))))) for v in fr]
 
 
+# --------------------------------------------------------------------- W8A8
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 2), (3, 5, 6), (8, 7, 64), (2, 3, 34)])
+def test_w8_acc_vs_int64_brute_force(oracle, M, N, K):
+    g = synth.rng(907, M, N, K)
+    xq = g.integers(-128, 128, size=(M, K), dtype=np.int8)
+    w8 = g.integers(-128, 128, size=(N, K), dtype=np.int8)
+    xq[0, :] = -128
+    w8[0, :] = -128
+    if N > 1:
+        w8[1, :] = 127
+    acc = oracle.gemm_acc_i32_w8(xq, w8)
+    for m in range(M):
+        for n in range(N):
+            assert int(acc[m, n]) == sum(int(xq[m, k]) * int(w8[n, k]) for k in range(K))
+
+
+def test_w8_acc_blas_closed_forms_and_the_int4_special_case(oracle):
+    g = synth.rng(908)
+    xq = g.integers(-127, 128, size=(8, 1024), dtype=np.int8)
+    w8 = g.integers(-128, 128, size=(96, 1024), dtype=np.int8)
+    acc = oracle.gemm_acc_i32_w8(xq, w8)
+    assert np.array_equal(acc.astype(np.float64), xq.astype(np.float64) @ w8.astype(np.float64).T)   # exact in dgemm
+    # largest magnitude at the largest K of the contract stays inside int32
+    K = 65536
+    a = oracle.gemm_acc_i32_w8(np.full((1, K), -128, np.int8), np.stack([np.full(K, -128, np.int8), np.full(K, 127, np.int8)]))
+    assert a[0, 0] == 128 * 128 * K == 2 ** 30 and a[0, 1] == -128 * 127 * K
+    # codes that fit four bits: the W8A8 sum is the W4A8 sum of the same codes (two independent loops agree)
+    w4 = g.integers(-8, 8, size=(40, 1024), dtype=np.int8)
+    assert np.array_equal(oracle.gemm_acc_i32_w8(xq, w4), oracle.gemm_acc_i32(xq, oracle.pack_w4(w4)))
+    # a single +-1 weight selects (or negates) an activation column; permuting k in both operands changes nothing
+    sel = np.zeros((2, 1024), np.int8)
+    sel[0, 77] = 1
+    sel[1, 1000] = -1
+    s = oracle.gemm_acc_i32_w8(xq, sel)
+    assert np.array_equal(s[:, 0], xq[:, 77].astype(np.int32)) and np.array_equal(s[:, 1], -xq[:, 1000].astype(np.int32))
+    perm = g.permutation(1024)
+    assert np.array_equal(oracle.gemm_acc_i32_w8(xq[:, perm], w8[:, perm]), acc)
+
+
+def test_w8_weight_rtn_eq8_eq9_eight_bits(oracle):
+    w = synth.weights_fp16(24, 256, config_id=9)
+    w[5, :] = 0
+    w[6, 0] = np.float16(-1.0)
+    wq, s_w = oracle.quantize_weights_rtn8(w)
+    wf = w.astype(np.float64)
+    top = np.abs(wf).max(axis=1)
+    assert np.array_equal(s_w, top.astype(np.float32) / np.float32(127.0))
+    assert wq.min() >= -127 and wq.max() <= 127
+    nz = top > 0
+    assert np.array_equal(np.abs(wq[nz].astype(np.int32)).max(axis=1), np.full(nz.sum(), 127))
+    assert wq[6, 0] == -127 and s_w[5] == 0 and not wq[5].any()
+    err = np.abs(wf - wq * s_w[:, None].astype(np.float64))
+    assert np.all(err <= 0.5 * s_w[:, None] * (1 + 2.0 ** -20))
+    for r in (0, 6, 23):
+        codes, scale = exact_quantize_row(w[r], 127, -128, 127)
+        assert list(wq[r]) == codes and Fraction(float(s_w[r])) == scale
+    # it is the per-token activation quantiser applied to weight rows (same formula, same rounding)
+    xq, s_a = oracle.quantize_act(w)
+    assert np.array_equal(xq, wq) and np.array_equal(s_a.view(np.uint32), s_w.view(np.uint32))
+
+
 # --------------------------------------------------------------------- glue
 
 def test_silu_mul_vs_library_and_identities(oracle):
