@@ -170,6 +170,26 @@ int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const 
                                   uint8_t *wp, float *s_w, int N, int K, void *stream);
 
 /*
+ * W8A8 comparison variant (the paper sets its W4A8 against its own W8A8, Table 4): the same contraction and the
+ * same epilogue (Eq. (6),(7)) with int8 weight codes,
+ *   O[m][n] = fp16( float( sum_k Xq[m][k] * W8[n][k] ) * (s_a[m] * s_w[n]) ),   W8 in [-128, 127],
+ * run by the large-M kernel without the int4 conversion.  Per-channel 8-bit weights (Eq. (8),(9) with 8 bits,
+ * gamma = beta = 1: s_w = absmax / 127) are what w4a8_quantize_act computes when given the weight matrix as its
+ * rows, so there is no separate weight quantiser.
+ *   Layout of wt: 4096-byte blocks; block (nb, kb), nb = n / 32, kb = k / 128, starts at ((nb * KB) + kb) * 4096,
+ *   KB = ceil(K / 128); inside a block the 16-byte chunk (c, r), c = 0..7, r = 0..31, at (c * 32 + r) * 16 holds
+ *   the codes k = 128 kb + 16 c .. + 15 of channel 32 nb + r.  Channels >= N and k >= K hold zeros.
+ * w8a8_tiled_weight_bytes: size of wt in bytes (0 for a shape outside the contract).
+ * w8a8_tile_weights: w8 [N][K] int8 (device) in -> wt (device, 16-byte aligned) out.
+ * w8a8_gemm_tiled: exactly one of out_fp16 / acc_i32 non-NULL (raw int32 sums for tests; s_a, s_w may then be NULL);
+ *   variant = output tile as for W4A8_TILING_PREFILL_TILED, 0 = library's choice.  Any M.
+ */
+size_t w8a8_tiled_weight_bytes(int N, int K);
+int w8a8_tile_weights(const int8_t *w8, uint8_t *wt, int N, int K, void *stream);
+int w8a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w,
+                    void *out_fp16, int32_t *acc_i32, int M, int N, int K, int variant, void *stream);
+
+/*
  * Glue between the gate/up GEMM and the down GEMM of a LLaMA MLP:
  *   h[m][i] = fp16( silu(gate_up[m][i]) * gate_up[m][I + i] ),  fp32 arithmetic.
  *   gate_up_fp16 [M][2I] in, h_fp16 [M][I] out.  I % 8 == 0.

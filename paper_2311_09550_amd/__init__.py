@@ -53,6 +53,12 @@ def lib():
         L.w4a8_tiled_weight_bytes.argtypes = [i, i]
         L.w4a8_tile_weights.argtypes = [vp, vp, i, i, vp]
         L.w4a8_gemm_tiled.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp]
+        L.w8a8_tiled_weight_bytes.restype = sz
+        L.w8a8_tiled_weight_bytes.argtypes = [i, i]
+        L.w8a8_tile_weights.argtypes = [vp, vp, i, i, vp]
+        L.w8a8_gemm_tiled.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+        L.w8a8_tile_weights.restype = i
+        L.w8a8_gemm_tiled.restype = i
         for name in ("w4a8_quantize_act", "w4a8_gemm", "w4a8_gemm_acc_i32", "w4a8_gemm_tuned",
                      "w4a8_quantize_weights", "w4a8_quantize_weights_clipped", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host",
                      "w4a8_tile_weights", "w4a8_gemm_tiled"):
@@ -213,6 +219,47 @@ def w4a8_gemm_tiled(xq, s_a, wt, s_w, out=None):
         raise ValueError("out shape mismatch")
     _check(lib().w4a8_gemm_tiled(_dev(xq, torch.int8, "xq"), _dev(s_a, torch.float32, "s_a"), _dev(wt, torch.uint8, "wt"),
                                  _dev(s_w, torch.float32, "s_w"), _dev(out, torch.float16, "out"), M, N, K, _stream()))
+    return out
+
+
+def w8a8_tiled_weight_bytes(N: int, K: int) -> int:
+    return int(lib().w8a8_tiled_weight_bytes(N, K))
+
+
+def w8a8_tile_weights(w8, wt=None):
+    """int8 [N][K] weight codes -> flat uint8 array in the tiled layout of the W8A8 variant."""
+    torch = _torch()
+    N, K = w8.shape
+    nbytes = w8a8_tiled_weight_bytes(N, K)
+    if nbytes == 0:
+        _check(-2)
+    wt = torch.empty((nbytes,), dtype=torch.uint8, device=w8.device) if wt is None else wt
+    if wt.numel() != nbytes:
+        raise ValueError("wt size mismatch")
+    _check(lib().w8a8_tile_weights(_dev(w8, torch.int8, "w8"), _dev(wt, torch.uint8, "wt"), N, K, _stream()))
+    return wt
+
+
+def w8a8_gemm_tiled(xq, s_a, wt, s_w, N=None, variant: int = 0, want_acc: bool = False, out=None):
+    """W8A8 linear over tiled int8 weights -> fp16 [M][N], or the raw int32 sums when want_acc."""
+    torch = _torch()
+    M, K = xq.shape
+    N = s_w.shape[0] if N is None else N
+    if wt.numel() != w8a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (N, K)")
+    if want_acc:
+        out = torch.empty((M, N), dtype=torch.int32, device=xq.device) if out is None else out
+        o16, o32 = None, _dev(out, torch.int32, "acc")
+        sa = None if s_a is None else _dev(s_a, torch.float32, "s_a")
+        sw = None if s_w is None else _dev(s_w, torch.float32, "s_w")
+    else:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device) if out is None else out
+        o16, o32 = _dev(out, torch.float16, "out"), None
+        sa, sw = _dev(s_a, torch.float32, "s_a"), _dev(s_w, torch.float32, "s_w")
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    _check(lib().w8a8_gemm_tiled(_dev(xq, torch.int8, "xq"), sa, _dev(wt, torch.uint8, "wt"), sw, o16, o32, M, N, K, variant,
+                                 _stream()))
     return out
 
 

@@ -112,6 +112,32 @@ int choose_tiled_tile(int M, int N) {
     return best;
 }
 
+// The same choice for the int8-weight variant, whose weight stages take twice the LDS (shallower rings, and the
+// 128 x 256 tile fits a compute unit only once).
+int choose_tiled_tile8(int M, int N) {
+    const int cus = compute_units();
+    auto count = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    if (count(128, 128) * 4 < (long long)cus * 3) {
+        if (M <= 32) return kTiled32x128;
+        return count(64, 128) * 4 >= (long long)cus * 3 ? kTiled64x128 : kTiled64x64;
+    }
+    struct Option { int id, bm, bn, per_cu; double eff; };
+    const Option options[] = {{kTiled256x256, 256, 256, 1, 1.00},
+                              {kTiled128x256, 128, 256, 1, 0.80},
+                              {kTiled128x128, 128, 128, 2, 0.85}};
+    int best = kTiled256x256;
+    double best_cost = 0;
+    for (const Option &o : options) {
+        const long long tiles = count(o.bm, o.bn);
+        const long long slots = (long long)cus * o.per_cu;
+        const long long full = tiles / slots, rest = tiles % slots;
+        const double last = rest == 0 ? 0.0 : (o.per_cu == 1 || rest * 2 > slots ? 1.0 : 0.5);
+        const double cost = ((double)full + last) * o.bm * o.bn * o.per_cu / o.eff;
+        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = o.id; }
+    }
+    return best;
+}
+
 // Tiling choice.  Small M streams the weights once (HBM bound); large M goes to the LDS-staged tiling
 // (matrix-core bound).  `variant` refines a forced tiling (see w4a8.h); 0 lets the library choose.
 int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
@@ -253,6 +279,39 @@ int w4a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const
                     int K, void *stream) {
     if (!out_fp16) return W4A8_ERR_NULL;
     return run_gemm(xq, s_a, wt, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_PREFILL_TILED, 0, stream);
+}
+
+// ---- W8A8 comparison variant: int8 weight codes in the tiled layout, the same kernels without the int4 conversion
+
+size_t w8a8_tiled_weight_bytes(int N, int K) {
+    if (check_gemm_shape(1, N, K)) return 0;
+    return tiled_weight_bytes(N, K, 8);
+}
+
+int w8a8_tile_weights(const int8_t *w8, uint8_t *wt, int N, int K, void *stream) {
+    if (!w8 || !wt) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(1, N, K)) return e;
+    if (misaligned(w8) || misaligned(wt)) return W4A8_ERR_ALIGN;
+    return launch_tile_weights8(w8, wt, N, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+}
+
+int w8a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
+                    int32_t *acc_i32, int M, int N, int K, int variant, void *stream) {
+    const bool want_acc = acc_i32 != nullptr;
+    if ((out_fp16 != nullptr) == want_acc) return W4A8_ERR_NULL;  // exactly one output
+    if (!xq || !wt) return W4A8_ERR_NULL;
+    if (!want_acc && (!s_a || !s_w)) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(M, N, K)) return e;
+    if (variant < 0 || variant > kTiledTileMax) return W4A8_ERR_ARG;
+    if (misaligned(xq) || misaligned(wt) || misaligned(out_fp16) || misaligned(acc_i32) || (s_w && misaligned(s_w)))
+        return W4A8_ERR_ALIGN;
+    PrefillArgs a{};
+    a.xq = xq; a.s_a = s_a; a.wp = wt; a.s_w = s_w;
+    a.out = out_fp16; a.acc_out = acc_i32;
+    a.M = M; a.N = N; a.K = K; a.ldc = N;
+    const int tile = variant ? variant : choose_tiled_tile8(M, N);
+    return launch_gemm_prefill_tiled(a, want_acc, tile, static_cast<hipStream_t>(stream), 8) == hipSuccess ? W4A8_OK
+                                                                                                             : W4A8_ERR_LAUNCH;
 }
 
 int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, int K, void *stream) {

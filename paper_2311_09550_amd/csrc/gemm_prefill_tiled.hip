@@ -91,20 +91,27 @@ __global__ __launch_bounds__(256) void tile_weights_kernel(const uint8_t *__rest
 
 }  // namespace
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT>
+// WBITS = 4: the W4A8 kernel described above.  WBITS = 8: the W8A8 comparison variant (the paper's Table 4 sets its
+// W4A8 against W8A8): int8 weight codes in blocks of 32 channels x 128 k = 4 KB, chunk (c, r), c = 0..7, at
+// (c * 32 + r) * 16 holding k = 128 kb + 16 c .. + 15 of channel 32 nb + r; a fragment is an MFMA operand as it is.
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS = 4>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(PrefillArgs p) {
+    static_assert(WBITS == 4 || WBITS == 8, "int4 or int8 weight codes");
+    constexpr bool W8 = WBITS == 8;
+    constexpr int kBlock = kTiledBlockK * 32 * WBITS / 8;  // bytes of a weight block: 2 KB or 4 KB
+    constexpr int kParts = kBlock / 1024;                  // wave loads per block
     constexpr int kWaves = WM * WN;
     constexpr int BM = 32 * MTW * WM;
     constexpr int BN = 32 * NTW * WN;
-    constexpr int A_TOTAL = BM / 8;   // wave loads (8 rows x 128 B) of an activation stage
-    constexpr int B_TOTAL = BN / 16;  // wave loads (half a 2 KB block) of a weight stage
+    constexpr int A_TOTAL = BM / 8;                 // wave loads (8 rows x 128 B) of an activation stage
+    constexpr int B_TOTAL = (BN / 32) * kParts;     // wave loads (1 KB of a weight block) of a weight stage
     static_assert(A_TOTAL % kWaves == 0 && (kWaves & 1) == 0, "activation loads must split evenly over an even wave count");
     constexpr int A_LOADS = A_TOTAL / kWaves;
     constexpr int B_LOADS = (B_TOTAL + kWaves - 1) / kWaves;
     constexpr bool kRagged = B_LOADS * kWaves != B_TOTAL;
     constexpr int kLoads = A_LOADS + B_LOADS;  // per wave and stage, the same for every wave: the waits count on it
     constexpr int A_STAGE = BM * 128;
-    constexpr int B_STAGE = BN * 64;
+    constexpr int B_STAGE = (BN / 32) * kBlock;
     constexpr int kBBase = STAGES * A_STAGE;
     constexpr int kSpare = STAGES * (A_STAGE + B_STAGE);  // 1 KB that absorbs the surplus loads of an uneven split
     static_assert(STAGES >= 2 && (STAGES - 1) * kLoads < 64, "outstanding loads must fit the counter");
@@ -144,7 +151,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         return r;
     };
     const v4i a_rsrc = make_rsrc(p.xq, (size_t)p.M * p.K);
-    const v4i b_rsrc = make_rsrc(p.wp, (size_t)nb_total * st_total * kTiledBlockBytes);
+    const v4i b_rsrc = make_rsrc(p.wp, (size_t)nb_total * st_total * kBlock);
 
     // Activation wave load L covers rows 8L .. 8L+7: lane -> row 8L + lane/8, physical slot lane%8, which receives
     // the logical chunk slot ^ fx(row).  With an even wave count fx(row) is the same for all loads of a lane.
@@ -156,12 +163,14 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         const int m = bm0 + 8 * (i * kWaves + wave) + (lane >> 3);
         a_off[i] = m < p.M ? (unsigned)m * (unsigned)p.K + a_chunk * 16 : kNowhere;
     }
-    // Weight wave load L covers half L%2 of the tile's 32-channel block L/2.
+    // Weight wave load L covers the 1 KB part L % kParts of the tile's 32-channel block L / kParts.
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) {
         const int L = i * kWaves + wave;
-        const int nb = (bn0 >> 5) + (L >> 1);
-        b_off[i] = (L < B_TOTAL && nb < nb_total) ? ((unsigned)nb * (unsigned)st_total * 2 + (L & 1)) * 1024u + lane * 16 : kNowhere;
+        const int nb = (bn0 >> 5) + L / kParts;
+        b_off[i] = (L < B_TOTAL && nb < nb_total)
+                       ? ((unsigned)nb * (unsigned)st_total * kParts + (L % kParts)) * 1024u + lane * 16
+                       : kNowhere;
     }
 
     // The load is written in assembly on purpose: the compiler orders LDS reads after every LDS-writing load it knows
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                 const int i = j - A_LOADS;
                 const int L = i * kWaves + wave;
                 const unsigned dst = (kRagged && L >= B_TOTAL) ? kSpare : kBBase + slot * B_STAGE + L * 1024;
-                dma16(b_rsrc, lds_base + dst, b_off[i], st * kTiledBlockBytes);
+                dma16(b_rsrc, lds_base + dst, b_off[i], st * kBlock);
             }
         }
     };
@@ -210,21 +219,28 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     {
         const int row = wm * (32 * MTW) + idx;  // rows of the other m tiles differ by 32: same swizzle
 #pragma unroll
-        for (int j = 0; j < 4; ++j) xa[j] = row * 128 + (((4 * (j >> 1) + 2 * g + (j & 1)) ^ fx(row)) << 4);
+        for (int j = 0; j < 4; ++j) {
+            // int8 weights: step j, lane group g holds k = 32 j + 16 g .. + 15, i.e. activation chunk 2 j + g
+            const int chunk = W8 ? 2 * j + g : 4 * (j >> 1) + 2 * g + (j & 1);
+            xa[j] = row * 128 + ((chunk ^ fx(row)) << 4);
+        }
     }
-    const int wa = kBBase + wn * (NTW * 2048) + (g * 32 + idx) * 16;
+    const int wa = kBBase + wn * (NTW * kBlock) + (g * 32 + idx) * 16;
     auto read_x = [&](v4u(&dst)[MTW], int slot, int j) {
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt) dst[mt] = *(const v4u *)(&lds[slot * A_STAGE + xa[j] + mt * 4096]);
     };
-    auto read_w = [&](v4u(&dst)[NTW], int slot, int s) {
+    // weight fragments of the pair of chunks q: int4 -> q = 0, 1 serves MFMA steps 2q and 2q + 1 (halves h = 0, 1 of
+    // the fragment); int8 -> q = 0 .. 3 serves MFMA step q
+    auto read_w = [&](v4u(&dst)[NTW], int slot, int q) {
 #pragma unroll
-        for (int t = 0; t < NTW; ++t) dst[t] = *(const v4u *)(&lds[slot * B_STAGE + wa + t * 2048 + s * 1024]);
+        for (int t = 0; t < NTW; ++t) dst[t] = *(const v4u *)(&lds[slot * B_STAGE + wa + t * kBlock + q * 1024]);
     };
     auto mfma_step = [&](const v4u(&x)[MTW], const v4u(&w)[NTW], int h) {
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
-            const v4i wop = h == 0 ? w_operand_tiled(w[t].x, w[t].y) : w_operand_tiled(w[t].z, w[t].w);
+            const v4i wop = W8 ? v4i{(int)w[t].x, (int)w[t].y, (int)w[t].z, (int)w[t].w}
+                               : (h == 0 ? w_operand_tiled(w[t].x, w[t].y) : w_operand_tiled(w[t].z, w[t].w));
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt)
                 acc[mt][t] = mfma32(wop, v4i{(int)x[mt].x, (int)x[mt].y, (int)x[mt].z, (int)x[mt].w}, acc[mt][t]);
@@ -265,21 +281,28 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         // The fragments of step 0 were requested eight MFMAs ago; waiting for them here, before the next reads go
         // out, costs nothing and spares the wait the compiler would otherwise place behind those reads.
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+        // Weight registers: int4 fragments hold two steps (w0: steps 0, 1; w1: steps 2, 3); int8 fragments one step
+        // each, w0 and w1 taking turns (w0: steps 0, 2; w1: steps 1, 3).
         read_x(x1, slot, 1);
+        if (W8) read_w(w1, slot, 1);
         if (have_target) issue(target, prev, 0, 3);
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(x0, w0, 0);
         __builtin_amdgcn_sched_barrier(0);
         read_x(x0, slot, 2);
-        read_w(w1, slot, 1);
+        if (W8)
+            read_w(w0, slot, 2);
+        else
+            read_w(w1, slot, 1);
         if (have_target) issue(target, prev, 1, 3);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_step(x1, w0, 1);
+        mfma_step(x1, *(W8 ? &w1 : &w0), 1);
         __builtin_amdgcn_sched_barrier(0);
         read_x(x1, slot, 3);
+        if (W8) read_w(w1, slot, 3);
         if (have_target) issue(target, prev, 2, 3);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_step(x0, w1, 0);
+        mfma_step(x0, *(W8 ? &w0 : &w1), 0);
         __builtin_amdgcn_sched_barrier(0);
         // Every fragment of this stage is in registers once the reads above have returned, so after the barrier the
         // slot can be refilled; stage st + 1 must be in LDS for every wave.
@@ -308,6 +331,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     // its 32-row slabs around in LDS (the ring is idle now: the last barrier of the loop lies behind every wave's
     // last fragment read and every load has landed) and stores whole 16-byte runs of 8 channels, 8 or more lanes per
     // row, i.e. whole cache lines.
+    // int4 sums are sixteen times the true sums (the nibbles sat in the high half of their bytes); int8 sums are true
+    auto deq = [](int a, float s_a, float s_w) { return W8 ? (float)a * (s_a * s_w) : dequant(a, s_a, s_w); };
     if (!ACC_OUT && (p.ldc & 7) == 0) {
         constexpr int kRowBytes = 64 * NTW;        // fp16 bytes of a slab row (32 NTW channels)
         constexpr int kPitch = kRowBytes + 16;     // padded: rows 16 apart, not 1 apart, share banks
@@ -338,8 +363,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                         sw.w = p.s_w[last];
                     }
                     v2u o;
-                    o.x = pack_f16x2(dequant(acc[mt][t][4 * q], sa, sw.x), dequant(acc[mt][t][4 * q + 1], sa, sw.y));
-                    o.y = pack_f16x2(dequant(acc[mt][t][4 * q + 2], sa, sw.z), dequant(acc[mt][t][4 * q + 3], sa, sw.w));
+                    o.x = pack_f16x2(deq(acc[mt][t][4 * q], sa, sw.x), deq(acc[mt][t][4 * q + 1], sa, sw.y));
+                    o.y = pack_f16x2(deq(acc[mt][t][4 * q + 2], sa, sw.z), deq(acc[mt][t][4 * q + 3], sa, sw.w));
                     *(v2u *)(slab + idx * kPitch + nl * 2) = o;
                 }
             }
@@ -381,7 +406,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                 const v4i s = v4i{acc[mt][t][4 * q], acc[mt][t][4 * q + 1], acc[mt][t][4 * q + 2], acc[mt][t][4 * q + 3]};
                 if (ACC_OUT) {
                     int *dst = p.acc_out + (size_t)m * p.ldc + n;
-                    const v4i v = v4i{s.x >> 4, s.y >> 4, s.z >> 4, s.w >> 4};  // exact: every sum is a multiple of 16
+                    constexpr int kShift = W8 ? 0 : 4;  // int4: exact, every sum is a multiple of 16
+                    const v4i v = v4i{s.x >> kShift, s.y >> kShift, s.z >> kShift, s.w >> kShift};
                     if (vec_ok && n + 3 < p.N) {
                         *(v4i *)dst = v;
                     } else {
@@ -394,13 +420,13 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                     if (vec_ok && n + 3 < p.N) {
                         const float4 sw = *(const float4 *)(p.s_w + n);
                         v2u o;
-                        o.x = pack_f16x2(dequant(s.x, sa, sw.x), dequant(s.y, sa, sw.y));
-                        o.y = pack_f16x2(dequant(s.z, sa, sw.z), dequant(s.w, sa, sw.w));
+                        o.x = pack_f16x2(deq(s.x, sa, sw.x), deq(s.y, sa, sw.y));
+                        o.y = pack_f16x2(deq(s.z, sa, sw.z), deq(s.w, sa, sw.w));
                         *(v2u *)dst = o;
                     } else {
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            if (n + j < p.N) dst[j] = f32_to_f16_bits(dequant(s[j], sa, p.s_w[n + j]));
+                            if (n + j < p.N) dst[j] = f32_to_f16_bits(deq(s[j], sa, p.s_w[n + j]));
                     }
                 }
             }
@@ -410,11 +436,12 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
 
 namespace {
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT>
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS>
 hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
-    constexpr int kLdsBytes = STAGES * (BM * 128 + BN * 64) + 1024;
-    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT>;
+    constexpr int kLdsBytes = STAGES * (BM * 128 + BN * 16 * WBITS) + 1024;
+    static_assert(kLdsBytes <= 160 * 1024, "a workgroup's ring must fit the compute unit's LDS");
+    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS>;
     // more than 64 KB of LDS per workgroup has to be asked for, once per device
     static bool raised[64] = {};
     int dev = 0;
@@ -428,24 +455,41 @@ hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int MTW, int NTW, int WM, int WN, int STAGES>
+template <int MTW, int NTW, int WM, int WN, int STAGES, int WBITS = 4>
 hipError_t launch_tile(PrefillArgs p, bool acc_out, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     const int total = p.tiles_m * p.tiles_n;
     const dim3 grid(8 * ((total + 7) / 8));
-    return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true>(p, grid, stream)
-                   : launch_one<MTW, NTW, WM, WN, STAGES, false>(p, grid, stream);
+    return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true, WBITS>(p, grid, stream)
+                   : launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS>(p, grid, stream);
+}
+
+// One thread per 16-byte chunk of the tiled int8 array (W8A8 variant): a plain gather, no reordering inside a chunk.
+__global__ __launch_bounds__(256) void tile_weights8_kernel(const int8_t *__restrict__ w8, uint8_t *__restrict__ wt, int N,
+                                                            int K, int kb_total, long long chunks) {
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= chunks) return;
+    const long long block = q >> 8;
+    const int c = (int)(q & 255) >> 5, r = (int)(q & 31);
+    const long long nb = block / kb_total;
+    const int kb = (int)(block - nb * kb_total);
+    const long long n = nb * 32 + r;
+    const int k0 = kb * 128 + c * 16;
+    v4u v = v4u{0u, 0u, 0u, 0u};
+    if (n < N && k0 < K) v = *(const v4u *)(w8 + (size_t)n * (size_t)K + k0);
+    *(v4u *)(wt + (size_t)q * 16) = v;
 }
 
 }  // namespace
 
-hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream) {
+hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream, int wbits) {
     // slices keep every byte offset inside the kernel below 2^32; slices of N start on a 32-channel block
     const long long kMaxBytes = 0xF0000000ll;
     const long long kb_total = (p.K + kTiledBlockK - 1) / kTiledBlockK;
-    long long m_rows = kMaxBytes / p.K, n_rows = kMaxBytes / (kb_total * (kTiledBlockK / 2));
+    const long long block_bytes = (long long)kTiledBlockBytes * wbits / 4;
+    long long m_rows = kMaxBytes / p.K, n_rows = kMaxBytes / (kb_total * (block_bytes / 32));
     m_rows -= m_rows % 256;
     n_rows -= n_rows % 1280;  // a multiple of every tile width
     for (long long n0 = 0; n0 < p.N; n0 += n_rows) {
@@ -454,22 +498,39 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
             q.M = (int)((p.M - m0) < m_rows ? (p.M - m0) : m_rows);
             q.N = (int)((p.N - n0) < n_rows ? (p.N - n0) : n_rows);
             q.xq = p.xq + (size_t)m0 * p.K;
-            q.wp = p.wp + (size_t)(n0 / 32) * (size_t)kb_total * kTiledBlockBytes;
+            q.wp = p.wp + (size_t)(n0 / 32) * (size_t)kb_total * (size_t)block_bytes;
             if (p.s_a) q.s_a = p.s_a + m0;
             if (p.s_w) q.s_w = p.s_w + n0;
             if (p.out) q.out = (unsigned short *)p.out + (size_t)m0 * p.ldc + n0;
             if (p.acc_out) q.acc_out = p.acc_out + (size_t)m0 * p.ldc + n0;
             hipError_t e;
-            switch (tile) {
-                case kTiled256x256: e = launch_tile<4, 2, 2, 4, 3>(q, acc_out, stream); break;
-                case kTiled256x256Square: e = launch_tile<2, 4, 4, 2, 3>(q, acc_out, stream); break;
-                case kTiled128x256: e = launch_tile<4, 2, 1, 4, 2>(q, acc_out, stream); break;
-                case kTiled128x160: e = launch_tile<1, 5, 4, 1, 3>(q, acc_out, stream); break;
-                case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3>(q, acc_out, stream); break;
-                case kTiled64x128: e = launch_tile<1, 2, 2, 2, 4>(q, acc_out, stream); break;
-                case kTiled64x64: e = launch_tile<1, 1, 2, 2, 4>(q, acc_out, stream); break;
-                case kTiled32x128: e = launch_tile<1, 1, 1, 4, 4>(q, acc_out, stream); break;
-                default: e = hipErrorInvalidConfiguration;
+            if (wbits == 4) {
+                switch (tile) {
+                    case kTiled256x256: e = launch_tile<4, 2, 2, 4, 3>(q, acc_out, stream); break;
+                    case kTiled256x256Square: e = launch_tile<2, 4, 4, 2, 3>(q, acc_out, stream); break;
+                    case kTiled128x256: e = launch_tile<4, 2, 1, 4, 2>(q, acc_out, stream); break;
+                    case kTiled128x160: e = launch_tile<1, 5, 4, 1, 3>(q, acc_out, stream); break;
+                    case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3>(q, acc_out, stream); break;
+                    case kTiled64x128: e = launch_tile<1, 2, 2, 2, 4>(q, acc_out, stream); break;
+                    case kTiled64x64: e = launch_tile<1, 1, 2, 2, 4>(q, acc_out, stream); break;
+                    case kTiled32x128: e = launch_tile<1, 1, 1, 4, 4>(q, acc_out, stream); break;
+                    default: e = hipErrorInvalidConfiguration;
+                }
+            } else if (wbits == 8) {
+                // int8 weight stages are twice as large: shallower rings for the same LDS
+                switch (tile) {
+                    case kTiled256x256: e = launch_tile<4, 2, 2, 4, 2, 8>(q, acc_out, stream); break;
+                    case kTiled256x256Square: e = launch_tile<2, 4, 4, 2, 2, 8>(q, acc_out, stream); break;
+                    case kTiled128x256: e = launch_tile<4, 2, 1, 4, 2, 8>(q, acc_out, stream); break;
+                    case kTiled128x160: e = launch_tile<1, 5, 4, 1, 2, 8>(q, acc_out, stream); break;
+                    case kTiled128x128: e = launch_tile<2, 2, 2, 2, 2, 8>(q, acc_out, stream); break;
+                    case kTiled64x128: e = launch_tile<1, 2, 2, 2, 3, 8>(q, acc_out, stream); break;
+                    case kTiled64x64: e = launch_tile<1, 1, 2, 2, 4, 8>(q, acc_out, stream); break;
+                    case kTiled32x128: e = launch_tile<1, 1, 1, 4, 3, 8>(q, acc_out, stream); break;
+                    default: e = hipErrorInvalidConfiguration;
+                }
+            } else {
+                e = hipErrorInvalidConfiguration;
             }
             if (e != hipSuccess) return e;
         }
@@ -477,16 +538,25 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
     return hipSuccess;
 }
 
-size_t tiled_weight_bytes(int N, int K) {
-    return (size_t)((N + 31) / 32) * (size_t)((K + kTiledBlockK - 1) / kTiledBlockK) * kTiledBlockBytes;
+size_t tiled_weight_bytes(int N, int K, int wbits) {
+    return (size_t)((N + 31) / 32) * (size_t)((K + kTiledBlockK - 1) / kTiledBlockK) * (size_t)(kTiledBlockBytes * wbits / 4);
 }
 
 hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream) {
     const int kb_total = (K + kTiledBlockK - 1) / kTiledBlockK;
-    const long long chunks = (long long)(tiled_weight_bytes(N, K) / 16);
+    const long long chunks = (long long)(tiled_weight_bytes(N, K, 4) / 16);
     const long long blocks = (chunks + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
     hipLaunchKernelGGL(tile_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, wp, wt, N, K, kb_total, chunks);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_weights8(const int8_t *w8, uint8_t *wt, int N, int K, hipStream_t stream) {
+    const int kb_total = (K + kTiledBlockK - 1) / kTiledBlockK;
+    const long long chunks = (long long)(tiled_weight_bytes(N, K, 8) / 16);
+    const long long blocks = (chunks + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tile_weights8_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w8, wt, N, K, kb_total, chunks);
     return hipGetLastError();
 }
 

@@ -70,9 +70,11 @@ constexpr int kTiled64x64 = 7;          // 4 waves of 32 x 32
 constexpr int kTiled32x128 = 8;         // 4 waves of 32 x 32 side by side
 constexpr int kTiledTileMax = 8;
 
-size_t tiled_weight_bytes(int N, int K);
+// wbits = 4: packed int4 codes (blocks of 2 KB); wbits = 8: int8 codes of the W8A8 comparison variant (blocks of 4 KB)
+size_t tiled_weight_bytes(int N, int K, int wbits = 4);
 hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream);
-hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
+hipError_t launch_tile_weights8(const int8_t *w8, uint8_t *wt, int N, int K, hipStream_t stream);
+hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream, int wbits = 4);
 
 hipError_t launch_gemm_prefill(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
 hipError_t launch_prefill_dma_slice(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);

@@ -26,7 +26,7 @@ def L():
 def declared_symbols():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(w4a8_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(w[48]a8_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol(L):
@@ -99,6 +99,14 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_tile_weights(p, odd, 32, 128, null) == -3
     assert L.w4a8_gemm_tiled(p, p, p, p, null, 1, 16, 32, null) == -1
     assert L.w4a8_gemm_tiled(p, p, p, p, p, 1, 16, 48, null) == -2
+    assert L.w8a8_tile_weights(null, p, 32, 128, null) == -1
+    assert L.w8a8_tile_weights(p, p, 32, 100, null) == -2
+    assert L.w8a8_gemm_tiled(p, p, p, p, p, p, 1, 16, 32, 0, null) == -1        # both outputs
+    assert L.w8a8_gemm_tiled(p, p, p, p, null, null, 1, 16, 32, 0, null) == -1  # no output
+    assert L.w8a8_gemm_tiled(p, p, p, p, p, null, 1, 16, 48, 0, null) == -2
+    assert L.w8a8_gemm_tiled(p, p, p, p, p, null, 1, 16, 32, 9, null) == -7
+    assert L.w8a8_gemm_tiled(p, p, odd, p, p, null, 1, 16, 32, 0, null) == -3
+    assert w4a8.w8a8_tiled_weight_bytes(32, 128) == 4096 and w4a8.w8a8_tiled_weight_bytes(33, 160) == 4 * 4096
 
 
 def test_tiled_weight_bytes_counts_whole_blocks(L):
