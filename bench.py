@@ -59,6 +59,7 @@ def parse_args():
     ap.add_argument("--M", type=int, default=1024, help="tokens per step (default: the 1024-token context)")
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1,4,16 weight-streaming measurements")
     ap.add_argument("--no-layer-stack", action="store_true", help="skip the graph-replayed layer stack at M=1..2048")
+    ap.add_argument("--no-w8a8", action="store_true", help="skip the per-GEMM W4A8 / W8A8 comparison")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -221,6 +222,52 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
     return rows
 
 
+def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
+    """The paper sets its W4A8 against its own W8A8 (Table 4).  Here, per GEMM: the same large-M kernel over tiled int4
+    and tiled int8 weights of the same fp16 matrix, every launch on a different weight copy (copies exceed the last-level
+    cache three times, so weights come from HBM), batches replayed from a HIP graph."""
+    rows = []
+    for name, (N, K) in synth.LLAMA_SHAPES[model].items():
+        w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).cuda()
+        wp, s_w4 = w4a8.w4a8_quantize_weights(w)
+        w8, s_w8 = w4a8.w4a8_quantize_act(w)          # per-channel int8: the per-token quantiser on weight rows
+        del w
+        wt = {4: w4a8.w4a8_tile_weights(wp), 8: w4a8.w8a8_tile_weights(w8)}
+        del wp, w8
+        copies = {b: max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wt[b].numel()) + 1) for b in (4, 8)}
+        wts = {b: [wt[b]] + [wt[b].clone() for _ in range(copies[b] - 1)] for b in (4, 8)}
+        for M in Ms:
+            x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
+            xq, s_a = w4a8.w4a8_quantize_act(x)
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            us = {}
+            for b in (4, 8):
+                call = (lambda t: w4a8.w4a8_gemm_tiled(xq, s_a, t, s_w4, out=out)) if b == 4 else \
+                       (lambda t: w4a8.w8a8_gemm_tiled(xq, s_a, t, s_w8, out=out))
+                call(wts[b][0])
+                torch.cuda.synchronize()
+                n = max(copies[b], 8)
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for i in range(n):
+                        call(wts[b][i % copies[b]])
+                graph.replay()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(iters):
+                    graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                us[b] = e0.elapsed_time(e1) * 1e3 / (n * iters)
+                del graph
+            rows.append({"linear": name, "M": M, "w4a8_us": round(us[4], 2), "w8a8_us": round(us[8], 2),
+                         "w8_over_w4": round(us[8] / us[4], 3)})
+        del wts, wt
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(synth, M, target_seconds):
     """The CPU oracle, as it stands, on the first rows of the same step (all four linears, complete N and K)."""
     import numpy as np
@@ -339,6 +386,8 @@ def main():
                                      "unit": "GB/s", "frac": round(mean_bytes / mean_us / 1e3 / HBM_PEAK_GBS, 4),
                                      "traffic": None, "kernel": "gemm_decode_kernel",
                                      "worst": worst, "best": best}
+    if not args.no_w8a8:
+        result["w4a8_vs_w8a8"] = time_w4_vs_w8(torch, w4a8, synth)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(synth, M, args.cpu_seconds)
     print(json.dumps(result))

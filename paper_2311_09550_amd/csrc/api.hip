@@ -124,6 +124,7 @@ int choose_tiled_tile8(int M, int N) {
     struct Option { int id, bm, bn, per_cu; double eff; };
     const Option options[] = {{kTiled256x256, 256, 256, 1, 1.00},
                               {kTiled128x256, 128, 256, 1, 0.80},
+                              {kTiled128x160, 128, 160, 2, 0.95},
                               {kTiled128x128, 128, 128, 2, 0.85}};
     int best = kTiled256x256;
     double best_cost = 0;
