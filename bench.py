@@ -11,8 +11,10 @@ work of a step (2*M*N*K summed over the four linears) divided by the step time.
 
 The same run also reports the decode side of the metric (M = 1, 4, 16 on the same
 four shapes, weights rotated through more than the last-level cache so every byte
-comes from HBM), a roofline object for the dominant kernel and the CPU oracle's
-throughput on a bounded sample of the workload.
+comes from HBM), a roofline object for the dominant kernel, the layer stack at
+M = 1 .. 2048 replayed from a HIP graph (layer time and GEMM share), the per-GEMM
+ratio of the W8A8 comparison variant to W4A8, and the CPU oracle's throughput on
+a bounded sample of the workload.
 
 All inputs are seeded synthetic tensors generated on the host and resident in
 HBM before the timed region starts.
@@ -45,10 +47,10 @@ def gemm_ops(M, N, K):
 
 COPY_CALIBRATION_BYTES = 256 << 20
 # L2 fill + write-back bytes per GEMM launch of the default workload (mean over its four linears), from the two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/gemm_prefill_tiled_13b_traffic.md, each scaled by
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/gemm_prefill_tiled_13b_counters.md, each scaled by
 # what the counter reads for the 256 MiB copy of --copy-calibration.  Counters cannot be read from inside this
 # process, so the figure is carried here and reported only for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("13b", 1024): 158.9e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("13b", 1024): 139.5e6}
 
 
 def parse_args():
