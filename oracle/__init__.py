@@ -173,6 +173,34 @@ def gemm(xq, s_a, wp, s_w):
     return acc, y32, out
 
 
+def pack_u4(u):
+    """Unsigned codes [N][K] in [0, 15] -> uint8 [N][K/2], low nibble = even k (the vanilla unsigned storage)."""
+    u = np.ascontiguousarray(u)
+    if u.min() < 0 or u.max() > 15 or u.shape[1] % 2:
+        raise ValueError("codes outside [0, 15] or odd K")
+    u = u.astype(np.uint8)
+    return np.ascontiguousarray(u[:, 0::2] | (u[:, 1::2] << 4))
+
+
+def gemm_acc_i32_u4(xq, up):
+    """sum_k xq * (u - 8) over unsigned nibbles u."""
+    xq = _c(xq, np.int8)
+    up = _c(up, np.uint8)
+    M, K = xq.shape
+    N, K2 = up.shape
+    if 2 * K2 != K:
+        raise ValueError("shape mismatch")
+    acc = np.empty((M, N), np.int32)
+    _load().oracle_gemm_acc_i32_u4(_p(xq), _p(up), _p(acc), M, N, K)
+    return acc
+
+
+def gemm_u4(xq, s_a, up, s_w):
+    acc = gemm_acc_i32_u4(xq, up)
+    y32, out = epilogue(acc, s_a, s_w)
+    return acc, y32, out
+
+
 def gemm_acc_i32_w8(xq, w8):
     xq = _c(xq, np.int8)
     w8 = _c(w8, np.int8)

@@ -266,6 +266,25 @@ void oracle_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int 
     }
 }
 
+/* The "vanilla" unsigned storage the paper compares against (Sec. 5.3, App. A.1, Fig. 4(b)): offline 8 is added to
+ * every signed code so that it lies in [0, 15], the nibble stored is that unsigned value u, and the device subtracts
+ * 8 again before multiplying:  acc[m][n] = sum_k xq[m][k] * (u[n][k] - 8).  Same packing order as the signed format. */
+void oracle_gemm_acc_i32_u4(const int8_t *xq, const uint8_t *up, int32_t *acc, int M, int N, int K)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int m = 0; m < M; ++m) {
+            int32_t s = 0;
+            for (int k = 0; k < K; ++k) {
+                unsigned b = up[(size_t)n * (K / 2) + (k >> 1)];
+                int u = (int)((k & 1) ? (b >> 4) : (b & 15u));
+                s += (int32_t)xq[(size_t)m * K + k] * (int32_t)(u - 8);
+            }
+            acc[(size_t)m * N + n] = s;
+        }
+    }
+}
+
 /* The W8A8 counterpart (the paper's own comparison point, Table 4): the same sum with int8 weight codes
  * w8[N][K] stored one per byte.  |acc| <= 128 * 128 * K, inside int32 for K <= 65536. */
 void oracle_gemm_acc_i32_w8(const int8_t *xq, const int8_t *w8, int32_t *acc, int M, int N, int K)

@@ -403,6 +403,35 @@ def test_weight_clipping_eq8_eq9_with_strengths(oracle):
         assert list(wq[r]) == [int(min(7, max(-8, rne_int(fp32_round(v / scale))))) for v in fr]
 
 
+# ------------------------------------------------- vanilla unsigned storage
+
+def test_u4_paper_worked_example_and_equivalence_with_signed_storage(oracle):
+    """App. A.1: -7 plus 8 is stored as 0000 0001; subtracting 8 on the device gives the signed code back, so the sum
+    over unsigned nibbles equals the sum over the signed format of the same codes."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "sint4_worked_example.txt")) if l.strip() and l[0] != "#"]
+    for value, _twos, _nibble, _hi, _as_int8, uint4 in rows:
+        value, u = int(value), int(uint4, 2)
+        assert u == value + 8 and oracle.pack_u4(np.array([[u, 8]]))[0, 0] == (u | (8 << 4))
+        x = np.array([[3, 5]], np.int8)
+        assert oracle.gemm_acc_i32_u4(x, oracle.pack_u4(np.array([[u, 8]])))[0, 0] == 3 * value
+    g = synth.rng(909)
+    xq = g.integers(-128, 128, size=(6, 192), dtype=np.int8)
+    wq = g.integers(-8, 8, size=(20, 192), dtype=np.int8)
+    wq[0, :] = -8
+    wq[1, :] = 7
+    acc_u = oracle.gemm_acc_i32_u4(xq, oracle.pack_u4(wq.astype(np.int16) + 8))
+    assert np.array_equal(acc_u, oracle.gemm_acc_i32(xq, oracle.pack_w4(wq)))
+    # int64 brute force and the closed form sum x*u - 8*sum x
+    u = (wq.astype(np.int64) + 8)
+    want = xq.astype(np.int64) @ u.T - 8 * xq.astype(np.int64).sum(axis=1, keepdims=True)
+    assert np.array_equal(acc_u.astype(np.int64), want)
+    for m in range(2):
+        for n in range(3):
+            assert int(acc_u[m, n]) == sum(int(xq[m, k]) * (int(u[n, k]) - 8) for k in range(192))
+    with pytest.raises(ValueError):
+        oracle.pack_u4(np.array([[16, 0]]))
+
+
 # --------------------------------------------------------------------- W8A8
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 2), (3, 5, 6), (8, 7, 64), (2, 3, 34)])
