@@ -190,6 +190,18 @@ int w8a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const
                     void *out_fp16, int32_t *acc_i32, int M, int N, int K, int variant, void *stream);
 
 /*
+ * Ablation of the weight storage (the paper's "Asym GEMM", Sec. 5.3 / App. A.1 / Sec. 6.4): the vanilla unsigned
+ * format stores u = Wq + 8 in [0, 15] in each nibble and subtracts 8 again in registers before the multiplication,
+ *   O[m][n] = fp16( float( sum_k Xq[m][k] * (u[n][k] - 8) ) * (s_a[m] * s_w[n]) ),
+ * i.e. the result of w4a8_gemm_tiled for Wq = u - 8, at a higher conversion cost (7 instead of 3 vector operations per
+ * 8 weights).  ut is the TILED array made by w4a8_tile_weights from the packed unsigned codes
+ * (up[n][j] = u[n][2j] | u[n][2j+1] << 4); exactly one of out_fp16 / acc_i32 non-NULL; variant as for
+ * W4A8_TILING_PREFILL_TILED.  For measurements and tests; a deployment uses the signed format.
+ */
+int w4a8_gemm_tiled_unsigned(const int8_t *xq, const float *s_a, const uint8_t *ut, const float *s_w,
+                             void *out_fp16, int32_t *acc_i32, int M, int N, int K, int variant, void *stream);
+
+/*
  * Glue between the gate/up GEMM and the down GEMM of a LLaMA MLP:
  *   h[m][i] = fp16( silu(gate_up[m][i]) * gate_up[m][I + i] ),  fp32 arithmetic.
  *   gate_up_fp16 [M][2I] in, h_fp16 [M][I] out.  I % 8 == 0.

@@ -59,6 +59,8 @@ def lib():
         L.w8a8_gemm_tiled.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
         L.w8a8_tile_weights.restype = i
         L.w8a8_gemm_tiled.restype = i
+        L.w4a8_gemm_tiled_unsigned.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+        L.w4a8_gemm_tiled_unsigned.restype = i
         for name in ("w4a8_quantize_act", "w4a8_gemm", "w4a8_gemm_acc_i32", "w4a8_gemm_tuned",
                      "w4a8_quantize_weights", "w4a8_quantize_weights_clipped", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host",
                      "w4a8_tile_weights", "w4a8_gemm_tiled"):
@@ -260,6 +262,29 @@ def w8a8_gemm_tiled(xq, s_a, wt, s_w, N=None, variant: int = 0, want_acc: bool =
         raise ValueError("out shape mismatch")
     _check(lib().w8a8_gemm_tiled(_dev(xq, torch.int8, "xq"), sa, _dev(wt, torch.uint8, "wt"), sw, o16, o32, M, N, K, variant,
                                  _stream()))
+    return out
+
+
+def w4a8_gemm_tiled_unsigned(xq, s_a, ut, s_w, N=None, variant: int = 0, want_acc: bool = False, out=None):
+    """The storage ablation: tiled unsigned nibbles u = w + 8 -> fp16 [M][N], or the raw int32 sums when want_acc."""
+    torch = _torch()
+    M, K = xq.shape
+    N = s_w.shape[0] if N is None else N
+    if ut.numel() != w4a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (N, K)")
+    if want_acc:
+        out = torch.empty((M, N), dtype=torch.int32, device=xq.device) if out is None else out
+        o16, o32 = None, _dev(out, torch.int32, "acc")
+        sa = None if s_a is None else _dev(s_a, torch.float32, "s_a")
+        sw = None if s_w is None else _dev(s_w, torch.float32, "s_w")
+    else:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device) if out is None else out
+        o16, o32 = _dev(out, torch.float16, "out"), None
+        sa, sw = _dev(s_a, torch.float32, "s_a"), _dev(s_w, torch.float32, "s_w")
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    _check(lib().w4a8_gemm_tiled_unsigned(_dev(xq, torch.int8, "xq"), sa, _dev(ut, torch.uint8, "ut"), sw, o16, o32, M, N, K,
+                                          variant, _stream()))
     return out
 
 

@@ -296,8 +296,23 @@ int w8a8_tile_weights(const int8_t *w8, uint8_t *wt, int N, int K, void *stream)
     return launch_tile_weights8(w8, wt, N, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
 }
 
+static int gemm_tiled_variant(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
+                              int32_t *acc_i32, int M, int N, int K, int variant, void *stream, int wfmt);
+
 int w8a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
                     int32_t *acc_i32, int M, int N, int K, int variant, void *stream) {
+    return gemm_tiled_variant(xq, s_a, wt, s_w, out_fp16, acc_i32, M, N, K, variant, stream, 8);
+}
+
+// ---- ablation: the vanilla unsigned storage (u = w + 8 in the nibbles, 8 subtracted in registers), same tiled layout
+
+int w4a8_gemm_tiled_unsigned(const int8_t *xq, const float *s_a, const uint8_t *ut, const float *s_w, void *out_fp16,
+                             int32_t *acc_i32, int M, int N, int K, int variant, void *stream) {
+    return gemm_tiled_variant(xq, s_a, ut, s_w, out_fp16, acc_i32, M, N, K, variant, stream, kWeightsUnsigned4);
+}
+
+static int gemm_tiled_variant(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
+                              int32_t *acc_i32, int M, int N, int K, int variant, void *stream, int wfmt) {
     const bool want_acc = acc_i32 != nullptr;
     if ((out_fp16 != nullptr) == want_acc) return W4A8_ERR_NULL;  // exactly one output
     if (!xq || !wt) return W4A8_ERR_NULL;
@@ -310,9 +325,10 @@ int w8a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const
     a.xq = xq; a.s_a = s_a; a.wp = wt; a.s_w = s_w;
     a.out = out_fp16; a.acc_out = acc_i32;
     a.M = M; a.N = N; a.K = K; a.ldc = N;
-    const int tile = variant ? variant : choose_tiled_tile8(M, N);
-    return launch_gemm_prefill_tiled(a, want_acc, tile, static_cast<hipStream_t>(stream), 8) == hipSuccess ? W4A8_OK
-                                                                                                             : W4A8_ERR_LAUNCH;
+    const int tile = variant ? variant : (wfmt == 8 ? choose_tiled_tile8(M, N) : choose_tiled_tile(M, N));
+    return launch_gemm_prefill_tiled(a, want_acc, tile, static_cast<hipStream_t>(stream), wfmt) == hipSuccess
+               ? W4A8_OK
+               : W4A8_ERR_LAUNCH;
 }
 
 int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, int K, void *stream) {

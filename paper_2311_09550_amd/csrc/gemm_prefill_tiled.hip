@@ -57,6 +57,18 @@ __device__ __forceinline__ v4i w_operand_tiled(unsigned w0, unsigned w1) {
     return r;
 }
 
+// The same for the unsigned storage: each nibble holds u = w + 8 and the subtraction happens here, on four bytes at
+// a time: (u + 0x78) ^ 0x80 is u - 8 as a two's-complement byte, and u + 0x78 <= 0x87 never carries into the next byte.
+__device__ __forceinline__ v4i u_operand_tiled(unsigned w0, unsigned w1) {
+    auto minus8 = [](unsigned bytes) { return (int)((bytes + 0x78787878u) ^ 0x80808080u); };
+    v4i r;
+    r.x = minus8(w0 & 0x0F0F0F0Fu);
+    r.y = minus8((w0 >> 4) & 0x0F0F0F0Fu);
+    r.z = minus8(w1 & 0x0F0F0F0Fu);
+    r.w = minus8((w1 >> 4) & 0x0F0F0F0Fu);
+    return r;
+}
+
 // nibbles k0..k7 of a row-major dword -> k0 k4 k1 k5 k2 k6 k3 k7
 __device__ __forceinline__ unsigned interleave_nibbles(unsigned w) {
     unsigned lo = w & 0xFFFFu, hi = w >> 16;
@@ -94,10 +106,15 @@ __global__ __launch_bounds__(256) void tile_weights_kernel(const uint8_t *__rest
 // WBITS = 4: the W4A8 kernel described above.  WBITS = 8: the W8A8 comparison variant (the paper's Table 4 sets its
 // W4A8 against W8A8): int8 weight codes in blocks of 32 channels x 128 k = 4 KB, chunk (c, r), c = 0..7, at
 // (c * 32 + r) * 16 holding k = 128 kb + 16 c .. + 15 of channel 32 nb + r; a fragment is an MFMA operand as it is.
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS = 4>
+// UNS (with WBITS = 4): the "vanilla" unsigned storage the paper measures FastGEMM against (Sec. 5.3, App. A.1,
+// Fig. 4(b), "Asym GEMM" of Sec. 6.4): the nibbles hold u = w + 8 and 8 is subtracted from every byte after
+// unpacking, 7 VALU operations per 8 weights instead of 3; the sums are then true sums, not sixteen-fold ones.
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS = 4, bool UNS = false>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(PrefillArgs p) {
     static_assert(WBITS == 4 || WBITS == 8, "int4 or int8 weight codes");
+    static_assert(!UNS || WBITS == 4, "the unsigned storage is a 4-bit format");
     constexpr bool W8 = WBITS == 8;
+    constexpr bool kTrueSums = W8 || UNS;  // else every sum is sixteen times the true one
     constexpr int kBlock = kTiledBlockK * 32 * WBITS / 8;  // bytes of a weight block: 2 KB or 4 KB
     constexpr int kParts = kBlock / 1024;                  // wave loads per block
     constexpr int kWaves = WM * WN;
@@ -239,8 +256,9 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     auto mfma_step = [&](const v4u(&x)[MTW], const v4u(&w)[NTW], int h) {
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
-            const v4i wop = W8 ? v4i{(int)w[t].x, (int)w[t].y, (int)w[t].z, (int)w[t].w}
-                               : (h == 0 ? w_operand_tiled(w[t].x, w[t].y) : w_operand_tiled(w[t].z, w[t].w));
+            const v4i wop = W8    ? v4i{(int)w[t].x, (int)w[t].y, (int)w[t].z, (int)w[t].w}
+                            : UNS ? (h == 0 ? u_operand_tiled(w[t].x, w[t].y) : u_operand_tiled(w[t].z, w[t].w))
+                                  : (h == 0 ? w_operand_tiled(w[t].x, w[t].y) : w_operand_tiled(w[t].z, w[t].w));
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt)
                 acc[mt][t] = mfma32(wop, v4i{(int)x[mt].x, (int)x[mt].y, (int)x[mt].z, (int)x[mt].w}, acc[mt][t]);
@@ -332,7 +350,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     // last fragment read and every load has landed) and stores whole 16-byte runs of 8 channels, 8 or more lanes per
     // row, i.e. whole cache lines.
     // int4 sums are sixteen times the true sums (the nibbles sat in the high half of their bytes); int8 sums are true
-    auto deq = [](int a, float s_a, float s_w) { return W8 ? (float)a * (s_a * s_w) : dequant(a, s_a, s_w); };
+    auto deq = [](int a, float s_a, float s_w) { return kTrueSums ? (float)a * (s_a * s_w) : dequant(a, s_a, s_w); };
     if (!ACC_OUT && (p.ldc & 7) == 0) {
         constexpr int kRowBytes = 64 * NTW;        // fp16 bytes of a slab row (32 NTW channels)
         constexpr int kPitch = kRowBytes + 16;     // padded: rows 16 apart, not 1 apart, share banks
@@ -406,7 +424,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                 const v4i s = v4i{acc[mt][t][4 * q], acc[mt][t][4 * q + 1], acc[mt][t][4 * q + 2], acc[mt][t][4 * q + 3]};
                 if (ACC_OUT) {
                     int *dst = p.acc_out + (size_t)m * p.ldc + n;
-                    constexpr int kShift = W8 ? 0 : 4;  // int4: exact, every sum is a multiple of 16
+                    constexpr int kShift = kTrueSums ? 0 : 4;  // signed int4: exact, every sum is a multiple of 16
                     const v4i v = v4i{s.x >> kShift, s.y >> kShift, s.z >> kShift, s.w >> kShift};
                     if (vec_ok && n + 3 < p.N) {
                         *(v4i *)dst = v;
@@ -436,12 +454,12 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
 
 namespace {
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS>
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS, bool UNS>
 hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
     constexpr int kLdsBytes = STAGES * (BM * 128 + BN * 16 * WBITS) + 1024;
     static_assert(kLdsBytes <= 160 * 1024, "a workgroup's ring must fit the compute unit's LDS");
-    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS>;
+    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS>;
     // more than 64 KB of LDS per workgroup has to be asked for, once per device
     static bool raised[64] = {};
     int dev = 0;
@@ -455,15 +473,15 @@ hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, int WBITS = 4>
+template <int MTW, int NTW, int WM, int WN, int STAGES, int WBITS = 4, bool UNS = false>
 hipError_t launch_tile(PrefillArgs p, bool acc_out, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     const int total = p.tiles_m * p.tiles_n;
     const dim3 grid(8 * ((total + 7) / 8));
-    return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true, WBITS>(p, grid, stream)
-                   : launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS>(p, grid, stream);
+    return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true, WBITS, UNS>(p, grid, stream)
+                   : launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS>(p, grid, stream);
 }
 
 // One thread per 16-byte chunk of the tiled int8 array (W8A8 variant): a plain gather, no reordering inside a chunk.
@@ -488,7 +506,7 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
     // slices keep every byte offset inside the kernel below 2^32; slices of N start on a 32-channel block
     const long long kMaxBytes = 0xF0000000ll;
     const long long kb_total = (p.K + kTiledBlockK - 1) / kTiledBlockK;
-    const long long block_bytes = (long long)kTiledBlockBytes * wbits / 4;
+    const long long block_bytes = (long long)kTiledBlockBytes * (wbits == 8 ? 2 : 1);
     long long m_rows = kMaxBytes / p.K, n_rows = kMaxBytes / (kb_total * (block_bytes / 32));
     m_rows -= m_rows % 256;
     n_rows -= n_rows % 1280;  // a multiple of every tile width
@@ -527,6 +545,18 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
                     case kTiled64x128: e = launch_tile<1, 2, 2, 2, 3, 8>(q, acc_out, stream); break;
                     case kTiled64x64: e = launch_tile<1, 1, 2, 2, 4, 8>(q, acc_out, stream); break;
                     case kTiled32x128: e = launch_tile<1, 1, 1, 4, 3, 8>(q, acc_out, stream); break;
+                    default: e = hipErrorInvalidConfiguration;
+                }
+            } else if (wbits == kWeightsUnsigned4) {
+                switch (tile) {
+                    case kTiled256x256: e = launch_tile<4, 2, 2, 4, 3, 4, true>(q, acc_out, stream); break;
+                    case kTiled256x256Square: e = launch_tile<2, 4, 4, 2, 3, 4, true>(q, acc_out, stream); break;
+                    case kTiled128x256: e = launch_tile<4, 2, 1, 4, 2, 4, true>(q, acc_out, stream); break;
+                    case kTiled128x160: e = launch_tile<1, 5, 4, 1, 3, 4, true>(q, acc_out, stream); break;
+                    case kTiled128x128: e = launch_tile<2, 2, 2, 2, 3, 4, true>(q, acc_out, stream); break;
+                    case kTiled64x128: e = launch_tile<1, 2, 2, 2, 4, 4, true>(q, acc_out, stream); break;
+                    case kTiled64x64: e = launch_tile<1, 1, 2, 2, 4, 4, true>(q, acc_out, stream); break;
+                    case kTiled32x128: e = launch_tile<1, 1, 1, 4, 4, 4, true>(q, acc_out, stream); break;
                     default: e = hipErrorInvalidConfiguration;
                 }
             } else {

@@ -70,7 +70,9 @@ constexpr int kTiled64x64 = 7;          // 4 waves of 32 x 32
 constexpr int kTiled32x128 = 8;         // 4 waves of 32 x 32 side by side
 constexpr int kTiledTileMax = 8;
 
-// wbits = 4: packed int4 codes (blocks of 2 KB); wbits = 8: int8 codes of the W8A8 comparison variant (blocks of 4 KB)
+// wbits = 4: packed int4 codes (blocks of 2 KB); wbits = 8: int8 codes of the W8A8 comparison variant (blocks of 4 KB);
+// wbits = kWeightsUnsigned4: the 2 KB blocks with unsigned nibbles u = w + 8 (the paper's vanilla storage, GEMM only)
+constexpr int kWeightsUnsigned4 = 104;
 size_t tiled_weight_bytes(int N, int K, int wbits = 4);
 hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream);
 hipError_t launch_tile_weights8(const int8_t *w8, uint8_t *wt, int N, int K, hipStream_t stream);

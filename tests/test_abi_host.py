@@ -99,6 +99,8 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_tile_weights(p, odd, 32, 128, null) == -3
     assert L.w4a8_gemm_tiled(p, p, p, p, null, 1, 16, 32, null) == -1
     assert L.w4a8_gemm_tiled(p, p, p, p, p, 1, 16, 48, null) == -2
+    assert L.w4a8_gemm_tiled_unsigned(p, p, null, p, p, null, 1, 16, 32, 0, null) == -1
+    assert L.w4a8_gemm_tiled_unsigned(p, p, p, p, p, null, 1, 16, 32, 9, null) == -7
     assert L.w8a8_tile_weights(null, p, 32, 128, null) == -1
     assert L.w8a8_tile_weights(p, p, 32, 100, null) == -2
     assert L.w8a8_gemm_tiled(p, p, p, p, p, p, 1, 16, 32, 0, null) == -1        # both outputs

@@ -102,6 +102,27 @@ def test_gemm_tiled_entry_equals_row_major_entry(gpu, oracle):
         assert_fp16_close(b.cpu().numpy(), y32, acc_o, f"tiled entry M={M}")
 
 
+@pytest.mark.parametrize("tile", TILES)
+@pytest.mark.parametrize("M,N,K", [(1, 520, 1056), (65, 520, 1056), (300, 520, 1056), (200, 1001, 160), (384, 300, 5120)])
+def test_unsigned_storage_variant(gpu, oracle, M, N, K, tile):
+    """The storage ablation (unsigned nibbles u = w + 8, 8 subtracted in registers) against the oracle's definition of
+    it, and bit-identical to the signed format on the same codes."""
+    t = gpu
+    xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=56)
+    up = oracle.pack_u4(wq.astype(np.int16) + 8)
+    acc_o, y32, _ = oracle.gemm_u4(xq, s_a, up, s_w)
+    dxq, dsa, dsw = t.from_numpy(xq).cuda(), t.from_numpy(s_a).cuda(), t.from_numpy(s_w).cuda()
+    ut = w4a8.w4a8_tile_weights(t.from_numpy(up).cuda())
+    acc = w4a8.w4a8_gemm_tiled_unsigned(dxq, None, ut, None, N=N, variant=tile, want_acc=True)
+    out = w4a8.w4a8_gemm_tiled_unsigned(dxq, dsa, ut, dsw, variant=tile)
+    wt = w4a8.w4a8_tile_weights(t.from_numpy(oracle.pack_w4(wq)).cuda())
+    ref = w4a8.w4a8_gemm_tuned(dxq, dsa, wt, dsw, TILED, tile, N=N)
+    t.cuda.synchronize()
+    assert_equal_bits(acc.cpu().numpy(), acc_o, f"unsigned tile={tile} acc")
+    assert_fp16_close(out.cpu().numpy(), y32, acc_o, f"unsigned tile={tile} out")
+    assert_equal_bits(out.cpu().numpy().view(np.uint16), ref.cpu().numpy().view(np.uint16), "unsigned vs signed storage")
+
+
 def test_tiled_llama13b_prefill_sampled(gpu, oracle):
     """Full-size LLaMA-13B gate/up shape at M = 1024 in the default tile: rows of the output sampled and checked
     against the oracle one by one (raw sums bit-exact)."""
