@@ -225,8 +225,9 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
 
 
 def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
-    """The paper sets its W4A8 against its own W8A8 (Table 4).  Here, per GEMM: the same large-M kernel over tiled int4
-    and tiled int8 weights of the same fp16 matrix, every launch on a different weight copy (copies exceed the last-level
+    """The paper sets its W4A8 against its own W8A8 (Table 4) and its signed storage against the vanilla unsigned one
+    ("Asym GEMM", Sec. 6.4).  Here, per GEMM: the same large-M kernel over tiled int4 (signed), tiled unsigned int4 and
+    tiled int8 weights of the same fp16 matrix, every launch on a different weight copy (copies exceed the last-level
     cache three times, so weights come from HBM), batches replayed from a HIP graph."""
     rows = []
     for name, (N, K) in synth.LLAMA_SHAPES[model].items():
@@ -234,18 +235,21 @@ def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
         wp, s_w4 = w4a8.w4a8_quantize_weights(w)
         w8, s_w8 = w4a8.w4a8_quantize_act(w)          # per-channel int8: the per-token quantiser on weight rows
         del w
-        wt = {4: w4a8.w4a8_tile_weights(wp), 8: w4a8.w8a8_tile_weights(w8)}
+        # "u4": the vanilla unsigned storage, u = w + 8, i.e. bit 3 of every two's-complement nibble flipped
+        wt = {4: w4a8.w4a8_tile_weights(wp), 8: w4a8.w8a8_tile_weights(w8), "u4": w4a8.w4a8_tile_weights(wp ^ 0x88)}
         del wp, w8
-        copies = {b: max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wt[b].numel()) + 1) for b in (4, 8)}
-        wts = {b: [wt[b]] + [wt[b].clone() for _ in range(copies[b] - 1)] for b in (4, 8)}
+        fmts = (4, "u4", 8)
+        copies = {b: max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wt[b].numel()) + 1) for b in fmts}
+        wts = {b: [wt[b]] + [wt[b].clone() for _ in range(copies[b] - 1)] for b in fmts}
         for M in Ms:
             x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
             xq, s_a = w4a8.w4a8_quantize_act(x)
             out = torch.empty((M, N), dtype=torch.float16, device="cuda")
             us = {}
-            for b in (4, 8):
-                call = (lambda t: w4a8.w4a8_gemm_tiled(xq, s_a, t, s_w4, out=out)) if b == 4 else \
-                       (lambda t: w4a8.w8a8_gemm_tiled(xq, s_a, t, s_w8, out=out))
+            for b in fmts:
+                call = {4: lambda t: w4a8.w4a8_gemm_tiled(xq, s_a, t, s_w4, out=out),
+                        "u4": lambda t: w4a8.w4a8_gemm_tiled_unsigned(xq, s_a, t, s_w4, out=out),
+                        8: lambda t: w4a8.w8a8_gemm_tiled(xq, s_a, t, s_w8, out=out)}[b]
                 call(wts[b][0])
                 torch.cuda.synchronize()
                 n = max(copies[b], 8)
@@ -263,7 +267,8 @@ def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
                 torch.cuda.synchronize()
                 us[b] = e0.elapsed_time(e1) * 1e3 / (n * iters)
                 del graph
-            rows.append({"linear": name, "M": M, "w4a8_us": round(us[4], 2), "w8a8_us": round(us[8], 2),
+            rows.append({"linear": name, "M": M, "w4a8_us": round(us[4], 2), "w4a8_unsigned_us": round(us["u4"], 2),
+                         "w8a8_us": round(us[8], 2), "unsigned_over_w4": round(us["u4"] / us[4], 3),
                          "w8_over_w4": round(us[8] / us[4], 3)})
         del wts, wt
         torch.cuda.empty_cache()
