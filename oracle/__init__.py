@@ -245,3 +245,44 @@ def silu_mul(gate_up_half):
     h = np.empty((M, I), np.uint16)
     _load().oracle_silu_mul(_p(g), _p(y64), _p(h), M, I)
     return y64, h.view(np.float16)
+
+
+def quantize_weights_groups(w_half, group=128):
+    """fp16 [N][K] -> (int8 codes [N][K] in [-7, 7], float32 group scales [K/group][N]): round-to-nearest with one
+    scale per run of `group` consecutive k of a channel."""
+    w = np.ascontiguousarray(w_half)
+    if w.dtype == np.float16:
+        w = w.view(np.uint16)
+    w = _c(w, np.uint16)
+    N, K = w.shape
+    if group <= 0 or K % group:
+        raise ValueError("K must be a multiple of the group size")
+    wq = np.empty((N, K), np.int8)
+    s_g = np.empty((K // group, N), np.float32)
+    if _load().oracle_quantize_weights_groups(_p(w), group, _p(wq), _p(s_g), N, K) != 0:
+        raise ValueError("bad group size")
+    return wq, s_g
+
+
+def gemm_fine_grained(xq, s_a, wp, s_g, group=128):
+    """The fine-grained (group-wise) W4A8 linear: s_g is float32 [K/group][N].
+    -> (y64 float64: the definition, y32 float32: the same in fp32 in ascending group order, out float16 = y32 rounded,
+        mag float64: the sum of the absolute group terms, what a rounding bound is relative to)."""
+    xq = _c(xq, np.int8)
+    wp = _c(wp, np.uint8)
+    s_a = _c(s_a, np.float32)
+    s_g = _c(s_g, np.float32)
+    M, K = xq.shape
+    N, K2 = wp.shape
+    if 2 * K2 != K or group <= 0 or K % group or s_g.shape != (K // group, N) or s_a.shape != (M,):
+        raise ValueError("shape mismatch")
+    y64 = np.empty((M, N), np.float64)
+    y32 = np.empty((M, N), np.float32)
+    out = np.empty((M, N), np.uint16)
+    mag = np.empty((M, N), np.float64)
+    lib = _load()
+    lib.oracle_gemm_fine_grained.restype = ctypes.c_int
+    if lib.oracle_gemm_fine_grained(_p(xq), _p(s_a), _p(wp), _p(s_g), group, _p(y64), _p(y32), _p(out), _p(mag),
+                                    M, N, K) != 0:
+        raise ValueError("bad group size")
+    return y64, y32, out.view(np.float16), mag

@@ -355,6 +355,88 @@ int oracle_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const flo
     return 0;
 }
 
+/* ------------------------------------------------- fine-grained comparison */
+
+/* Group-wise symmetric 4-bit round-to-nearest (the "g128" recipes of Table 1, Sec. 3): every run of `group`
+ * consecutive k of an output channel has its own scale S = max|W| / 7 over that run (Eq. (8),(9) with gamma = beta
+ * = 1 applied per group).  s_g is stored group-major: s_g[g * N + n].  K must be a multiple of group. */
+int oracle_quantize_weights_groups(const uint16_t *w_half, int group, int8_t *wq, float *s_g, int N, int K)
+{
+    if (group <= 0 || K % group) return -1;
+    for (int n = 0; n < N; ++n) {
+        for (int g = 0; g < K / group; ++g) {
+            const uint16_t *src = w_half + (size_t)n * K + (size_t)g * group;
+            int8_t *dst = wq + (size_t)n * K + (size_t)g * group;
+            float top = 0.0f;
+            for (int k = 0; k < group; ++k) {
+                float v = fabsf((float)half_bits_to_double(src[k]));
+                if (v > top) top = v;
+            }
+            float scale = top / 7.0f;
+            s_g[(size_t)g * N + n] = top == 0.0f ? 0.0f : scale;
+            for (int k = 0; k < group; ++k) {
+                float r = 0.0f;
+                if (top != 0.0f) {
+                    r = nearbyintf((float)half_bits_to_double(src[k]) / scale);
+                    if (r > 7.0f) r = 7.0f;
+                    if (r < -8.0f) r = -8.0f;
+                }
+                dst[k] = (int8_t)r;
+            }
+        }
+    }
+    return 0;
+}
+
+/* The fine-grained W4A8 product the paper sets its per-channel kernel against (Eq. (2), Fig. 2(b), Sec. 6.4):
+ *     O[m][n] = sum_g Dq( sum_{k in group g} xq[m][k] * W_q[n][k],  s_a[m],  s_g[g][n] ),
+ * an exact integer sum per group, made floating point and scaled group by group.
+ *   y64  : the definition in fp64, s_a[m] * sum_g (acc_g * s_g[g][n]);
+ *   y32  : the same in the fp32 arithmetic the paper names for O, in this order: f = 0; for g ascending
+ *          f = fma(float(acc_g), s_g[g][n], f); y = f * s_a[m]   (the per-token factor is common to all groups
+ *          and is applied once, after the sum);
+ *   out_half : y32 rounded once to fp16;
+ *   mag  : s_a[m] * sum_g |acc_g| * s_g[g][n] in fp64, the size a rounding-error bound is relative to.
+ * Any output pointer may be NULL.  K must be a multiple of group. */
+int oracle_gemm_fine_grained(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_g, int group,
+                             double *y64, float *y32, uint16_t *out_half, double *mag, int M, int N, int K)
+{
+    if (group <= 0 || K % group) return -1;
+    const int G = K / group;
+#pragma omp parallel
+    {
+        int8_t *wrow = (int8_t *)malloc((size_t)K);
+#pragma omp for schedule(static)
+        for (int n = 0; n < N; ++n) {
+            for (int k = 0; k < K; ++k) {
+                unsigned b = wp[(size_t)n * (K / 2) + (k >> 1)];
+                wrow[k] = (int8_t)nibble_value((k & 1) ? (b >> 4) : (b & 15u));
+            }
+            for (int m = 0; m < M; ++m) {
+                double d = 0.0, a = 0.0;
+                float f = 0.0f;
+                for (int g = 0; g < G; ++g) {
+                    int32_t s = 0;
+                    for (int k = g * group; k < (g + 1) * group; ++k)
+                        s += (int32_t)xq[(size_t)m * K + k] * (int32_t)wrow[k];
+                    float sc = s_g[(size_t)g * N + n];
+                    d += (double)s * (double)sc;
+                    a += fabs((double)s) * fabs((double)sc);
+                    f = fmaf((float)s, sc, f);
+                }
+                float y = f * s_a[m];
+                size_t o = (size_t)m * N + n;
+                if (y64) y64[o] = (double)s_a[m] * d;
+                if (y32) y32[o] = y;
+                if (out_half) out_half[o] = double_to_half_bits((double)y);
+                if (mag) mag[o] = fabs((double)s_a[m]) * a;
+            }
+        }
+        free(wrow);
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------- layer glue */
 
 /* h[m][i] = silu(gate[m][i]) * up[m][i], gate = columns [0,I), up = columns

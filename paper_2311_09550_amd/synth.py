@@ -66,3 +66,11 @@ def weights_fp16(N: int, K: int, config_id: int = 2, sigma: float = 0.02) -> np.
     w = g.standard_normal(size=(N, K), dtype=np.float32)
     w *= np.float32(sigma)
     return w.astype(np.float16)
+
+
+def group_scales(N: int, K: int, group: int = 128, config_id: int = 1) -> np.ndarray:
+    """fp32 [K/group][N]: one positive scale per group of `group` consecutive k of every output channel, drawn
+    log-uniformly over [1e-3, 1e-2] (a decade of spread inside a channel, as group-wise weight quantisation gives
+    when a channel's magnitude varies along k)."""
+    g = rng(config_id, N, K, group, 7)
+    return np.exp(g.uniform(math.log(1e-3), math.log(1e-2), size=(K // group, N))).astype(np.float32)

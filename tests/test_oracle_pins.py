@@ -530,3 +530,105 @@ def test_w4a8_linear_tracks_the_fp_matmul(oracle):
     assert rel < 0.25
     assert np.corrcoef(y32.ravel(), ref.ravel())[0, 1] > 0.97
     assert np.allclose(out.astype(np.float32), y32, rtol=2.0 ** -10, atol=2.0 ** -24)
+
+
+# ------------------------------------------------ fine-grained comparison
+
+def test_fine_grained_hand_worked_example(oracle):
+    """Two groups of 128, two channels with different scales (a transposed scale array would swap them):
+    channel 0: 128 * 1 * 0.5 + 128 * (-2) * 0.125 = 64 - 32 = 32, times s_a = 2 -> 64;
+    channel 1: 128 * 3 * 0.25 + 128 * (-1) * 1.0 = 96 - 128 = -32, times 2 -> -64."""
+    xq = np.ones((1, 256), np.int8)
+    wq = np.empty((2, 256), np.int8)
+    wq[0, :128], wq[0, 128:] = 1, -2
+    wq[1, :128], wq[1, 128:] = 3, -1
+    s_g = np.array([[0.5, 0.25], [0.125, 1.0]], np.float32)   # [group][channel]
+    y64, y32, out, mag = oracle.gemm_fine_grained(xq, np.array([2.0], np.float32), oracle.pack_w4(wq), s_g)
+    assert y64.tolist() == [[64.0, -64.0]] and y32.tolist() == [[64.0, -64.0]]
+    assert out.astype(np.float64).tolist() == [[64.0, -64.0]]
+    assert mag.tolist() == [[192.0, 448.0]]
+
+
+def test_fine_grained_equals_dequantise_first_matmul(oracle):
+    """Scaling each group's integer sum equals multiplying by weights dequantised group-wise beforehand
+    (the W4A16-shaped Eq. (1)): checked against a float64 library matmul."""
+    M, N, K = 9, 37, 640
+    xq, wq, s_a, _ = synth.uniform_codes(M, N, K, config_id=60)
+    s_g = synth.group_scales(N, K, 128, config_id=60)
+    y64, y32, out, mag = oracle.gemm_fine_grained(xq, s_a, oracle.pack_w4(wq), s_g)
+    w_deq = wq.astype(np.float64) * np.repeat(s_g.astype(np.float64).T, 128, axis=1)   # [N][K]
+    ref = s_a.astype(np.float64)[:, None] * (xq.astype(np.float64) @ w_deq.T)
+    assert np.all(np.abs(y64 - ref) <= 1e-13 * mag + 1e-300)
+    # fp32 chain: one rounding per group term plus the final product
+    assert np.all(np.abs(y32.astype(np.float64) - y64) <= (K // 128 + 2) * 2.0 ** -24 * mag)
+    assert np.all(np.abs(out.astype(np.float64) - y32.astype(np.float64)) <= 2.0 ** -11 * np.abs(y32) + 2.0 ** -25)
+    assert np.all(mag >= np.abs(y64))
+    # other group sizes follow the same definition
+    for group in (32, 64, 320, 640):
+        sg = synth.group_scales(N, K, group, config_id=61)
+        y = oracle.gemm_fine_grained(xq, s_a, oracle.pack_w4(wq), sg, group)[0]
+        wd = wq.astype(np.float64) * np.repeat(sg.astype(np.float64).T, group, axis=1)
+        ref = s_a.astype(np.float64)[:, None] * (xq.astype(np.float64) @ wd.T)
+        assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_fine_grained_reduces_to_per_channel(oracle):
+    """With the same scale in every group of a channel, and with one group spanning all of K, Eq. (2) is Eq. (3)."""
+    M, N, K = 7, 21, 512
+    xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=62)
+    wp = oracle.pack_w4(wq)
+    acc = oracle.gemm_acc_i32(xq, wp)
+    exact = acc.astype(np.float64) * s_a.astype(np.float64)[:, None] * s_w.astype(np.float64)[None, :]
+    y64 = oracle.gemm_fine_grained(xq, s_a, wp, np.tile(s_w, (4, 1)))[0]
+    assert np.allclose(y64, exact, rtol=1e-14, atol=0)
+    y64, y32, _, _ = oracle.gemm_fine_grained(xq, s_a, wp, s_w.reshape(1, N), group=K)
+    assert np.allclose(y64, exact, rtol=1e-15, atol=0)
+    # a single group: fma(float(acc), s, 0) * s_a, two fp32 roundings, in exact rational arithmetic
+    for m in range(M):
+        for n in range(0, N, 5):
+            want = fp32_round(fp32_round(Fraction(int(acc[m, n])) * Fraction(float(s_w[n]))) * Fraction(float(s_a[m])))
+            assert Fraction(float(y32[m, n])) == want
+
+
+def test_fine_grained_fp32_chain_in_exact_rational_arithmetic(oracle):
+    """The fp32 result is a chain of fused multiply-adds in ascending group order (one rounding each), then one
+    product with s_a: replayed with exact rationals and explicit roundings on small inputs."""
+    M, N, K, group = 3, 4, 384, 64
+    xq, wq, s_a, _ = synth.uniform_codes(M, N, K, config_id=63)
+    s_g = synth.group_scales(N, K, group, config_id=63)
+    _, y32, out, _ = oracle.gemm_fine_grained(xq, s_a, oracle.pack_w4(wq), s_g, group)
+    differs_from_unfused = 0
+    for m in range(M):
+        for n in range(N):
+            f = Fraction(0)
+            unfused = Fraction(0)
+            for g in range(K // group):
+                s = int(np.dot(xq[m, g * group:(g + 1) * group].astype(np.int64), wq[n, g * group:(g + 1) * group].astype(np.int64)))
+                f = fp32_round(Fraction(s) * Fraction(float(s_g[g, n])) + f)
+                unfused = fp32_round(fp32_round(Fraction(s) * Fraction(float(s_g[g, n]))) + unfused)
+            want = fp32_round(f * Fraction(float(s_a[m])))
+            assert Fraction(float(y32[m, n])) == want
+            assert float(out[m, n]) == float(np.float32(float(want)).astype(np.float16))
+            differs_from_unfused += fp32_round(unfused * Fraction(float(s_a[m]))) != want
+    assert differs_from_unfused > 0   # the check above tells a fused chain from a multiply-then-add one
+
+
+def test_group_weight_quantiser(oracle):
+    """Group-wise round-to-nearest: with one group per channel it is the per-channel quantiser; every non-zero group
+    reaches code magnitude 7; the reconstruction error is at most half a step of the group's own scale."""
+    N, K = 12, 512
+    w = synth.weights_fp16(N, K, config_id=64)
+    w[3, 128:256] = 0
+    wq1, s1 = oracle.quantize_weights_groups(w, group=K)
+    wq0, s0 = oracle.quantize_weights_rtn(w)
+    assert np.array_equal(wq1, wq0) and np.array_equal(s1.reshape(-1), s0)
+    wq, s_g = oracle.quantize_weights_groups(w, group=128)
+    assert s_g.shape == (4, N) and s_g[1, 3] == 0 and not wq[3, 128:256].any()
+    blocks = np.abs(wq.astype(np.int32)).reshape(N, 4, 128).max(axis=2)
+    assert np.all((blocks == 7) | (s_g.T == 0))
+    top = np.abs(w.astype(np.float64)).reshape(N, 4, 128).max(axis=2)
+    assert np.allclose(s_g.T, (top / 7).astype(np.float32), rtol=2.0 ** -23)
+    rec = wq.astype(np.float64) * np.repeat(s_g.astype(np.float64).T, 128, axis=1)
+    assert np.all(np.abs(rec - w.astype(np.float64)) <= 0.5000001 * np.repeat(s_g.astype(np.float64).T, 128, axis=1))
+    # finer groups never reconstruct worse in the maximum norm of a group than the channel-wide scale allows
+    assert np.all(s_g.T <= s0[:, None] * (1 + 2.0 ** -22))
