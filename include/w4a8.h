@@ -202,6 +202,28 @@ int w4a8_gemm_tiled_unsigned(const int8_t *xq, const float *s_a, const uint8_t *
                              void *out_fp16, int32_t *acc_i32, int M, int N, int K, int variant, void *stream);
 
 /*
+ * Ablation of the scale granularity (the paper's "fine-grained" GEMM: Eq. (2), Fig. 2(b), Sec. 4.1 and 6.4): the
+ * weights carry one scale per group of 128 consecutive k and output channel instead of one per channel, so each
+ * group's integer sum has to be made floating point and scaled before it can be added to the others:
+ *   f[m][n]  = sum over groups g = 0 .. K/128 - 1, in ascending order, in fp32 with one fused multiply-add per group, of
+ *              float( sum_{k in group g} Xq[m][k] * Wq[n][k] ) * s_g[g][n],
+ *   O[m][n]  = fp16( f[m][n] * s_a[m] ).
+ * The per-token factor is common to all groups and is applied once, after the sum.  A group's integer sum is below
+ * 2^24 in magnitude, so its conversion to fp32 is exact.
+ *   wt   : signed int4 codes in the TILED layout (w4a8_tile_weights), device.
+ *   s_g  : group scales, fp32 [K / 128][ldg] (group-major: the scales of one group for all channels are consecutive),
+ *          device, 16-byte aligned; ldg >= N, ldg % 4 == 0; columns N .. ldg - 1 are read but never used.
+ *   K % 128 == 0; M * K, the tiled weight bytes and (K / 128) * ldg * 4 each below 0xF0000000 (one launch covers the
+ *   problem), otherwise W4A8_ERR_SHAPE.
+ *   variant: output tile, 0 = library's choice, 1 = 128 x 256 (rows of X x channels), 2 = 256 x 128, 3 = 128 x 128,
+ *            4 = 64 x 128, 5 = 64 x 64, 6 = 32 x 128; the 256 x 256 tile of the per-channel kernel does not exist here
+ *            because the second, floating-point set of accumulators does not fit the register file beside the first.
+ * For measurements and tests: this is the cost the per-channel recipe avoids.
+ */
+int w4a8_gemm_fine_grained(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_g, int ldg,
+                           void *out_fp16, int M, int N, int K, int variant, void *stream);
+
+/*
  * Glue between the gate/up GEMM and the down GEMM of a LLaMA MLP:
  *   h[m][i] = fp16( silu(gate_up[m][i]) * gate_up[m][I + i] ),  fp32 arithmetic.
  *   gate_up_fp16 [M][2I] in, h_fp16 [M][I] out.  I % 8 == 0.

@@ -60,6 +60,8 @@ def lib():
         L.w8a8_tile_weights.restype = i
         L.w8a8_gemm_tiled.restype = i
         L.w4a8_gemm_tiled_unsigned.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+        L.w4a8_gemm_fine_grained.restype = i
+        L.w4a8_gemm_fine_grained.argtypes = [vp, vp, vp, vp, i, vp, i, i, i, i, vp]
         L.w4a8_gemm_tiled_unsigned.restype = i
         for name in ("w4a8_quantize_act", "w4a8_gemm", "w4a8_gemm_acc_i32", "w4a8_gemm_tuned",
                      "w4a8_quantize_weights", "w4a8_quantize_weights_clipped", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host",
@@ -285,6 +287,26 @@ def w4a8_gemm_tiled_unsigned(xq, s_a, ut, s_w, N=None, variant: int = 0, want_ac
         raise ValueError("out shape mismatch")
     _check(lib().w4a8_gemm_tiled_unsigned(_dev(xq, torch.int8, "xq"), sa, _dev(ut, torch.uint8, "ut"), sw, o16, o32, M, N, K,
                                           variant, _stream()))
+    return out
+
+
+def w4a8_gemm_fine_grained(xq, s_a, wt, s_g, N=None, variant: int = 0, out=None):
+    """The granularity ablation: tiled signed int4 weights with group scales s_g fp32 [K/128][ldg] (ldg >= N, a
+    multiple of 4; columns past N are ignored) -> fp16 [M][N]."""
+    torch = _torch()
+    M, K = xq.shape
+    G, ldg = s_g.shape
+    N = ldg if N is None else N
+    if G * 128 != K:
+        raise ValueError("s_g must have K / 128 rows")
+    if wt.numel() != w4a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (N, K)")
+    out = torch.empty((M, N), dtype=torch.float16, device=xq.device) if out is None else out
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    _check(lib().w4a8_gemm_fine_grained(_dev(xq, torch.int8, "xq"), _dev(s_a, torch.float32, "s_a"), _dev(wt, torch.uint8, "wt"),
+                                        _dev(s_g, torch.float32, "s_g"), ldg, _dev(out, torch.float16, "out"), M, N, K,
+                                        variant, _stream()))
     return out
 
 

@@ -112,6 +112,30 @@ int choose_tiled_tile(int M, int N) {
     return best;
 }
 
+// The choice among the fine-grained variant's tiles (initial efficiencies: equal work per byte staged for both
+// 128-row tiles; the 8-wave one occupies a compute unit alone).
+int choose_fine_tile(int M, int N) {
+    const int cus = compute_units();
+    auto count = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    if (count(128, 128) * 4 < (long long)cus * 3) {
+        if (M <= 32) return kFine32x128;
+        return count(64, 128) * 4 >= (long long)cus * 3 ? kFine64x128 : kFine64x64;
+    }
+    struct Option { int id, bm, bn, per_cu; double eff; };
+    const Option options[] = {{kFine128x256, 128, 256, 1, 1.00}, {kFine128x128, 128, 128, 2, 0.90}};
+    int best = kFine128x256;
+    double best_cost = 0;
+    for (const Option &o : options) {
+        const long long tiles = count(o.bm, o.bn);
+        const long long slots = (long long)cus * o.per_cu;
+        const long long full = tiles / slots, rest = tiles % slots;
+        const double last = rest == 0 ? 0.0 : (o.per_cu == 1 || rest * 2 > slots ? 1.0 : 0.5);
+        const double cost = ((double)full + last) * o.bm * o.bn * o.per_cu / o.eff;
+        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = o.id; }
+    }
+    return best;
+}
+
 // The same choice for the int8-weight variant, whose weight stages take twice the LDS (shallower rings, and the
 // 128 x 256 tile fits a compute unit only once).
 int choose_tiled_tile8(int M, int N) {
@@ -309,6 +333,30 @@ int w8a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const
 int w4a8_gemm_tiled_unsigned(const int8_t *xq, const float *s_a, const uint8_t *ut, const float *s_w, void *out_fp16,
                              int32_t *acc_i32, int M, int N, int K, int variant, void *stream) {
     return gemm_tiled_variant(xq, s_a, ut, s_w, out_fp16, acc_i32, M, N, K, variant, stream, kWeightsUnsigned4);
+}
+
+// ---- ablation: fine-grained (group-wise) weight scales, Eq. (2)
+
+int w4a8_gemm_fine_grained(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_g, int ldg, void *out_fp16,
+                           int M, int N, int K, int variant, void *stream) {
+    if (!xq || !s_a || !wt || !s_g || !out_fp16) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(M, N, K)) return e;
+    if (K % kTiledBlockK != 0 || ldg < N || (ldg & 3) != 0) return W4A8_ERR_SHAPE;
+    // one launch covers the problem: every byte offset inside the kernel stays below 2^32
+    const long long kMaxBytes = 0xF0000000ll;
+    if ((long long)M * K > kMaxBytes || (long long)tiled_weight_bytes(N, K, 4) > kMaxBytes ||
+        (long long)(K / kTiledBlockK) * ldg * 4 > kMaxBytes)
+        return W4A8_ERR_SHAPE;
+    if (variant < 0 || variant > kFineTileMax) return W4A8_ERR_ARG;
+    if (misaligned(xq) || misaligned(wt) || misaligned(out_fp16) || misaligned(s_g)) return W4A8_ERR_ALIGN;
+    PrefillArgs a{};
+    a.xq = xq; a.s_a = s_a; a.wp = wt; a.s_w = s_g;
+    a.out = out_fp16;
+    a.M = M; a.N = N; a.K = K; a.ldc = N; a.ldg = ldg;
+    const int tile = variant ? variant : choose_fine_tile(M, N);
+    return launch_gemm_prefill_tiled(a, false, tile, static_cast<hipStream_t>(stream), kWeightsFineGrained4) == hipSuccess
+               ? W4A8_OK
+               : W4A8_ERR_LAUNCH;
 }
 
 static int gemm_tiled_variant(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,

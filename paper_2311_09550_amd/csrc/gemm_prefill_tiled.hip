@@ -109,10 +109,17 @@ __global__ __launch_bounds__(256) void tile_weights_kernel(const uint8_t *__rest
 // UNS (with WBITS = 4): the "vanilla" unsigned storage the paper measures FastGEMM against (Sec. 5.3, App. A.1,
 // Fig. 4(b), "Asym GEMM" of Sec. 6.4): the nibbles hold u = w + 8 and 8 is subtracted from every byte after
 // unpacking, 7 VALU operations per 8 weights instead of 3; the sums are then true sums, not sixteen-fold ones.
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS = 4, bool UNS = false>
+// FG (with WBITS = 4, signed): the fine-grained recipe the paper argues against (Eq. (2), Fig. 2(b), Sec. 6.4): one
+// weight scale per group of 128 k and channel, p.s_w = s_g[K / 128][p.ldg].  A stage of the ring is exactly one
+// group, so every stage starts its integer sums from zero and ends by folding them, converted to fp32 and multiplied
+// by the group's scales, into a second, floating-point set of accumulators: per MFMA 8 extra VALU operations, twice
+// the accumulator registers (which rules out the 256 x 256 tile), and one more 16-byte load per wave and stage (each
+// wave brings in the 32 NTW scales it needs itself, next to its share of the operands).
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS = 4, bool UNS = false, bool FG = false>
 __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(PrefillArgs p) {
     static_assert(WBITS == 4 || WBITS == 8, "int4 or int8 weight codes");
     static_assert(!UNS || WBITS == 4, "the unsigned storage is a 4-bit format");
+    static_assert(!FG || (WBITS == 4 && !UNS && !ACC_OUT), "group scales: signed int4 codes, fp16 output");
     constexpr bool W8 = WBITS == 8;
     constexpr bool kTrueSums = W8 || UNS;  // else every sum is sixteen times the true one
     constexpr int kBlock = kTiledBlockK * 32 * WBITS / 8;  // bytes of a weight block: 2 KB or 4 KB
@@ -126,11 +133,13 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     constexpr int A_LOADS = A_TOTAL / kWaves;
     constexpr int B_LOADS = (B_TOTAL + kWaves - 1) / kWaves;
     constexpr bool kRagged = B_LOADS * kWaves != B_TOTAL;
-    constexpr int kLoads = A_LOADS + B_LOADS;  // per wave and stage, the same for every wave: the waits count on it
+    constexpr int kLoads = A_LOADS + B_LOADS + (FG ? 1 : 0);  // per wave and stage, the same for every wave: the waits count on it
     constexpr int A_STAGE = BM * 128;
     constexpr int B_STAGE = (BN / 32) * kBlock;
     constexpr int kBBase = STAGES * A_STAGE;
     constexpr int kSpare = STAGES * (A_STAGE + B_STAGE);  // 1 KB that absorbs the surplus loads of an uneven split
+    constexpr int kScaleBase = kSpare + 1024;             // FG: per ring slot and wave, 32 NTW group scales
+    constexpr int kScaleWave = NTW * 128;
     static_assert(STAGES >= 2 && (STAGES - 1) * kLoads < 64, "outstanding loads must fit the counter");
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
@@ -189,6 +198,11 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                        ? ((unsigned)nb * (unsigned)st_total * kParts + (L % kParts)) * 1024u + lane * 16
                        : kNowhere;
     }
+    // FG: lane L < 8 NTW of every wave fetches the scales of channels n_wave + 4 L .. + 3 of the stage's group
+    // (p.ldg is a multiple of 4, so a 16-byte run lies wholly inside a row of s_g or wholly outside)
+    const v4i g_rsrc = FG ? make_rsrc(p.s_w, (size_t)st_total * (size_t)p.ldg * 4) : v4i{0, 0, 0, 0};
+    const int g_n = bn0 + wn * (32 * NTW) + 4 * lane;
+    const unsigned g_off = (FG && g_n < p.ldg) ? (unsigned)g_n * 4u : kNowhere;
 
     // The load is written in assembly on purpose: the compiler orders LDS reads after every LDS-writing load it knows
     // of (it cannot tell the ring slots apart) and would wait for the stage just requested before each fragment read.
@@ -209,11 +223,13 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
             if (j < A_LOADS) {
                 dma16(a_rsrc, lds_base + slot * A_STAGE + (j * kWaves + wave) * 1024,
                       (last && !a_last_ok) ? kNowhere : a_off[j], st * kStageK);
-            } else {
+            } else if (j < A_LOADS + B_LOADS) {
                 const int i = j - A_LOADS;
                 const int L = i * kWaves + wave;
                 const unsigned dst = (kRagged && L >= B_TOTAL) ? kSpare : kBBase + slot * B_STAGE + L * 1024;
                 dma16(b_rsrc, lds_base + dst, b_off[i], st * kBlock);
+            } else if (lane < 8 * NTW) {  // FG: the other lanes are masked off and write nothing
+                dma16(g_rsrc, lds_base + kScaleBase + (slot * kWaves + wave) * kScaleWave, g_off, st * p.ldg * 4);
             }
         }
     };
@@ -225,6 +241,16 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         for (int t = 0; t < NTW; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mt][t][v] = 0;
+    // FG: sum over the groups of float(integer sum of the group) * group scale, sixteen-fold like the integer sums
+    float facc[FG ? MTW : 1][FG ? NTW : 1][16];
+    if (FG) {
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+            for (int t = 0; t < NTW; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) facc[FG ? mt : 0][FG ? t : 0][v] = 0.f;
+    }
 
     // LDS offsets of this lane's fragments inside a stage.  MFMA step j = 0..3 of a stage covers k = 32 j .. 32 j + 31;
     // lane (idx, g) supplies k = 32 j + 16 g .. + 15: activation chunk 2 j + g of its row, and dwords 2 (j % 2), +1
@@ -253,7 +279,23 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
 #pragma unroll
         for (int t = 0; t < NTW; ++t) dst[t] = *(const v4u *)(&lds[slot * B_STAGE + wa + t * kBlock + q * 1024]);
     };
-    auto mfma_step = [&](const v4u(&x)[MTW], const v4u(&w)[NTW], int h) {
+    // the scales of this wave's channels for the group in ring slot `slot`, in accumulator order:
+    // register 4 q + e of block t belongs to channel 32 t + 8 q + 4 g + e
+    auto read_sg = [&](float(&dst)[NTW][16], int slot) {
+#pragma unroll
+        for (int t = 0; t < NTW; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = *(const float4 *)(&lds[kScaleBase + (slot * kWaves + wave) * kScaleWave +
+                                                        (32 * t + 8 * q + 4 * g) * 4]);
+                dst[t][4 * q] = v.x;
+                dst[t][4 * q + 1] = v.y;
+                dst[t][4 * q + 2] = v.z;
+                dst[t][4 * q + 3] = v.w;
+            }
+    };
+    // fresh = true (FG, first step of a stage): the group's integer sums start from zero
+    auto mfma_step = [&](const v4u(&x)[MTW], const v4u(&w)[NTW], int h, bool fresh = false) {
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
             const v4i wop = W8    ? v4i{(int)w[t].x, (int)w[t].y, (int)w[t].z, (int)w[t].w}
@@ -261,7 +303,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                                   : (h == 0 ? w_operand_tiled(w[t].x, w[t].y) : w_operand_tiled(w[t].z, w[t].w));
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt)
-                acc[mt][t] = mfma32(wop, v4i{(int)x[mt].x, (int)x[mt].y, (int)x[mt].z, (int)x[mt].w}, acc[mt][t]);
+                acc[mt][t] = mfma32(wop, v4i{(int)x[mt].x, (int)x[mt].y, (int)x[mt].z, (int)x[mt].w},
+                                    fresh ? v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0} : acc[mt][t]);
         }
     };
 
@@ -286,6 +329,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     __builtin_amdgcn_s_barrier();
 
     v4u x0[MTW], x1[MTW], w0[NTW], w1[NTW];
+    float sg[FG ? NTW : 1][16];
     read_x(x0, 0, 0);
     read_w(w0, 0, 0);
     int slot = 0;
@@ -305,7 +349,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         if (W8) read_w(w1, slot, 1);
         if (have_target) issue(target, prev, 0, 3);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_step(x0, w0, 0);
+        mfma_step(x0, w0, 0, FG);
         __builtin_amdgcn_sched_barrier(0);
         read_x(x0, slot, 2);
         if (W8)
@@ -318,6 +362,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         __builtin_amdgcn_sched_barrier(0);
         read_x(x1, slot, 3);
         if (W8) read_w(w1, slot, 3);
+        if constexpr (FG) read_sg(sg, slot);  // before the barrier that lets the slot be refilled
         if (have_target) issue(target, prev, 2, 3);
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(x0, *(W8 ? &w0 : &w1), 0);
@@ -340,6 +385,16 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(x1, w1, 1);
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (FG) {
+            // Dq of Eq. (2) for this group: a group's sums are below 2^24 in magnitude, so the conversion is exact
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                for (int t = 0; t < NTW; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        facc[mt][t][v] = __builtin_fmaf((float)acc[mt][t][v], sg[t][v], facc[mt][t][v]);
+        }
         slot = next;
     }
     wait_vmcnt<0>();
@@ -351,6 +406,14 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     // row, i.e. whole cache lines.
     // int4 sums are sixteen times the true sums (the nibbles sat in the high half of their bytes); int8 sums are true
     auto deq = [](int a, float s_a, float s_w) { return kTrueSums ? (float)a * (s_a * s_w) : dequant(a, s_a, s_w); };
+    // FG: the sixteen-fold fp32 sum times s_a / 16 (both scalings by a power of two are exact): one rounding, as in
+    // f * s_a on the true sum
+    auto value = [&](int mt, int t, int v, float s_a, float s_w) {
+        if constexpr (FG)
+            return facc[mt][t][v] * (s_a * 0.0625f);
+        else
+            return deq(acc[mt][t][v], s_a, s_w);
+    };
     if (!ACC_OUT && (p.ldc & 7) == 0) {
         constexpr int kRowBytes = 64 * NTW;        // fp16 bytes of a slab row (32 NTW channels)
         constexpr int kPitch = kRowBytes + 16;     // padded: rows 16 apart, not 1 apart, share banks
@@ -370,8 +433,9 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                 for (int q = 0; q < 4; ++q) {
                     const int nl = 32 * t + 8 * q + 4 * g;
                     const int n = n_wave + nl;
-                    float4 sw;
-                    if (n + 3 < p.N) {
+                    float4 sw = float4{0.f, 0.f, 0.f, 0.f};
+                    if constexpr (FG) {
+                    } else if (n + 3 < p.N) {
                         sw = *(const float4 *)(p.s_w + n);
                     } else {  // values past N are formed but never stored; keep their scale reads in bounds
                         const int last = p.N - 1;
@@ -381,8 +445,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                         sw.w = p.s_w[last];
                     }
                     v2u o;
-                    o.x = pack_f16x2(deq(acc[mt][t][4 * q], sa, sw.x), deq(acc[mt][t][4 * q + 1], sa, sw.y));
-                    o.y = pack_f16x2(deq(acc[mt][t][4 * q + 2], sa, sw.z), deq(acc[mt][t][4 * q + 3], sa, sw.w));
+                    o.x = pack_f16x2(value(mt, t, 4 * q, sa, sw.x), value(mt, t, 4 * q + 1, sa, sw.y));
+                    o.y = pack_f16x2(value(mt, t, 4 * q + 2, sa, sw.z), value(mt, t, 4 * q + 3, sa, sw.w));
                     *(v2u *)(slab + idx * kPitch + nl * 2) = o;
                 }
             }
@@ -436,15 +500,16 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
                 } else {
                     unsigned short *dst = (unsigned short *)p.out + (size_t)m * p.ldc + n;
                     if (vec_ok && n + 3 < p.N) {
-                        const float4 sw = *(const float4 *)(p.s_w + n);
+                        const float4 sw = FG ? float4{0.f, 0.f, 0.f, 0.f} : *(const float4 *)(p.s_w + n);
                         v2u o;
-                        o.x = pack_f16x2(deq(s.x, sa, sw.x), deq(s.y, sa, sw.y));
-                        o.y = pack_f16x2(deq(s.z, sa, sw.z), deq(s.w, sa, sw.w));
+                        o.x = pack_f16x2(value(mt, t, 4 * q, sa, sw.x), value(mt, t, 4 * q + 1, sa, sw.y));
+                        o.y = pack_f16x2(value(mt, t, 4 * q + 2, sa, sw.z), value(mt, t, 4 * q + 3, sa, sw.w));
                         *(v2u *)dst = o;
                     } else {
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            if (n + j < p.N) dst[j] = f32_to_f16_bits(deq(s[j], sa, p.s_w[n + j]));
+                            if (n + j < p.N)
+                                dst[j] = f32_to_f16_bits(value(mt, t, 4 * q + j, sa, FG ? 0.f : p.s_w[n + j]));
                     }
                 }
             }
@@ -454,12 +519,13 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
 
 namespace {
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS, bool UNS>
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS, bool UNS, bool FG>
 hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
-    constexpr int kLdsBytes = STAGES * (BM * 128 + BN * 16 * WBITS) + 1024;
+    // ring + spare KB; group scales: 128 NTW bytes per wave and ring slot, and a KB of slack behind them
+    constexpr int kLdsBytes = STAGES * (BM * 128 + BN * 16 * WBITS) + 1024 + (FG ? STAGES * WM * WN * NTW * 128 + 1024 : 0);
     static_assert(kLdsBytes <= 160 * 1024, "a workgroup's ring must fit the compute unit's LDS");
-    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS>;
+    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS, FG>;
     // more than 64 KB of LDS per workgroup has to be asked for, once per device
     static bool raised[64] = {};
     int dev = 0;
@@ -473,15 +539,20 @@ hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, int WBITS = 4, bool UNS = false>
+template <int MTW, int NTW, int WM, int WN, int STAGES, int WBITS = 4, bool UNS = false, bool FG = false>
 hipError_t launch_tile(PrefillArgs p, bool acc_out, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     const int total = p.tiles_m * p.tiles_n;
     const dim3 grid(8 * ((total + 7) / 8));
-    return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true, WBITS, UNS>(p, grid, stream)
-                   : launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS>(p, grid, stream);
+    if constexpr (FG) {
+        if (acc_out) return hipErrorInvalidValue;  // there is no single integer sum to return
+        return launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS, true>(p, grid, stream);
+    } else {
+        return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true, WBITS, UNS, false>(p, grid, stream)
+                       : launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS, false>(p, grid, stream);
+    }
 }
 
 // One thread per 16-byte chunk of the tiled int8 array (W8A8 variant): a plain gather, no reordering inside a chunk.
@@ -507,6 +578,9 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
     const long long kMaxBytes = 0xF0000000ll;
     const long long kb_total = (p.K + kTiledBlockK - 1) / kTiledBlockK;
     const long long block_bytes = (long long)kTiledBlockBytes * (wbits == 8 ? 2 : 1);
+    if (wbits == kWeightsFineGrained4 && (p.K % kTiledBlockK != 0 || p.ldg < p.N || (p.ldg & 3) != 0 ||
+                                          kb_total * (long long)p.ldg * 4 > kMaxBytes))
+        return hipErrorInvalidValue;
     long long m_rows = kMaxBytes / p.K, n_rows = kMaxBytes / (kb_total * (block_bytes / 32));
     m_rows -= m_rows % 256;
     n_rows -= n_rows % 1280;  // a multiple of every tile width
@@ -557,6 +631,18 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
                     case kTiled64x128: e = launch_tile<1, 2, 2, 2, 4, 4, true>(q, acc_out, stream); break;
                     case kTiled64x64: e = launch_tile<1, 1, 2, 2, 4, 4, true>(q, acc_out, stream); break;
                     case kTiled32x128: e = launch_tile<1, 1, 1, 4, 4, 4, true>(q, acc_out, stream); break;
+                    default: e = hipErrorInvalidConfiguration;
+                }
+            } else if (wbits == kWeightsFineGrained4) {
+                // one problem, one launch: the group scales are addressed with the whole problem's pitch
+                if (q.M != p.M || q.N != p.N) return hipErrorInvalidValue;
+                switch (tile) {
+                    case kFine128x256: e = launch_tile<2, 2, 2, 4, 3, 4, false, true>(q, acc_out, stream); break;
+                    case kFine256x128: e = launch_tile<2, 2, 4, 2, 3, 4, false, true>(q, acc_out, stream); break;
+                    case kFine128x128: e = launch_tile<2, 2, 2, 2, 3, 4, false, true>(q, acc_out, stream); break;
+                    case kFine64x128: e = launch_tile<1, 2, 2, 2, 4, 4, false, true>(q, acc_out, stream); break;
+                    case kFine64x64: e = launch_tile<1, 1, 2, 2, 4, 4, false, true>(q, acc_out, stream); break;
+                    case kFine32x128: e = launch_tile<1, 1, 1, 4, 4, 4, false, true>(q, acc_out, stream); break;
                     default: e = hipErrorInvalidConfiguration;
                 }
             } else {

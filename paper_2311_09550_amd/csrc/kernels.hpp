@@ -39,6 +39,7 @@ struct PrefillArgs {
     int *acc_out;
     int M, N, K;       // extent of this launch (a slice of the whole problem when that exceeds 32-bit byte offsets)
     int ldc;           // row stride of out / acc_out in elements (the full N)
+    int ldg;           // fine-grained variant only: s_w then holds group scales [K / 128][ldg], ldg >= N, ldg % 4 == 0
     int tiles_m, tiles_n;
 };
 
@@ -73,6 +74,16 @@ constexpr int kTiledTileMax = 8;
 // wbits = 4: packed int4 codes (blocks of 2 KB); wbits = 8: int8 codes of the W8A8 comparison variant (blocks of 4 KB);
 // wbits = kWeightsUnsigned4: the 2 KB blocks with unsigned nibbles u = w + 8 (the paper's vanilla storage, GEMM only)
 constexpr int kWeightsUnsigned4 = 104;
+// wbits = kWeightsFineGrained4: signed int4 blocks with one scale per group of 128 k and channel (the fine-grained
+// recipe of Eq. (2)); its accumulators take twice the registers, hence its own, smaller set of tiles
+constexpr int kWeightsFineGrained4 = 204;
+constexpr int kFine128x256 = 1;  // 8 waves of 64 x 64
+constexpr int kFine256x128 = 2;  // 8 waves of 64 x 64, four down and two across
+constexpr int kFine128x128 = 3;  // 4 waves of 64 x 64
+constexpr int kFine64x128 = 4;   // 4 waves of 32 x 64
+constexpr int kFine64x64 = 5;    // 4 waves of 32 x 32
+constexpr int kFine32x128 = 6;   // 4 waves of 32 x 32 side by side
+constexpr int kFineTileMax = 6;
 size_t tiled_weight_bytes(int N, int K, int wbits = 4);
 hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream);
 hipError_t launch_tile_weights8(const int8_t *w8, uint8_t *wt, int N, int K, hipStream_t stream);

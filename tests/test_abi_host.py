@@ -101,6 +101,13 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_gemm_tiled(p, p, p, p, p, 1, 16, 48, null) == -2
     assert L.w4a8_gemm_tiled_unsigned(p, p, null, p, p, null, 1, 16, 32, 0, null) == -1
     assert L.w4a8_gemm_tiled_unsigned(p, p, p, p, p, null, 1, 16, 32, 9, null) == -7
+    fg = L.w4a8_gemm_fine_grained
+    assert fg(p, p, p, null, 16, p, 1, 16, 128, 0, null) == -1
+    assert fg(p, p, p, p, 16, p, 1, 16, 160, 0, null) == -2      # K must be whole groups of 128
+    assert fg(p, p, p, p, 12, p, 1, 16, 128, 0, null) == -2      # pitch of the scales below N
+    assert fg(p, p, p, p, 18, p, 1, 16, 128, 0, null) == -2      # pitch not a multiple of 4
+    assert fg(p, p, p, p, 16, p, 1, 16, 128, 7, null) == -7      # unknown tile
+    assert fg(p, p, p, odd, 16, p, 1, 16, 128, 0, null) == -3
     assert L.w8a8_tile_weights(null, p, 32, 128, null) == -1
     assert L.w8a8_tile_weights(p, p, 32, 100, null) == -2
     assert L.w8a8_gemm_tiled(p, p, p, p, p, p, 1, 16, 32, 0, null) == -1        # both outputs
