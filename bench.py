@@ -226,8 +226,9 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
 
 def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
     """The paper sets its W4A8 against its own W8A8 (Table 4) and its signed storage against the vanilla unsigned one
-    ("Asym GEMM", Sec. 6.4).  Here, per GEMM: the same large-M kernel over tiled int4 (signed), tiled unsigned int4 and
-    tiled int8 weights of the same fp16 matrix, every launch on a different weight copy (copies exceed the last-level
+    ("Asym GEMM", Sec. 6.4) and the fine-grained recipe (group scales, Eq. (2)).  Here, per GEMM: the same large-M kernel
+    over tiled int4 (signed), tiled unsigned int4, signed int4 with group scales, and tiled int8 weights of the same
+    fp16 matrix, every launch on a different weight copy (copies exceed the last-level
     cache three times, so weights come from HBM), batches replayed from a HIP graph."""
     rows = []
     for name, (N, K) in synth.LLAMA_SHAPES[model].items():
@@ -238,38 +239,47 @@ def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
         # "u4": the vanilla unsigned storage, u = w + 8, i.e. bit 3 of every two's-complement nibble flipped
         wt = {4: w4a8.w4a8_tile_weights(wp), 8: w4a8.w8a8_tile_weights(w8), "u4": w4a8.w4a8_tile_weights(wp ^ 0x88)}
         del wp, w8
-        fmts = (4, "u4", 8)
-        copies = {b: max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wt[b].numel()) + 1) for b in fmts}
-        wts = {b: [wt[b]] + [wt[b].clone() for _ in range(copies[b] - 1)] for b in fmts}
+        # "fg": the fine-grained recipe (one scale per group of 128 k and channel, Eq. (2)) over the signed codes
+        s_g = torch.from_numpy(synth.group_scales(N, K, 128, config_id=3)).cuda()
+        fmts = (4, "u4", "fg", 8)
+        copies = {b: max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wt[b].numel()) + 1) for b in (4, "u4", 8)}
+        wts = {b: [wt[b]] + [wt[b].clone() for _ in range(copies[b] - 1)] for b in (4, "u4", 8)}
+        copies["fg"], wts["fg"] = copies[4], wts[4]
         for M in Ms:
             x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
             xq, s_a = w4a8.w4a8_quantize_act(x)
             out = torch.empty((M, N), dtype=torch.float16, device="cuda")
-            us = {}
+            calls = {4: lambda t: w4a8.w4a8_gemm_tiled(xq, s_a, t, s_w4, out=out),
+                     "u4": lambda t: w4a8.w4a8_gemm_tiled_unsigned(xq, s_a, t, s_w4, out=out),
+                     "fg": lambda t: w4a8.w4a8_gemm_fine_grained(xq, s_a, t, s_g, out=out),
+                     8: lambda t: w4a8.w8a8_gemm_tiled(xq, s_a, t, s_w8, out=out)}
+            graphs, launches = {}, {}
             for b in fmts:
-                call = {4: lambda t: w4a8.w4a8_gemm_tiled(xq, s_a, t, s_w4, out=out),
-                        "u4": lambda t: w4a8.w4a8_gemm_tiled_unsigned(xq, s_a, t, s_w4, out=out),
-                        8: lambda t: w4a8.w8a8_gemm_tiled(xq, s_a, t, s_w8, out=out)}[b]
-                call(wts[b][0])
+                calls[b](wts[b][0])
                 torch.cuda.synchronize()
-                n = max(copies[b], 8)
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph):
-                    for i in range(n):
-                        call(wts[b][i % copies[b]])
-                graph.replay()
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(iters):
-                    graph.replay()
-                e1.record()
-                torch.cuda.synchronize()
-                us[b] = e0.elapsed_time(e1) * 1e3 / (n * iters)
-                del graph
+                launches[b] = max(copies[b], 8)
+                graphs[b] = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graphs[b]):
+                    for i in range(launches[b]):
+                        calls[b](wts[b][i % copies[b]])
+                graphs[b].replay()
+            torch.cuda.synchronize()
+            # the formats take turns, so that drift of the clocks during the measurement touches all alike
+            ms = {b: 0.0 for b in fmts}
+            for _ in range(iters):
+                for b in fmts:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    graphs[b].replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ms[b] += e0.elapsed_time(e1)
+            us = {b: ms[b] * 1e3 / (launches[b] * iters) for b in fmts}
+            del graphs
             rows.append({"linear": name, "M": M, "w4a8_us": round(us[4], 2), "w4a8_unsigned_us": round(us["u4"], 2),
-                         "w8a8_us": round(us[8], 2), "unsigned_over_w4": round(us["u4"] / us[4], 3),
-                         "w8_over_w4": round(us[8] / us[4], 3)})
+                         "w4a8_fine_grained_us": round(us["fg"], 2), "w8a8_us": round(us[8], 2),
+                         "unsigned_over_w4": round(us["u4"] / us[4], 3),
+                         "fine_grained_over_w4": round(us["fg"] / us[4], 3), "w8_over_w4": round(us[8] / us[4], 3)})
         del wts, wt
         torch.cuda.empty_cache()
     return rows

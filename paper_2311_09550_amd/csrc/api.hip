@@ -95,10 +95,9 @@ int choose_tiled_tile(int M, int N) {
     // Medium M: when not even 128 x 128 tiles occupy three quarters of the compute units, run time is the length of
     // one workgroup's walk over K, and smaller tiles (more workgroups, each with a shorter stage) shorten it.
     auto count = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    if (count(128, 128) * 4 < (long long)cus * 3) {
-        if (M <= 32) return kTiled32x128;
+    if (M <= 32) return kTiled32x128;  // taller tiles would multiply rows that do not exist
+    if (M <= 64 || count(128, 128) * 4 < (long long)cus * 3)
         return count(64, 128) * 4 >= (long long)cus * 3 ? kTiled64x128 : kTiled64x64;
-    }
     int best = kTiled256x256;
     double best_cost = 0;
     for (const Option &o : options) {
@@ -112,17 +111,16 @@ int choose_tiled_tile(int M, int N) {
     return best;
 }
 
-// The choice among the fine-grained variant's tiles (initial efficiencies: equal work per byte staged for both
-// 128-row tiles; the 8-wave one occupies a compute unit alone).
+// The choice among the fine-grained variant's tiles (measured on LLaMA-13B shapes at M = 1024 and 4096: two
+// 128 x 128 workgroups per compute unit are never slower than one 128 x 256 workgroup of 8 waves).
 int choose_fine_tile(int M, int N) {
     const int cus = compute_units();
     auto count = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    if (count(128, 128) * 4 < (long long)cus * 3) {
-        if (M <= 32) return kFine32x128;
+    if (M <= 32) return kFine32x128;
+    if (M <= 64 || count(128, 128) * 4 < (long long)cus * 3)
         return count(64, 128) * 4 >= (long long)cus * 3 ? kFine64x128 : kFine64x64;
-    }
     struct Option { int id, bm, bn, per_cu; double eff; };
-    const Option options[] = {{kFine128x256, 128, 256, 1, 1.00}, {kFine128x128, 128, 128, 2, 0.90}};
+    const Option options[] = {{kFine128x256, 128, 256, 1, 0.95}, {kFine128x128, 128, 128, 2, 1.00}};
     int best = kFine128x256;
     double best_cost = 0;
     for (const Option &o : options) {
@@ -141,10 +139,9 @@ int choose_fine_tile(int M, int N) {
 int choose_tiled_tile8(int M, int N) {
     const int cus = compute_units();
     auto count = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    if (count(128, 128) * 4 < (long long)cus * 3) {
-        if (M <= 32) return kTiled32x128;
+    if (M <= 32) return kTiled32x128;  // taller tiles would multiply rows that do not exist
+    if (M <= 64 || count(128, 128) * 4 < (long long)cus * 3)
         return count(64, 128) * 4 >= (long long)cus * 3 ? kTiled64x128 : kTiled64x64;
-    }
     struct Option { int id, bm, bn, per_cu; double eff; };
     const Option options[] = {{kTiled256x256, 256, 256, 1, 1.00},
                               {kTiled128x256, 128, 256, 1, 0.80},
