@@ -120,16 +120,17 @@ class LayerStack:
             b.record()
             self.gemm_events.append((name, a, b))
 
-    def step(self, record=False):
+    def step(self, record=None):
+        """One pass over the eight launches; `record` names the GEMM to bracket with timing events (None: none)."""
         w = self.w4a8
         w.w4a8_quantize_act(self.h, self.xq_h, self.sa_h)
-        self._gemm("qkv", self.xq_h, self.sa_h, record)
+        self._gemm("qkv", self.xq_h, self.sa_h, record == "qkv")
         w.w4a8_quantize_act(self.attn, self.xq_h, self.sa_h)
-        self._gemm("o", self.xq_h, self.sa_h, record)
+        self._gemm("o", self.xq_h, self.sa_h, record == "o")
         w.w4a8_quantize_act(self.h2, self.xq_h, self.sa_h)
-        self._gemm("gate_up", self.xq_h, self.sa_h, record)
+        self._gemm("gate_up", self.xq_h, self.sa_h, record == "gate_up")
         w.w4a8_silu_mul_quantize(self.out["gate_up"], self.xq_i, self.sa_i)   # SiLU*up and its quantiser, one pass
-        self._gemm("down", self.xq_i, self.sa_i, record)
+        self._gemm("down", self.xq_i, self.sa_i, record == "down")
 
     def gemms_only(self):
         for name, xq, sa in (("qkv", self.xq_h, self.sa_h), ("o", self.xq_h, self.sa_h), ("gate_up", self.xq_h, self.sa_h),
@@ -350,8 +351,11 @@ def main():
         stack.step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        stack.step(record=True)
+    # every step brackets one of its four GEMMs with events, in rotation: each event is a packet of its own in the
+    # queue and widens the gap between launches, so instrumenting all four would slow down the step being timed
+    names = list(stack.shapes)
+    for i in range(args.steps):
+        stack.step(record=names[i % len(names)])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
@@ -362,14 +366,13 @@ def main():
     for name, a, b in stack.gemm_events:
         per.setdefault(name, []).append(a.elapsed_time(b) * 1e3)
     gemm_us = {k: sum(v) / len(v) for k, v in per.items()}
-    launches = sum(len(v) for v in per.values())
-    avg_us = sum(sum(v) for v in per.values()) / launches
-    ops_per_launch = stack.ops_per_step() / len(per)
+    avg_us = sum(gemm_us.values()) / len(gemm_us)      # mean over the linears of each linear's mean launch
+    ops_per_launch = sum(gemm_ops(M, *stack.shapes[k]) for k in gemm_us) / len(gemm_us)
     achieved = ops_per_launch / avg_us / 1e6   # TOPS
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(("13b", M)),
                 "traffic_unit": "bytes per launch (L2 fills + write-backs)",
-                "algorithmic_bytes_per_launch": round(sum(gemm_bytes(M, N, K) for N, K in stack.shapes.values()) / len(per)),
+                "algorithmic_bytes_per_launch": round(sum(gemm_bytes(M, *stack.shapes[k]) for k in gemm_us) / len(gemm_us)),
                 "kernel": "gemm_prefill_tiled_kernel", "avg_launch_us": round(avg_us, 2),
                 "per_linear_us": {k: round(v, 2) for k, v in gemm_us.items()},
                 "per_linear_tops": {k: round(gemm_ops(M, *stack.shapes[k]) / v / 1e6, 1) for k, v in gemm_us.items()}}

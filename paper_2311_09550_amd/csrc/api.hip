@@ -184,7 +184,7 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
         if (mt == 4 && s.row_tiles == 2 && s.waves == 8) return W4A8_ERR_ARG;  // would not fit in LDS
         pl->decode = s;
     } else if (pl->tiling == W4A8_TILING_PREFILL_TILED) {
-        if (variant < 0 || variant > kTiledTileMax) return W4A8_ERR_ARG;
+        if (variant < 0 || variant > kTiledTileMax4) return W4A8_ERR_ARG;
         pl->prefill_tile = variant ? variant : choose_tiled_tile(M, N);
     } else {
         if (variant < 0 || variant > kPrefillTileMax) return W4A8_ERR_ARG;
@@ -363,7 +363,7 @@ static int gemm_tiled_variant(const int8_t *xq, const float *s_a, const uint8_t 
     if (!xq || !wt) return W4A8_ERR_NULL;
     if (!want_acc && (!s_a || !s_w)) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, N, K)) return e;
-    if (variant < 0 || variant > kTiledTileMax) return W4A8_ERR_ARG;
+    if (variant < 0 || variant > (wfmt == 4 ? kTiledTileMax4 : kTiledTileMax)) return W4A8_ERR_ARG;
     if (misaligned(xq) || misaligned(wt) || misaligned(out_fp16) || misaligned(acc_i32) || (s_w && misaligned(s_w)))
         return W4A8_ERR_ALIGN;
     PrefillArgs a{};

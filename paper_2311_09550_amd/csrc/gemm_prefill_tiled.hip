@@ -115,8 +115,14 @@ __global__ __launch_bounds__(256) void tile_weights_kernel(const uint8_t *__rest
 // by the group's scales, into a second, floating-point set of accumulators: per MFMA 8 extra VALU operations, twice
 // the accumulator registers (which rules out the 256 x 256 tile), and one more 16-byte load per wave and stage (each
 // wave brings in the 32 NTW scales it needs itself, next to its share of the operands).
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS = 4, bool UNS = false, bool FG = false>
-__global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(PrefillArgs p) {
+// KS = 2 (signed int4, per-channel scales only): two sets of WM x WN waves share the output tile and split every
+// stage's k between them (set ks takes k = 64 ks .. 64 ks + 63 of the stage, i.e. MFMA steps 2 ks and 2 ks + 1); their
+// integer sums meet in LDS before the epilogue.  For tiles that a compute unit holds only once (N too small for
+// more workgroups) this doubles the waves per SIMD without shrinking the tile.
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS = 4, bool UNS = false, bool FG = false,
+          int KS = 1>
+__global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kernel(PrefillArgs p) {
+    static_assert(KS == 1 || (KS == 2 && WBITS == 4 && !UNS && !FG && STAGES == 3), "k split: the plain W4A8 kernel only");
     static_assert(WBITS == 4 || WBITS == 8, "int4 or int8 weight codes");
     static_assert(!UNS || WBITS == 4, "the unsigned storage is a 4-bit format");
     static_assert(!FG || (WBITS == 4 && !UNS && !ACC_OUT), "group scales: signed int4 codes, fp16 output");
@@ -124,7 +130,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     constexpr bool kTrueSums = W8 || UNS;  // else every sum is sixteen times the true one
     constexpr int kBlock = kTiledBlockK * 32 * WBITS / 8;  // bytes of a weight block: 2 KB or 4 KB
     constexpr int kParts = kBlock / 1024;                  // wave loads per block
-    constexpr int kWaves = WM * WN;
+    constexpr int kOutWaves = WM * WN;     // waves that own a part of the output tile
+    constexpr int kWaves = kOutWaves * KS;
     constexpr int BM = 32 * MTW * WM;
     constexpr int BN = 32 * NTW * WN;
     constexpr int A_TOTAL = BM / 8;                 // wave loads (8 rows x 128 B) of an activation stage
@@ -146,8 +153,10 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps LDS addresses in scalar registers
-    const int wm = wave / WN;
-    const int wn = wave % WN;
+    const int ks = wave / kOutWaves;       // which half of every stage's k this wave multiplies (KS = 2)
+    const int wsub = wave % kOutWaves;
+    const int wm = wsub / WN;
+    const int wn = wsub % WN;
     const int idx = lane & 31;
     const int g = lane >> 5;
 
@@ -269,10 +278,11 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         }
     }
     const int wa = kBBase + wn * (NTW * kBlock) + (g * 32 + idx) * 16;
-    auto read_x = [&](v4u(&dst)[MTW], int slot, int j) {
+    auto read_x_at = [&](v4u(&dst)[MTW], int slot, int offset) {
 #pragma unroll
-        for (int mt = 0; mt < MTW; ++mt) dst[mt] = *(const v4u *)(&lds[slot * A_STAGE + xa[j] + mt * 4096]);
+        for (int mt = 0; mt < MTW; ++mt) dst[mt] = *(const v4u *)(&lds[slot * A_STAGE + offset + mt * 4096]);
     };
+    auto read_x = [&](v4u(&dst)[MTW], int slot, int j) { read_x_at(dst, slot, xa[j]); };
     // weight fragments of the pair of chunks q: int4 -> q = 0, 1 serves MFMA steps 2q and 2q + 1 (halves h = 0, 1 of
     // the fragment); int8 -> q = 0 .. 3 serves MFMA step q
     auto read_w = [&](v4u(&dst)[NTW], int slot, int q) {
@@ -330,74 +340,141 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
 
     v4u x0[MTW], x1[MTW], w0[NTW], w1[NTW];
     float sg[FG ? NTW : 1][16];
-    read_x(x0, 0, 0);
-    read_w(w0, 0, 0);
     int slot = 0;
-    for (int st = 0; st < st_total; ++st) {
-        const int next = slot + 1 == STAGES ? 0 : slot + 1;
-        const int prev = slot == 0 ? STAGES - 1 : slot - 1;
-        const int target = st + STAGES - 1;            // kSpread: the stage requested during this one
-        const bool have_target = kSpread && target < st_total;
-        // The scheduling fences keep each block of LDS reads in front of the MFMA block it overlaps with; left alone
-        // the compiler sinks the reads next to their first use and every step then starts with an exposed LDS wait.
-        // The fragments of step 0 were requested eight MFMAs ago; waiting for them here, before the next reads go
-        // out, costs nothing and spares the wait the compiler would otherwise place behind those reads.
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-        // Weight registers: int4 fragments hold two steps (w0: steps 0, 1; w1: steps 2, 3); int8 fragments one step
-        // each, w0 and w1 taking turns (w0: steps 0, 2; w1: steps 1, 3).
-        read_x(x1, slot, 1);
-        if (W8) read_w(w1, slot, 1);
-        if (have_target) issue(target, prev, 0, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(x0, w0, 0, FG);
-        __builtin_amdgcn_sched_barrier(0);
-        read_x(x0, slot, 2);
-        if (W8)
-            read_w(w0, slot, 2);
-        else
-            read_w(w1, slot, 1);
-        if (have_target) issue(target, prev, 1, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(x1, *(W8 ? &w1 : &w0), 1);
-        __builtin_amdgcn_sched_barrier(0);
-        read_x(x1, slot, 3);
-        if (W8) read_w(w1, slot, 3);
-        if constexpr (FG) read_sg(sg, slot);  // before the barrier that lets the slot be refilled
-        if (have_target) issue(target, prev, 2, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(x0, *(W8 ? &w0 : &w1), 0);
-        __builtin_amdgcn_sched_barrier(0);
-        // Every fragment of this stage is in registers once the reads above have returned, so after the barrier the
-        // slot can be refilled; stage st + 1 must be in LDS for every wave.
-        if (kSpread ? have_target : st + STAGES <= st_total)
-            wait_vmcnt<(STAGES - 2) * kLoads>();  // the stages behind st + 1 may still be in flight
-        else
-            wait_vmcnt<0>();
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's last fragment reads of the slot have returned
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-        if (!kSpread && st + STAGES < st_total) issue(st + STAGES, slot, 0, 1);
-        if (st + 1 < st_total) {
-            read_x(x0, next, 0);
-            read_w(w0, next, 0);
+    if constexpr (KS == 2) {
+        // Per stage and wave two MFMA steps (2 ks and 2 ks + 1, one weight fragment) with the barrier between them:
+        // by then this wave has every fragment of the stage in registers.  The target stage goes out in halves,
+        // one before and one behind the barrier, so behind the barrier's wait only the first half may be in flight.
+        static_assert(kSpread, "the k split uses the spread schedule");
+        constexpr int kFirstHalf = (kLoads + 1) / 2;
+        const int xa_first = ks ? xa[2] : xa[0], xa_second = ks ? xa[3] : xa[1];
+        read_x_at(x0, 0, xa_first);
+        read_w(w0, 0, ks);
+        for (int st = 0; st < st_total; ++st) {
+            const int next = slot + 1 == STAGES ? 0 : slot + 1;
+            const int prev = slot == 0 ? STAGES - 1 : slot - 1;
+            const int target = st + STAGES - 1;
+            const bool have_target = target < st_total;
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+            read_x_at(x1, slot, xa_second);
+            if (have_target) issue(target, prev, 0, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(x0, w0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (have_target)
+                wait_vmcnt<kFirstHalf>();
+            else
+                wait_vmcnt<0>();
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            if (have_target) issue(target, prev, 1, 2);
+            if (st + 1 < st_total) {
+                read_x_at(x0, next, xa_first);
+                read_w(w1, next, ks);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(x1, w0, 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < NTW; ++t) w0[t] = w1[t];
+            slot = next;
         }
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(x1, w1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (FG) {
-            // Dq of Eq. (2) for this group: a group's sums are below 2^24 in magnitude, so the conversion is exact
+    } else {
+        read_x(x0, 0, 0);
+        read_w(w0, 0, 0);
+        for (int st = 0; st < st_total; ++st) {
+            const int next = slot + 1 == STAGES ? 0 : slot + 1;
+            const int prev = slot == 0 ? STAGES - 1 : slot - 1;
+            const int target = st + STAGES - 1;            // kSpread: the stage requested during this one
+            const bool have_target = kSpread && target < st_total;
+            // The scheduling fences keep each block of LDS reads in front of the MFMA block it overlaps with; left alone
+            // the compiler sinks the reads next to their first use and every step then starts with an exposed LDS wait.
+            // The fragments of step 0 were requested eight MFMAs ago; waiting for them here, before the next reads go
+            // out, costs nothing and spares the wait the compiler would otherwise place behind those reads.
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+            // Weight registers: int4 fragments hold two steps (w0: steps 0, 1; w1: steps 2, 3); int8 fragments one step
+            // each, w0 and w1 taking turns (w0: steps 0, 2; w1: steps 1, 3).
+            read_x(x1, slot, 1);
+            if (W8) read_w(w1, slot, 1);
+            if (have_target) issue(target, prev, 0, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(x0, w0, 0, FG);
+            __builtin_amdgcn_sched_barrier(0);
+            read_x(x0, slot, 2);
+            if (W8)
+                read_w(w0, slot, 2);
+            else
+                read_w(w1, slot, 1);
+            if (have_target) issue(target, prev, 1, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(x1, *(W8 ? &w1 : &w0), 1);
+            __builtin_amdgcn_sched_barrier(0);
+            read_x(x1, slot, 3);
+            if (W8) read_w(w1, slot, 3);
+            if constexpr (FG) read_sg(sg, slot);  // before the barrier that lets the slot be refilled
+            if (have_target) issue(target, prev, 2, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(x0, *(W8 ? &w0 : &w1), 0);
+            __builtin_amdgcn_sched_barrier(0);
+            // Every fragment of this stage is in registers once the reads above have returned, so after the barrier the
+            // slot can be refilled; stage st + 1 must be in LDS for every wave.
+            if (kSpread ? have_target : st + STAGES <= st_total)
+                wait_vmcnt<(STAGES - 2) * kLoads>();  // the stages behind st + 1 may still be in flight
+            else
+                wait_vmcnt<0>();
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's last fragment reads of the slot have returned
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+            if (!kSpread && st + STAGES < st_total) issue(st + STAGES, slot, 0, 1);
+            if (st + 1 < st_total) {
+                read_x(x0, next, 0);
+                read_w(w0, next, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(x1, w1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (FG) {
+                // Dq of Eq. (2) for this group: a group's sums are below 2^24 in magnitude, so the conversion is exact
+#pragma unroll
+                for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                    for (int t = 0; t < NTW; ++t)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            facc[mt][t][v] = __builtin_fmaf((float)acc[mt][t][v], sg[t][v], facc[mt][t][v]);
+            }
+            slot = next;
+        }
+    }
+    wait_vmcnt<0>();
+
+    if constexpr (KS == 2) {
+        // The two k halves meet: the ring is idle (the last barrier lies behind every wave's last fragment read and
+        // every load has landed), the upper set parks its sums behind the area the epilogue's slabs will use and leaves.
+        constexpr int kRedBase = kOutWaves * 32 * (64 * NTW + 16);
+        int *part = (int *)(lds + kRedBase) + wsub * (MTW * NTW * 16 * 64) + lane;
+        if (ks == 1) {
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
                 for (int t = 0; t < NTW; ++t)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        facc[mt][t][v] = __builtin_fmaf((float)acc[mt][t][v], sg[t][v], facc[mt][t][v]);
+                    for (int v = 0; v < 16; ++v) part[((mt * NTW + t) * 16 + v) * 64] = acc[mt][t][v];
         }
-        slot = next;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        if (ks == 1) return;
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+            for (int t = 0; t < NTW; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mt][t][v] += part[((mt * NTW + t) * 16 + v) * 64];
     }
-    wait_vmcnt<0>();
 
     // Epilogue (Eq. (6),(7)).  A lane holds, per (mt, t, quad), four consecutive n of one m, so storing from the
     // accumulator layout writes 16 bytes into each of 32 different rows per instruction.  Instead every wave turns
@@ -419,8 +496,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
         constexpr int kPitch = kRowBytes + 16;     // padded: rows 16 apart, not 1 apart, share banks
         constexpr int kChunksPerRow = 4 * NTW;     // 16-byte chunks
         constexpr int kReads = (32 * kChunksPerRow + 63) / 64;
-        static_assert(kWaves * 32 * kPitch <= STAGES * (A_STAGE + B_STAGE), "slabs must fit the ring");
-        uint8_t *slab = lds + wave * (32 * kPitch);
+        static_assert(kOutWaves * 32 * kPitch <= STAGES * (A_STAGE + B_STAGE), "slabs must fit the ring");
+        uint8_t *slab = lds + wsub * (32 * kPitch);
         const int n_wave = bn0 + wn * (32 * NTW);
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt) {
@@ -519,13 +596,16 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_prefill_tiled_kernel(Pre
 
 namespace {
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS, bool UNS, bool FG>
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS, bool UNS, bool FG, int KS>
 hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
     // ring + spare KB; group scales: 128 NTW bytes per wave and ring slot, and a KB of slack behind them
-    constexpr int kLdsBytes = STAGES * (BM * 128 + BN * 16 * WBITS) + 1024 + (FG ? STAGES * WM * WN * NTW * 128 + 1024 : 0);
+    constexpr int kRing = STAGES * (BM * 128 + BN * 16 * WBITS) + 1024 + (FG ? STAGES * WM * WN * NTW * 128 + 1024 : 0);
+    // k split: the epilogue's slabs and, behind them, the parked sums of the upper wave set
+    constexpr int kMeet = KS == 2 ? WM * WN * (32 * (64 * NTW + 16) + MTW * NTW * 16 * 256) : 0;
+    constexpr int kLdsBytes = kRing > kMeet ? kRing : kMeet;
     static_assert(kLdsBytes <= 160 * 1024, "a workgroup's ring must fit the compute unit's LDS");
-    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS, FG>;
+    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS, FG, KS>;
     // more than 64 KB of LDS per workgroup has to be asked for, once per device
     static bool raised[64] = {};
     int dev = 0;
@@ -535,11 +615,11 @@ hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
         if (e != hipSuccess) return e;
         raised[dev] = true;
     }
-    hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN), kLdsBytes, stream, p);
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN * KS), kLdsBytes, stream, p);
     return hipGetLastError();
 }
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, int WBITS = 4, bool UNS = false, bool FG = false>
+template <int MTW, int NTW, int WM, int WN, int STAGES, int WBITS = 4, bool UNS = false, bool FG = false, int KS = 1>
 hipError_t launch_tile(PrefillArgs p, bool acc_out, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
     p.tiles_m = (p.M + BM - 1) / BM;
@@ -548,10 +628,10 @@ hipError_t launch_tile(PrefillArgs p, bool acc_out, hipStream_t stream) {
     const dim3 grid(8 * ((total + 7) / 8));
     if constexpr (FG) {
         if (acc_out) return hipErrorInvalidValue;  // there is no single integer sum to return
-        return launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS, true>(p, grid, stream);
+        return launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS, true, 1>(p, grid, stream);
     } else {
-        return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true, WBITS, UNS, false>(p, grid, stream)
-                       : launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS, false>(p, grid, stream);
+        return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true, WBITS, UNS, false, KS>(p, grid, stream)
+                       : launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS, false, KS>(p, grid, stream);
     }
 }
 
@@ -606,6 +686,8 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
                     case kTiled64x128: e = launch_tile<1, 2, 2, 2, 4>(q, acc_out, stream); break;
                     case kTiled64x64: e = launch_tile<1, 1, 2, 2, 4>(q, acc_out, stream); break;
                     case kTiled32x128: e = launch_tile<1, 1, 1, 4, 4>(q, acc_out, stream); break;
+                    case kTiled128x160K2: e = launch_tile<1, 5, 4, 1, 3, 4, false, false, 2>(q, acc_out, stream); break;
+                    case kTiled128x128K2: e = launch_tile<2, 2, 2, 2, 3, 4, false, false, 2>(q, acc_out, stream); break;
                     default: e = hipErrorInvalidConfiguration;
                 }
             } else if (wbits == 8) {

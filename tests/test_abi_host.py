@@ -93,7 +93,7 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_silu_mul(p, p, 1, 12, null) == -2
     assert L.w4a8_silu_mul_quantize(p, null, p, 1, 32, null) == -1
     assert L.w4a8_silu_mul_quantize(p, p, p, 1, 24, null) == -2
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 4, 9, p, big, null) == -7       # tiled layout: unknown tile id
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 4, 11, p, big, null) == -7      # tiled layout: unknown tile id
     assert L.w4a8_tile_weights(null, p, 32, 128, null) == -1
     assert L.w4a8_tile_weights(p, p, 32, 100, null) == -2
     assert L.w4a8_tile_weights(p, odd, 32, 128, null) == -3

@@ -12,7 +12,8 @@ from parity import assert_equal_bits, assert_fp16_close
 pytestmark = pytest.mark.gpu
 
 TILED = w4a8.TILING_PREFILL_TILED
-TILES = [1, 2, 3, 4, 5, 6, 7, 8]   # 256x256 (2x4 waves), 256x256 (4x2), 128x256, 128x160, 128x128, 64x128, 64x64, 32x128
+BASE_TILES = [1, 2, 3, 4, 5, 6, 7, 8]   # 256x256 (2x4 waves), 256x256 (4x2), 128x256, 128x160, 128x128, 64x128, 64x64, 32x128
+TILES = BASE_TILES + [9, 10]            # signed int4 only: 128x160 and 128x128 with two wave sets splitting each stage's k
 
 
 def tiled_layout(wq):
@@ -102,7 +103,7 @@ def test_gemm_tiled_entry_equals_row_major_entry(gpu, oracle):
         assert_fp16_close(b.cpu().numpy(), y32, acc_o, f"tiled entry M={M}")
 
 
-@pytest.mark.parametrize("tile", TILES)
+@pytest.mark.parametrize("tile", BASE_TILES)
 @pytest.mark.parametrize("M,N,K", [(1, 520, 1056), (65, 520, 1056), (300, 520, 1056), (200, 1001, 160), (384, 300, 5120)])
 def test_unsigned_storage_variant(gpu, oracle, M, N, K, tile):
     """The storage ablation (unsigned nibbles u = w + 8, 8 subtracted in registers) against the oracle's definition of
