@@ -70,7 +70,8 @@ def parse_args():
     return ap.parse_args()
 
 
-DECODE_MAX_M = 64   # up to here the row-major array and the weight-streaming kernels, above it the tiled array
+RESIDENT_MAX_M = 16  # the layer stack uses the weight-streaming kernels over the row-major array up to here; above it the tiled array,
+                     # with K cut into slices where the tiles alone would not fill the chip (2x faster at M = 32 .. 64)
 
 
 def prepare_weights(torch, w4a8, synth, model="13b"):
@@ -92,7 +93,7 @@ class LayerStack:
         self.torch, self.w4a8, self.M = torch, w4a8, M
         self.shapes = synth.LLAMA_SHAPES[model]
         dev = "cuda"
-        self.tiled = M > DECODE_MAX_M
+        self.tiled = M > RESIDENT_MAX_M
         self.wp = {k: (v[1] if self.tiled else v[0]) for k, v in weights.items()}
         self.s_w = {k: v[2] for k, v in weights.items()}
         H = self.shapes["qkv"][1]
@@ -105,43 +106,51 @@ class LayerStack:
         self.xq_h, self.sa_h = e(M, H, dt=torch.int8), e(M, dt=torch.float32)
         self.xq_i, self.sa_i = e(M, I, dt=torch.int8), e(M, dt=torch.float32)
         self.out = {name: e(M, N, dt=torch.float16) for name, (N, K) in self.shapes.items()}
+        # scratch for the GEMMs whose K the library cuts into slices (medium M; empty where it does not)
+        self.ws = {name: e(max(16, w4a8.w4a8_gemm_tiled_workspace_bytes(M, N, K)), dt=torch.uint8)
+                   for name, (N, K) in self.shapes.items()} if self.tiled else {}
         self.gemm_events = []   # (name, start, stop) around GEMM launches, filled when record=True
+        # the eight launches with their arguments marshalled once: the timed loop then spends its host time in the
+        # library, not in Python
+        b = w4a8.bound_call
+        self.quant = {"qkv": b("w4a8_quantize_act", self.h, self.xq_h, self.sa_h, M, H),
+                      "o": b("w4a8_quantize_act", self.attn, self.xq_h, self.sa_h, M, H),
+                      "gate_up": b("w4a8_quantize_act", self.h2, self.xq_h, self.sa_h, M, H),
+                      "down": b("w4a8_silu_mul_quantize", self.out["gate_up"], self.xq_i, self.sa_i, M, I)}
+        self.gemm = {}
+        for name, (N, K) in self.shapes.items():
+            xq, sa = (self.xq_i, self.sa_i) if name == "down" else (self.xq_h, self.sa_h)
+            if self.tiled:
+                self.gemm[name] = b("w4a8_gemm_tiled_splitk", xq, sa, self.wp[name], self.s_w[name], self.out[name], M, N, K,
+                                    0, 0, self.ws[name], self.ws[name].numel())
+            else:
+                self.gemm[name] = b("w4a8_gemm", xq, sa, self.wp[name], self.s_w[name], self.out[name], M, N, K, None, 0)
 
-    def _gemm(self, name, xq, sa, record):
-        t, w = self.torch, self.w4a8
+    def _gemm(self, name, record=False):
         if record:
+            t = self.torch
             a, b = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
             a.record()
-        if self.tiled:
-            w.w4a8_gemm_tiled(xq, sa, self.wp[name], self.s_w[name], out=self.out[name])
-        else:
-            w.w4a8_gemm(xq, sa, self.wp[name], self.s_w[name], out=self.out[name])
+        self.gemm[name]()
         if record:
             b.record()
             self.gemm_events.append((name, a, b))
 
     def step(self, record=None):
         """One pass over the eight launches; `record` names the GEMM to bracket with timing events (None: none)."""
-        w = self.w4a8
-        w.w4a8_quantize_act(self.h, self.xq_h, self.sa_h)
-        self._gemm("qkv", self.xq_h, self.sa_h, record == "qkv")
-        w.w4a8_quantize_act(self.attn, self.xq_h, self.sa_h)
-        self._gemm("o", self.xq_h, self.sa_h, record == "o")
-        w.w4a8_quantize_act(self.h2, self.xq_h, self.sa_h)
-        self._gemm("gate_up", self.xq_h, self.sa_h, record == "gate_up")
-        w.w4a8_silu_mul_quantize(self.out["gate_up"], self.xq_i, self.sa_i)   # SiLU*up and its quantiser, one pass
-        self._gemm("down", self.xq_i, self.sa_i, record == "down")
+        for name in ("qkv", "o", "gate_up", "down"):
+            self.quant[name]()           # "down": SiLU*up and its quantiser in one pass
+            self._gemm(name, record == name)
 
     def gemms_only(self):
-        for name, xq, sa in (("qkv", self.xq_h, self.sa_h), ("o", self.xq_h, self.sa_h), ("gate_up", self.xq_h, self.sa_h),
-                             ("down", self.xq_i, self.sa_i)):
-            self._gemm(name, xq, sa, False)
+        for name in ("qkv", "o", "gate_up", "down"):
+            self.gemm[name]()
 
     def ops_per_step(self):
         return sum(gemm_ops(self.M, N, K) for N, K in self.shapes.values())
 
 
-def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 16, 128, 1024, 2048), steps_per_graph=8, replays=6):
+def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 16, 64, 128, 1024, 2048), steps_per_graph=8, replays=6):
     """The decoder layer's linear stack at several M, replayed from a HIP graph (what a serving loop does; at small M
     the eight launches would otherwise be timed by the interpreter).  Layer time = graph time / steps; the GEMM share
     is the time of a second graph that holds only the four GEMMs, over the layer time.  One layer's weights (158 MB)

@@ -172,6 +172,24 @@ int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const 
                                   uint8_t *wp, float *s_w, int N, int K, void *stream);
 
 /*
+ * w4a8_gemm_tiled for shapes whose output tiles alone would leave most of the chip idle (medium M, small N: e.g.
+ * 40 tiles for M = 32, N = 5120): K is cut into slices, every (tile, slice) pair is a workgroup of the same kernel that
+ * writes its raw int32 sums to a slab of the workspace, and a second kernel adds the slabs and applies Eq. (6),(7).
+ * Integer sums do not depend on the order of addition: the output has the bits w4a8_gemm_tiled gives.
+ *   variant : output tile as for W4A8_TILING_PREFILL_TILED, 0 = library's choice;
+ *   splits  : number of K slices, 0 = library's choice (1 when the tiles fill the chip: then this is w4a8_gemm_tiled
+ *             and the workspace is not touched), at most 64 and at most K / 128 rounded up;
+ *   workspace (device, 16-byte aligned), workspace_bytes: at least splits * M * N * 4 bytes when more than one slice is
+ *             used, else W4A8_ERR_WORKSPACE; w4a8_gemm_tiled_workspace_bytes(M, N, K) is the size the library's own
+ *             choice (splits = 0) needs, 0 if it does not split.  Contents on return: unspecified.
+ *   With more than one slice M * K and the tiled weight bytes must each be below 0xF0000000 (W4A8_ERR_SHAPE).
+ */
+size_t w4a8_gemm_tiled_workspace_bytes(int M, int N, int K);
+int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
+                           int M, int N, int K, int variant, int splits, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/*
  * W8A8 comparison variant (the paper sets its W4A8 against its own W8A8, Table 4): the same contraction and the
  * same epilogue (Eq. (6),(7)) with int8 weight codes,
  *   O[m][n] = fp16( float( sum_k Xq[m][k] * W8[n][k] ) * (s_a[m] * s_w[n]) ),   W8 in [-128, 127],

@@ -60,6 +60,10 @@ def lib():
         L.w8a8_tile_weights.restype = i
         L.w8a8_gemm_tiled.restype = i
         L.w4a8_gemm_tiled_unsigned.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+        L.w4a8_gemm_tiled_workspace_bytes.restype = sz
+        L.w4a8_gemm_tiled_workspace_bytes.argtypes = [i, i, i]
+        L.w4a8_gemm_tiled_splitk.restype = i
+        L.w4a8_gemm_tiled_splitk.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
         L.w4a8_gemm_fine_grained.restype = i
         L.w4a8_gemm_fine_grained.argtypes = [vp, vp, vp, vp, i, vp, i, i, i, i, vp]
         L.w4a8_gemm_tiled_unsigned.restype = i
@@ -90,6 +94,28 @@ def _dev(t, dtype, what):
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError(f"{what}: expected a contiguous device tensor of {dtype}")
     return ctypes.c_void_p(t.data_ptr())
+
+
+def bound_call(name: str, *args):
+    """A launch with its arguments marshalled once, for loops that repeat the same call: `name` is an entry point of
+    the C ABI, `args` its arguments in the C order without the trailing stream (device tensors, ints, or None for a
+    NULL pointer).  Returns a function of no arguments that launches on torch's current stream and raises on an error
+    code.  The tensors are kept alive by the returned function; shapes and dtypes are the caller's responsibility here
+    (the C side still validates pointers, sizes and alignment)."""
+    torch = _torch()
+    fn = getattr(lib(), name)
+    keep = [a for a in args if isinstance(a, torch.Tensor)]
+    for t in keep:
+        if not (t.is_cuda and t.is_contiguous()):
+            raise TypeError(f"{name}: expected contiguous device tensors")
+    cargs = [ctypes.c_void_p(a.data_ptr()) if isinstance(a, torch.Tensor) else a for a in args]
+    current_stream = torch.cuda.current_stream
+
+    def call(_keep=keep):
+        code = fn(*cargs, ctypes.c_void_p(current_stream().cuda_stream))
+        if code != 0:
+            _check(code)
+    return call
 
 
 def w4a8_version() -> int:
@@ -287,6 +313,31 @@ def w4a8_gemm_tiled_unsigned(xq, s_a, ut, s_w, N=None, variant: int = 0, want_ac
         raise ValueError("out shape mismatch")
     _check(lib().w4a8_gemm_tiled_unsigned(_dev(xq, torch.int8, "xq"), sa, _dev(ut, torch.uint8, "ut"), sw, o16, o32, M, N, K,
                                           variant, _stream()))
+    return out
+
+
+def w4a8_gemm_tiled_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().w4a8_gemm_tiled_workspace_bytes(M, N, K))
+
+
+def w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, variant: int = 0, splits: int = 0, ws=None, out=None):
+    """w4a8_gemm_tiled with K cut into slices over workgroups when the tiles alone would not fill the chip.  ws: a
+    uint8 device buffer of at least w4a8_gemm_tiled_workspace_bytes(M, N, K) bytes (splits = 0) or splits * M * N * 4
+    (forced); allocated here when None."""
+    torch = _torch()
+    M, K = xq.shape
+    N = s_w.shape[0]
+    if wt.numel() != w4a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (N, K)")
+    out = torch.empty((M, N), dtype=torch.float16, device=xq.device) if out is None else out
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    if ws is None:
+        need = w4a8_gemm_tiled_workspace_bytes(M, N, K) if splits == 0 else max(splits, 1) * M * N * 4
+        ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=xq.device)
+    _check(lib().w4a8_gemm_tiled_splitk(_dev(xq, torch.int8, "xq"), _dev(s_a, torch.float32, "s_a"), _dev(wt, torch.uint8, "wt"),
+                                        _dev(s_w, torch.float32, "s_w"), _dev(out, torch.float16, "out"), M, N, K, variant,
+                                        splits, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
     return out
 
 

@@ -303,6 +303,87 @@ int w4a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const
     return run_gemm(xq, s_a, wt, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_PREFILL_TILED, 0, stream);
 }
 
+// ---- K split over workgroups for shapes whose tiles alone leave most of the chip idle (medium M, small N)
+
+namespace {
+
+struct SplitPlan { int tile, splits, stages_per_split; };
+
+// Tile and number of K slices (measured on LLaMA-13B shapes, M = 32 .. 512).  Slices pay where the tiles alone leave
+// the chip under-filled: up to half the compute units for a short walk over K (fewer than 64 stages), up to all of
+// them for a long one; they aim at two workgroups per compute unit, at least 12 stages per slice and at most 6 slices
+// (each slice adds a slab to write and to read again).  With slices available the 64 x 128 tile replaces the
+// 64 x 64 one, and the 128 x 128 tile the 64 x 128 one on a long K (same workgroup count after the split, fewer operand
+// bytes per MFMA).  M above 512 is left alone: there the tiles fill the chip or the slabs cost more than they save.
+SplitPlan plan_split(int M, int N, int K, int variant, int splits) {
+    SplitPlan pl{};
+    const int st_all = (K + kTiledBlockK - 1) / kTiledBlockK;
+    const int cus = compute_units();
+    const bool long_k = st_all >= 64;
+    auto count = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    pl.tile = variant ? variant : choose_tiled_tile(M, N);
+    const int unsplit_tile = pl.tile;
+    if (!variant && M > 64 && M <= 512) {
+        if (pl.tile == kTiled64x64) pl.tile = kTiled64x128;
+        if (long_k && pl.tile == kTiled64x128 && count(128, 128) <= cus) pl.tile = kTiled128x128;
+    }
+    int s = splits;
+    if (s == 0) {
+        static const int bm[] = {0, 256, 256, 128, 128, 128, 64, 64, 32, 128, 128};
+        static const int bn[] = {0, 256, 256, 256, 160, 128, 128, 64, 128, 160, 128};
+        const long long tiles = count(bm[pl.tile], bn[pl.tile]);
+        s = 1;
+        if (M <= 512 && tiles <= (long_k ? cus : cus / 2)) {
+            s = (int)((2 * (long long)cus + tiles / 2) / tiles);
+            if (s > 6) s = 6;
+            if (s > st_all / 12) s = st_all / 12;
+            if (s < 1) s = 1;
+        }
+    }
+    if (s > st_all) s = st_all;
+    if (s <= 1) pl.tile = unsplit_tile;  // the larger tiles are only worth it together with the slices
+    pl.stages_per_split = (st_all + s - 1) / s;
+    pl.splits = (st_all + pl.stages_per_split - 1) / pl.stages_per_split;  // no empty slice
+    return pl;
+}
+
+}  // namespace
+
+size_t w4a8_gemm_tiled_workspace_bytes(int M, int N, int K) {
+    if (check_gemm_shape(M, N, K)) return 0;
+    // the library's own choice never exceeds 6 slices; a forced count is checked against the buffer at the call
+    const SplitPlan pl = plan_split(M, N, K, 0, 0);
+    return pl.splits > 1 ? (size_t)pl.splits * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+}
+
+int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16, int M,
+                           int N, int K, int variant, int splits, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!xq || !s_a || !wt || !s_w || !out_fp16) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(M, N, K)) return e;
+    if (variant < 0 || variant > kTiledTileMax4 || splits < 0 || splits > 64) return W4A8_ERR_ARG;
+    if (misaligned(xq) || misaligned(wt) || misaligned(out_fp16) || misaligned(s_w) || misaligned(workspace))
+        return W4A8_ERR_ALIGN;
+    const SplitPlan pl = plan_split(M, N, K, variant, splits);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PrefillArgs a{};
+    a.xq = xq; a.s_a = s_a; a.wp = wt; a.s_w = s_w;
+    a.M = M; a.N = N; a.K = K; a.ldc = N;
+    if (pl.splits <= 1) {
+        a.out = out_fp16;
+        return launch_gemm_prefill_tiled(a, false, pl.tile, st) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+    }
+    // one launch must cover the problem (slabs are whole M x N matrices)
+    if ((long long)M * K > 0xF0000000ll || (long long)tiled_weight_bytes(N, K, 4) > 0xF0000000ll) return W4A8_ERR_SHAPE;
+    if (!workspace) return W4A8_ERR_NULL;
+    if (workspace_bytes < (size_t)pl.splits * (size_t)M * (size_t)N * sizeof(int32_t)) return W4A8_ERR_WORKSPACE;
+    a.acc_out = static_cast<int32_t *>(workspace);
+    a.splits = pl.splits;
+    a.stages_per_split = pl.stages_per_split;
+    if (launch_gemm_prefill_tiled(a, true, pl.tile, st) != hipSuccess) return W4A8_ERR_LAUNCH;
+    return launch_splitk_epilogue(a.acc_out, pl.splits, s_a, s_w, out_fp16, M, N, st) == hipSuccess ? W4A8_OK
+                                                                                                    : W4A8_ERR_LAUNCH;
+}
+
 // ---- W8A8 comparison variant: int8 weight codes in the tiled layout, the same kernels without the int4 conversion
 
 size_t w8a8_tiled_weight_bytes(int N, int K) {

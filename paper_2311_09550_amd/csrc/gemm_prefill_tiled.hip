@@ -171,8 +171,12 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
     const int bm0 = tile_m * BM;
     const int bn0 = tile_n * BN;
 
-    const int st_total = (p.K + kStageK - 1) / kStageK;
-    const int k_last = (st_total - 1) * kStageK;
+    // Split of K across workgroups (p.splits > 1, raw sums only): blockIdx.y takes the stages
+    // [st_begin, st_begin + st_total) and writes its partial sums to its own M x ldc slab of acc_out.
+    const int st_all = (p.K + kStageK - 1) / kStageK;
+    const int st_begin = p.splits > 1 ? (int)blockIdx.y * p.stages_per_split : 0;
+    const int st_total = p.splits > 1 ? min(st_all - st_begin, p.stages_per_split) : st_all;
+    const int k_last = (st_all - 1) * kStageK;
     const int nb_total = (p.N + 31) >> 5;
 
     constexpr unsigned kNowhere = 0xFFFFFFF0u;  // beyond every buffer: such a lane fetches nothing and delivers zeros
@@ -186,7 +190,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
         return r;
     };
     const v4i a_rsrc = make_rsrc(p.xq, (size_t)p.M * p.K);
-    const v4i b_rsrc = make_rsrc(p.wp, (size_t)nb_total * st_total * kBlock);
+    const v4i b_rsrc = make_rsrc(p.wp, (size_t)nb_total * st_all * kBlock);
 
     // Activation wave load L covers rows 8L .. 8L+7: lane -> row 8L + lane/8, physical slot lane%8, which receives
     // the logical chunk slot ^ fx(row).  With an even wave count fx(row) is the same for all loads of a lane.
@@ -204,12 +208,12 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
         const int L = i * kWaves + wave;
         const int nb = (bn0 >> 5) + L / kParts;
         b_off[i] = (L < B_TOTAL && nb < nb_total)
-                       ? ((unsigned)nb * (unsigned)st_total * kParts + (L % kParts)) * 1024u + lane * 16
+                       ? ((unsigned)nb * (unsigned)st_all * kParts + (L % kParts)) * 1024u + lane * 16
                        : kNowhere;
     }
     // FG: lane L < 8 NTW of every wave fetches the scales of channels n_wave + 4 L .. + 3 of the stage's group
     // (p.ldg is a multiple of 4, so a 16-byte run lies wholly inside a row of s_g or wholly outside)
-    const v4i g_rsrc = FG ? make_rsrc(p.s_w, (size_t)st_total * (size_t)p.ldg * 4) : v4i{0, 0, 0, 0};
+    const v4i g_rsrc = FG ? make_rsrc(p.s_w, (size_t)st_all * (size_t)p.ldg * 4) : v4i{0, 0, 0, 0};
     const int g_n = bn0 + wn * (32 * NTW) + 4 * lane;
     const unsigned g_off = (FG && g_n < p.ldg) ? (unsigned)g_n * 4u : kNowhere;
 
@@ -224,8 +228,9 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
     };
     const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)(lds_ptr_t)lds);
     // loads j = part, part + parts, ... of the kLoads loads of stage st (activation loads first), into ring slot `slot`
-    auto issue = [&](int st, int slot, int part, int parts) {
-        const bool last = st + 1 >= st_total;
+    auto issue = [&](int st_local, int slot, int part, int parts) {
+        const int st = st_begin + st_local;  // position along K
+        const bool last = st + 1 >= st_all;
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             if (j % parts != part) continue;
@@ -565,6 +570,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
                 const v4i s = v4i{acc[mt][t][4 * q], acc[mt][t][4 * q + 1], acc[mt][t][4 * q + 2], acc[mt][t][4 * q + 3]};
                 if (ACC_OUT) {
                     int *dst = p.acc_out + (size_t)m * p.ldc + n;
+                    if (p.splits > 1) dst += (size_t)blockIdx.y * (size_t)p.M * (size_t)p.ldc;
                     constexpr int kShift = kTrueSums ? 0 : 4;  // signed int4: exact, every sum is a multiple of 16
                     const v4i v = v4i{s.x >> kShift, s.y >> kShift, s.z >> kShift, s.w >> kShift};
                     if (vec_ok && n + 3 < p.N) {
@@ -625,7 +631,8 @@ hipError_t launch_tile(PrefillArgs p, bool acc_out, hipStream_t stream) {
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     const int total = p.tiles_m * p.tiles_n;
-    const dim3 grid(8 * ((total + 7) / 8));
+    const dim3 grid(8 * ((total + 7) / 8), p.splits > 1 ? p.splits : 1);
+    if (p.splits > 1 && (!acc_out || FG)) return hipErrorInvalidValue;  // a split of K returns raw partial sums
     if constexpr (FG) {
         if (acc_out) return hipErrorInvalidValue;  // there is no single integer sum to return
         return launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS, true, 1>(p, grid, stream);
@@ -653,6 +660,47 @@ __global__ __launch_bounds__(256) void tile_weights8_kernel(const int8_t *__rest
 
 }  // namespace
 
+// Second half of a GEMM whose K was split over workgroups: adds the slabs of raw sums and applies Eq. (6),(7).
+// Integer addition in any order gives the same sum, so the result has the bits of the unsplit kernel.
+__global__ __launch_bounds__(256) void splitk_epilogue_kernel(const int *__restrict__ part, int splits,
+                                                              const float *__restrict__ s_a, const float *__restrict__ s_w,
+                                                              unsigned short *__restrict__ out, int M, int N, int quads_per_row) {
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= (long long)M * quads_per_row) return;
+    const int m = (int)(q / quads_per_row);
+    const int n = (int)(q - (long long)m * quads_per_row) * 4;
+    const size_t slab = (size_t)M * N, at = (size_t)m * N + n;
+    const float sa = s_a[m];
+    if ((N & 3) == 0) {
+        v4i s = *(const v4i *)(part + at);
+        for (int i = 1; i < splits; ++i) {
+            const v4i t = *(const v4i *)(part + i * slab + at);
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+        const float4 sw = *(const float4 *)(s_w + n);
+        v2u o;
+        o.x = pack_f16x2((float)s.x * (sa * sw.x), (float)s.y * (sa * sw.y));
+        o.y = pack_f16x2((float)s.z * (sa * sw.z), (float)s.w * (sa * sw.w));
+        *(v2u *)(out + at) = o;
+    } else {
+        for (int j = 0; j < 4 && n + j < N; ++j) {
+            int s = 0;
+            for (int i = 0; i < splits; ++i) s += part[i * slab + at + j];
+            out[at + j] = f32_to_f16_bits((float)s * (sa * s_w[n + j]));
+        }
+    }
+}
+
+hipError_t launch_splitk_epilogue(const int *part, int splits, const float *s_a, const float *s_w, void *out, int M, int N,
+                                  hipStream_t stream) {
+    const int quads_per_row = (N + 3) / 4;
+    const long long blocks = ((long long)M * quads_per_row + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(splitk_epilogue_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, part, splits, s_a, s_w,
+                       (unsigned short *)out, M, N, quads_per_row);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream, int wbits) {
     // slices keep every byte offset inside the kernel below 2^32; slices of N start on a 32-channel block
     const long long kMaxBytes = 0xF0000000ll;
@@ -675,6 +723,7 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
             if (p.s_w) q.s_w = p.s_w + n0;
             if (p.out) q.out = (unsigned short *)p.out + (size_t)m0 * p.ldc + n0;
             if (p.acc_out) q.acc_out = p.acc_out + (size_t)m0 * p.ldc + n0;
+            if (p.splits > 1 && (q.M != p.M || q.N != p.N)) return hipErrorInvalidValue;  // slabs are whole problems
             hipError_t e;
             if (wbits == 4) {
                 switch (tile) {

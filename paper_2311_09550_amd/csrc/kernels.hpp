@@ -39,6 +39,8 @@ struct PrefillArgs {
     int *acc_out;
     int M, N, K;       // extent of this launch (a slice of the whole problem when that exceeds 32-bit byte offsets)
     int ldc;           // row stride of out / acc_out in elements (the full N)
+    int splits;            // tiled kernel, raw sums only: > 1 = K is split over this many workgroups per tile, each
+    int stages_per_split;  // taking this many 128-k stages and writing its own M x ldc slab of acc_out
     int ldg;           // fine-grained variant only: s_w then holds group scales [K / 128][ldg], ldg >= N, ldg % 4 == 0
     int tiles_m, tiles_n;
 };
@@ -91,6 +93,9 @@ size_t tiled_weight_bytes(int N, int K, int wbits = 4);
 hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream);
 hipError_t launch_tile_weights8(const int8_t *w8, uint8_t *wt, int N, int K, hipStream_t stream);
 hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream, int wbits = 4);
+// fp16 output from `splits` slabs [M][N] of raw int32 sums (what the tiled kernel writes when PrefillArgs::splits > 1)
+hipError_t launch_splitk_epilogue(const int *part, int splits, const float *s_a, const float *s_w, void *out, int M, int N,
+                                  hipStream_t stream);
 
 hipError_t launch_gemm_prefill(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
 hipError_t launch_prefill_dma_slice(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);

@@ -101,6 +101,14 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_gemm_tiled(p, p, p, p, p, 1, 16, 48, null) == -2
     assert L.w4a8_gemm_tiled_unsigned(p, p, null, p, p, null, 1, 16, 32, 0, null) == -1
     assert L.w4a8_gemm_tiled_unsigned(p, p, p, p, p, null, 1, 16, 32, 9, null) == -7
+    sk = L.w4a8_gemm_tiled_splitk
+    assert sk(p, p, p, p, null, 1, 16, 256, 0, 0, p, big, null) == -1
+    assert sk(p, p, p, p, p, 1, 16, 48, 0, 0, p, big, null) == -2
+    assert sk(p, p, p, p, p, 1, 16, 256, 11, 0, p, big, null) == -7          # unknown tile
+    assert sk(p, p, p, p, p, 1, 16, 256, 0, 65, p, big, null) == -7          # too many slices
+    assert sk(p, p, p, p, p, 1, 16, 256, 0, 2, null, big, null) == -1        # two slices need a workspace
+    assert sk(p, p, p, p, p, 1, 16, 256, 0, 2, p, ctypes.c_size_t(127), null) == -4
+    assert sk(p, p, p, p, p, 1, 16, 256, 0, 2, odd, big, null) == -3
     fg = L.w4a8_gemm_fine_grained
     assert fg(p, p, p, null, 16, p, 1, 16, 128, 0, null) == -1
     assert fg(p, p, p, p, 16, p, 1, 16, 160, 0, null) == -2      # K must be whole groups of 128
@@ -138,3 +146,12 @@ def test_host_packing_matches_oracle_and_rejects_bad_codes(L, oracle):
     with pytest.raises(w4a8.W4A8Error) as e:
         w4a8.w4a8_pack_weights_host(bad)
     assert e.value.code == -6
+
+
+def test_split_workspace_is_a_pure_function_of_shape(L):
+    f = w4a8.w4a8_gemm_tiled_workspace_bytes
+    assert f(1024, 15360, 5120) == 0                      # 240 tiles of 256 x 256: no split
+    assert f(16, 48, 40) == 0 and f(0, 16, 32) == 0       # outside the contract
+    for shape in [(32, 5120, 5120), (128, 5120, 13824), (64, 4096, 4096)]:
+        n = f(*shape)
+        assert n == f(*shape) and n % (shape[0] * shape[1] * 4) == 0 and 2 <= n // (shape[0] * shape[1] * 4) <= 8
