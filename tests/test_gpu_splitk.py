@@ -66,3 +66,23 @@ def test_workspace_too_small_is_refused(gpu, oracle):
     with pytest.raises(w4a8.W4A8Error) as e:
         w4a8.w4a8_gemm_tiled_splitk(d["xq"], d["s_a"], d["wt"], d["s_w"], splits=2, ws=ws)
     assert e.value.code == -4
+
+
+def test_bound_call_launches_what_the_plain_binding_launches(gpu, oracle):
+    """The pre-marshalled launch used by tight loops goes through the same C entry points: same bits out, and an error
+    code still raises."""
+    t = gpu
+    M, N, K = 48, 300, 2080
+    d, _, _ = _inputs(t, oracle, M, N, K, 83)
+    ref = w4a8.w4a8_gemm_tiled(d["xq"], d["s_a"], d["wt"], d["s_w"])
+    out = t.zeros((M, N), dtype=t.float16, device="cuda")
+    ws = t.empty((3 * M * N * 4,), dtype=t.uint8, device="cuda")
+    call = w4a8.bound_call("w4a8_gemm_tiled_splitk", d["xq"], d["s_a"], d["wt"], d["s_w"], out, M, N, K, 0, 3, ws, ws.numel())
+    call()
+    call()
+    t.cuda.synchronize()
+    assert_equal_bits(out.cpu().numpy().view(np.uint16), ref.cpu().numpy().view(np.uint16), "bound call")
+    bad = w4a8.bound_call("w4a8_gemm_tiled_splitk", d["xq"], d["s_a"], d["wt"], d["s_w"], out, M, N, K, 0, 3, ws, 16)
+    with pytest.raises(w4a8.W4A8Error) as e:
+        bad()
+    assert e.value.code == -4
