@@ -70,19 +70,19 @@ def parse_args():
     return ap.parse_args()
 
 
-RESIDENT_MAX_M = 16  # the layer stack uses the weight-streaming kernels over the row-major array up to here; above it the tiled array,
-                     # with K cut into slices where the tiles alone would not fill the chip (2x faster at M = 32 .. 64)
+# One copy of the weights, in the tiled layout, serves every M: the library's tiled entry runs the weight-streaming
+# kernels up to M = 16 and the large-M kernel above, with K cut into slices where its tiles alone would not fill the chip.
 
 
 def prepare_weights(torch, w4a8, synth, model="13b"):
-    """Offline weight preparation, on the GPU: quantise, pack (row-major array for small M), reorder (tiled array for
-    large M).  Returns name -> (wp, wt, s_w)."""
+    """Offline weight preparation, on the GPU: quantise and pack, then reorder into the tiled array (the only copy that
+    is kept).  Returns name -> (wt, s_w)."""
     out = {}
     for name, (N, K) in synth.LLAMA_SHAPES[model].items():
         w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).to("cuda")
         wp, s_w = w4a8.w4a8_quantize_weights(w)
-        out[name] = (wp, w4a8.w4a8_tile_weights(wp), s_w)
-        del w
+        out[name] = (w4a8.w4a8_tile_weights(wp), s_w)
+        del w, wp
     return out
 
 
@@ -93,9 +93,8 @@ class LayerStack:
         self.torch, self.w4a8, self.M = torch, w4a8, M
         self.shapes = synth.LLAMA_SHAPES[model]
         dev = "cuda"
-        self.tiled = M > RESIDENT_MAX_M
-        self.wp = {k: (v[1] if self.tiled else v[0]) for k, v in weights.items()}
-        self.s_w = {k: v[2] for k, v in weights.items()}
+        self.wp = {k: v[0] for k, v in weights.items()}
+        self.s_w = {k: v[1] for k, v in weights.items()}
         H = self.shapes["qkv"][1]
         I = self.shapes["down"][1]
         # fp16 inputs of the three linears that are fed from outside the stack (attention itself is not modelled)
@@ -108,7 +107,7 @@ class LayerStack:
         self.out = {name: e(M, N, dt=torch.float16) for name, (N, K) in self.shapes.items()}
         # scratch for the GEMMs whose K the library cuts into slices (medium M; empty where it does not)
         self.ws = {name: e(max(16, w4a8.w4a8_gemm_tiled_workspace_bytes(M, N, K)), dt=torch.uint8)
-                   for name, (N, K) in self.shapes.items()} if self.tiled else {}
+                   for name, (N, K) in self.shapes.items()}
         self.gemm_events = []   # (name, start, stop) around GEMM launches, filled when record=True
         # the eight launches with their arguments marshalled once: the timed loop then spends its host time in the
         # library, not in Python
@@ -120,11 +119,8 @@ class LayerStack:
         self.gemm = {}
         for name, (N, K) in self.shapes.items():
             xq, sa = (self.xq_i, self.sa_i) if name == "down" else (self.xq_h, self.sa_h)
-            if self.tiled:
-                self.gemm[name] = b("w4a8_gemm_tiled_splitk", xq, sa, self.wp[name], self.s_w[name], self.out[name], M, N, K,
-                                    0, 0, self.ws[name], self.ws[name].numel())
-            else:
-                self.gemm[name] = b("w4a8_gemm", xq, sa, self.wp[name], self.s_w[name], self.out[name], M, N, K, None, 0)
+            self.gemm[name] = b("w4a8_gemm_tiled_splitk", xq, sa, self.wp[name], self.s_w[name], self.out[name], M, N, K,
+                                0, 0, self.ws[name], self.ws[name].numel())
 
     def _gemm(self, name, record=False):
         if record:
@@ -181,7 +177,7 @@ def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 16, 64, 128, 1024, 2048
         rows.append({"M": M, "layer_us": round(times["layer"], 2), "gemm_us": round(times["gemms"], 2),
                      "gemm_share": round(times["gemms"] / times["layer"], 4),
                      "TOPS": round(stack.ops_per_step() / times["layer"] / 1e6, 2),
-                     "weights": "tiled" if stack.tiled else "row-major"})
+                     "weights": "tiled"})
         del stack
         torch.cuda.empty_cache()
     return rows
@@ -196,17 +192,17 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
     for name, (N, K) in synth.LLAMA_SHAPES[model].items():
         w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).cuda()
         wp, s_w = w4a8.w4a8_quantize_weights(w)
-        del w
+        wt = w4a8.w4a8_tile_weights(wp)   # the same array the large-M kernel reads
+        del w, wp
         wbytes = N * K // 2
         copies = max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wbytes) + 1)
-        wps = [wp] + [wp.clone() for _ in range(copies - 1)]
+        wps = [wt] + [wt.clone() for _ in range(copies - 1)]
         for M in Ms:
             x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
             xq, s_a = w4a8.w4a8_quantize_act(x)
             out = torch.empty((M, N), dtype=torch.float16, device="cuda")
-            ws = w4a8.workspace(M, N, K)
             for i in range(min(copies, 4)):
-                w4a8.w4a8_gemm(xq, s_a, wps[i], s_w, out=out, ws=ws)
+                w4a8.w4a8_gemm_tiled(xq, s_a, wps[i], s_w, out=out)
             torch.cuda.synchronize()
             # One graph holds a back-to-back batch of launches (a decode loop is replayed from a graph as well; launching
             # each 5-15 us kernel from Python would time the interpreter, not the GPU).
@@ -214,7 +210,7 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph):
                 for i in range(n):
-                    w4a8.w4a8_gemm(xq, s_a, wps[i % copies], s_w, out=out, ws=ws)
+                    w4a8.w4a8_gemm_tiled(xq, s_a, wps[i % copies], s_w, out=out)
             graph.replay()
             torch.cuda.synchronize()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -229,7 +225,7 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
             rows.append({"linear": name, "M": M, "N": N, "K": K, "us": round(us, 3),
                          "GBps": round(by / us / 1e3, 1), "hbm_frac": round(by / us / 1e3 / HBM_PEAK_GBS, 4),
                          "weight_copies": copies})
-        del wps, wp
+        del wps, wt
         torch.cuda.empty_cache()
     return rows
 

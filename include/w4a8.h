@@ -128,6 +128,9 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
 #define W4A8_TILING_DECODE_STREAM 2   /* general weight-streaming kernel, M <= 64                         */
 #define W4A8_TILING_PREFILL 3         /* LDS-staged output tiles on 32x32x32 int8 MFMA, for large M       */
 #define W4A8_TILING_PREFILL_TILED 4   /* the same over the tiled weight layout (any M; meant for large M)  */
+#define W4A8_TILING_DECODE_RESIDENT_TILED 5 /* tilings 1 and 2 reading the TILED weight array (`wp` = wt);        */
+#define W4A8_TILING_DECODE_STREAM_TILED 6   /* same limits and variants as 1 and 2                                 */
+#define W4A8_TILING_AUTO_TILED 7      /* library's choice over the TILED array: 5 or 6 up to M = 16, 4 above   */
 int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w,
                     void *out_fp16, int32_t *acc_i32, int M, int N, int K,
                     int tiling, int variant,
@@ -143,8 +146,11 @@ int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const
  *   as nibbles k0 k4 k1 k5 k2 k6 k3 k7 from the lowest to the highest.  Channels >= N and k >= K hold zero codes.
  * w4a8_tiled_weight_bytes: size of wt in bytes (0 for a shape outside the contract).
  * w4a8_tile_weights: wp [N][K/2] (device) in -> wt (device, 16-byte aligned, w4a8_tiled_weight_bytes(N, K)) out.
- * w4a8_gemm_tiled: w4a8_gemm over wt instead of wp (all other arguments as there).  Every M is accepted; the
- *   kernel behind it is the large-M one, so for M <= 64 w4a8_gemm on the row-major array is the faster call.
+ * w4a8_gemm_tiled: w4a8_gemm over wt instead of wp (all other arguments as there).  Every M is accepted, and one
+ *   copy of the weights, the tiled one, serves them all: up to M = 16 (token generation) the weight-streaming kernels
+ *   read wt directly, above that the large-M kernel runs (through w4a8_gemm_tiled_splitk it also fills the chip at a
+ *   few dozen to a few hundred rows).  w4a8_gemm serves every M from the row-major array, at up to twice the tiled
+ *   time for M between 17 and 512.
  */
 size_t w4a8_tiled_weight_bytes(int N, int K);
 int w4a8_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, void *stream);

@@ -15,6 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw4a8.so")
 
 TILING_AUTO, TILING_DECODE_RESIDENT, TILING_DECODE_STREAM, TILING_PREFILL, TILING_PREFILL_TILED = 0, 1, 2, 3, 4
+TILING_DECODE_RESIDENT_TILED, TILING_DECODE_STREAM_TILED, TILING_AUTO_TILED = 5, 6, 7
+_TILED_TILINGS = (TILING_PREFILL_TILED, TILING_DECODE_RESIDENT_TILED, TILING_DECODE_STREAM_TILED, TILING_AUTO_TILED)
 
 _lib = None
 
@@ -191,11 +193,11 @@ def w4a8_gemm_acc_i32(xq, wp, acc=None, ws=None):
 
 
 def w4a8_gemm_tuned(xq, s_a, wp, s_w, tiling: int, variant: int = 0, want_acc: bool = False, out=None, ws=None, N=None):
-    """Forced tiling / variant; returns fp16 [M][N], or int32 [M][N] when want_acc.  With TILING_PREFILL_TILED, wp is
-    the flat tiled array of w4a8_tile_weights and N must be given."""
+    """Forced tiling / variant; returns fp16 [M][N], or int32 [M][N] when want_acc.  With a tiling over the tiled
+    layout (TILING_*_TILED), wp is the flat tiled array of w4a8_tile_weights and N must be given."""
     torch = _torch()
     M, K = xq.shape
-    if tiling == TILING_PREFILL_TILED:
+    if tiling in _TILED_TILINGS:
         if N is None or wp.numel() != w4a8_tiled_weight_bytes(N, K):
             raise ValueError("tiled weights: N missing or array size mismatch")
     else:

@@ -42,10 +42,11 @@ struct Plan {
 // Shape of the persistent decode kernel for (M, K): 8 waves while a wave's k steps stay few (fewer
 // registers per wave, two workgroups per compute unit), else 16 waves.  Returns false when the
 // activations of a wave would not fit in registers.
-bool resident_shape(int M, int N, int K, int waves, int grid, DecodeShape *out) {
+bool resident_shape(int M, int N, int K, int waves, int grid, DecodeShape *out, bool tiled = false) {
     const int ks_total = (K + 127) / 128;
     DecodeShape s{};
     s.resident = true;
+    s.tiled = tiled;
     if (waves == 0) waves = (M <= 16 && ks_total <= 40) ? 8 : 16;
     s.waves = waves;
     s.x_steps = (ks_total + waves - 1) / waves;
@@ -164,6 +165,17 @@ int choose_tiled_tile8(int M, int N) {
 // (matrix-core bound).  `variant` refines a forced tiling (see w4a8.h); 0 lets the library choose.
 int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
     pl->tiling = tiling;
+    if (tiling == W4A8_TILING_AUTO_TILED) {
+        // one weight array for every M: the weight-streaming kernels up to M = 16, the large-M kernel above
+        if (M > 16)
+            pl->tiling = W4A8_TILING_PREFILL_TILED;
+        else
+            pl->tiling = resident_shape(M, N, K, 0, 0, &pl->decode, true) ? W4A8_TILING_DECODE_RESIDENT_TILED
+                                                                           : W4A8_TILING_DECODE_STREAM_TILED;
+    }
+    const bool decode_tiled = pl->tiling == W4A8_TILING_DECODE_RESIDENT_TILED || pl->tiling == W4A8_TILING_DECODE_STREAM_TILED;
+    if (pl->tiling == W4A8_TILING_DECODE_RESIDENT_TILED) pl->tiling = W4A8_TILING_DECODE_RESIDENT;
+    if (pl->tiling == W4A8_TILING_DECODE_STREAM_TILED) pl->tiling = W4A8_TILING_DECODE_STREAM;
     if (tiling == W4A8_TILING_AUTO) {
         if (M > kDecodeMaxM)
             pl->tiling = W4A8_TILING_PREFILL;
@@ -172,12 +184,13 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
     }
     if (pl->tiling == W4A8_TILING_DECODE_RESIDENT) {
         if (M > kDecodeMaxM) return W4A8_ERR_ARG;
-        if (!resident_shape(M, N, K, variant / 100000, variant % 100000, &pl->decode)) return W4A8_ERR_ARG;
+        if (!resident_shape(M, N, K, variant / 100000, variant % 100000, &pl->decode, decode_tiled)) return W4A8_ERR_ARG;
     } else if (pl->tiling == W4A8_TILING_DECODE_STREAM) {
         if (M > kDecodeMaxM) return W4A8_ERR_ARG;
         const int mt = (M + 15) / 16;
         DecodeShape s{};
         s.resident = false;
+        s.tiled = decode_tiled;
         s.row_tiles = variant ? variant / 100 : (M <= 8 ? 1 : 2);
         s.waves = variant ? variant % 100 : ((mt >= 4 && s.row_tiles == 2) ? 4 : 8);
         if ((s.row_tiles != 1 && s.row_tiles != 2) || (s.waves != 4 && s.waves != 8)) return W4A8_ERR_ARG;
@@ -200,7 +213,7 @@ int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float 
     if (!xq || !wp) return W4A8_ERR_NULL;
     if (!want_acc && (!s_a || !s_w)) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, N, K)) return e;
-    if (tiling < W4A8_TILING_AUTO || tiling > W4A8_TILING_PREFILL_TILED || variant < 0) return W4A8_ERR_ARG;
+    if (tiling < W4A8_TILING_AUTO || tiling > W4A8_TILING_AUTO_TILED || variant < 0) return W4A8_ERR_ARG;
     if (misaligned(xq) || misaligned(wp) || misaligned(out_fp16) || misaligned(acc_i32) || (s_w && misaligned(s_w)))
         return W4A8_ERR_ALIGN;
 
@@ -300,7 +313,7 @@ int w4a8_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, void *stream
 int w4a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16, int M, int N,
                     int K, void *stream) {
     if (!out_fp16) return W4A8_ERR_NULL;
-    return run_gemm(xq, s_a, wt, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_PREFILL_TILED, 0, stream);
+    return run_gemm(xq, s_a, wt, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_AUTO_TILED, 0, stream);
 }
 
 // ---- K split over workgroups for shapes whose tiles alone leave most of the chip idle (medium M, small N)
@@ -363,6 +376,8 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
     if (variant < 0 || variant > kTiledTileMax4 || splits < 0 || splits > 64) return W4A8_ERR_ARG;
     if (misaligned(xq) || misaligned(wt) || misaligned(out_fp16) || misaligned(s_w) || misaligned(workspace))
         return W4A8_ERR_ALIGN;
+    if (M <= 16 && variant == 0 && splits == 0)  // token generation: the weight-streaming kernels over the same array
+        return run_gemm(xq, s_a, wt, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_AUTO_TILED, 0, stream);
     const SplitPlan pl = plan_split(M, N, K, variant, splits);
     hipStream_t st = static_cast<hipStream_t>(stream);
     PrefillArgs a{};

@@ -47,6 +47,17 @@ __device__ __forceinline__ v4i w_operand(unsigned w0, unsigned w1) {
     return r;
 }
 
+// Two dwords of the TILED weight layout (16 codes; nibbles of a dword hold k0 k4 k1 k5 k2 k6 k3 k7 from the lowest
+// up) -> one MFMA operand: int8 values 16 * w in the natural k order, so the activations need no reordering.
+__device__ __forceinline__ v4i w_operand_tiled(unsigned w0, unsigned w1) {
+    v4i r;
+    r.x = (int)((w0 << 4) & 0xF0F0F0F0u);
+    r.y = (int)(w0 & 0xF0F0F0F0u);
+    r.z = (int)((w1 << 4) & 0xF0F0F0F0u);
+    r.w = (int)(w1 & 0xF0F0F0F0u);
+    return r;
+}
+
 // 16 consecutive int8 activations (k = 0..15) reordered to the k order of
 // w_operand: bytes {0,2,4,6}, {1,3,5,7} of the first eight, then of the second eight.
 __device__ __forceinline__ v4i x_operand(v4u x) {

@@ -103,7 +103,13 @@ __device__ __forceinline__ void lds_barrier() {
     lds_acquire();
 }
 
-template <int MT, int XS, int P, int WAVES, bool ACC_OUT>
+//
+// TILED: p.wp is the tiled weight array of the large-M kernel (2 KB blocks of 32 channels x 128 k, see
+// gemm_prefill_tiled.hip) instead of the row-major one, so that one copy of the weights serves every M.  A lane's
+// 16 bytes are the chunk (c = its K group, r = its channel within the block); a wave load then covers four runs of
+// 256 contiguous bytes.  The nibble order inside the tiled dwords yields the natural k order, so the activations are
+// used as they are.
+template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(DecodeArgs p) {
     __shared__ int tile[2 * kEpoch][MT][256];  // sixteen-fold sums of one chunk each
     __shared__ int arrived[2 * kEpoch];
@@ -137,8 +143,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     // That is how a dead K group (K % 128 != 0), a wave without a step, a row outside the workgroup's range and a
     // finished walk are handled, with neither a branch nor a select nor a wasted access.
     constexpr unsigned kNowhere = 0xFFFFFFF0u;
-    const __amdgpu_buffer_rsrc_t w_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, (unsigned)((size_t)p.N * (p.K >> 1)), 0x00020000);
+    const unsigned w_bytes = TILED ? (unsigned)((size_t)((p.N + 31) >> 5) * ks_total * kTiledBlockBytes)
+                                   : (unsigned)((size_t)p.N * (p.K >> 1));
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, w_bytes, 0x00020000);
     // k steps of this wave.  Where possible a wave takes two adjacent steps (128 contiguous bytes of every row,
     // i.e. whole 128-byte lines) -- steps i = 0 .. 2*(XS/2)-1 -- and, if XS is odd, one single step at the end.
     auto k_step = [&](int i) {
@@ -151,14 +158,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     for (int i = 0; i < XS; ++i) {
         const int ks = k_step(i);
         live[i] = ks < ks_total && (ks * 128 + 32 * g) < p.K;
-        w_off[i] = live[i] ? (unsigned)(ks * 64 + 16 * g) : kNowhere;
+        w_off[i] = !live[i] ? kNowhere : TILED ? (unsigned)(ks * kTiledBlockBytes + 512 * g) : (unsigned)(ks * 64 + 16 * g);
     }
 
     const unsigned w_stride = (unsigned)(p.K >> 1);
     // byte offset of this lane's row in chunk c of the workgroup's range, or nowhere
     auto w_row = [&](int c) {
         const int n = row0 + 16 * c + r;
-        return (c < chunks && n < row_end) ? (unsigned)n * w_stride : kNowhere;
+        if (!(c < chunks && n < row_end)) return kNowhere;
+        return TILED ? (unsigned)(n >> 5) * (unsigned)(ks_total * kTiledBlockBytes) + (unsigned)(n & 31) * 16u
+                     : (unsigned)n * w_stride;
     };
     auto w_load = [&](unsigned row, unsigned off) {
         const unsigned o = (row >= kNowhere || off >= kNowhere) ? kNowhere : row + off;
@@ -183,8 +192,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
             // a dead K group reads the start of the row: it meets zero weights
             const int m = min(16 * mt + r, p.M - 1);
             const v4u *px = (const v4u *)(p.xq + (size_t)m * p.K + (live[i] ? k_step(i) * 128 + 32 * g : 0));
-            xop[i][mt][0] = x_operand(px[0]);
-            xop[i][mt][1] = x_operand(px[1]);
+            xop[i][mt][0] = TILED ? v4i{(int)px[0].x, (int)px[0].y, (int)px[0].z, (int)px[0].w} : x_operand(px[0]);
+            xop[i][mt][1] = TILED ? v4i{(int)px[1].x, (int)px[1].y, (int)px[1].z, (int)px[1].w} : x_operand(px[1]);
         }
     }
     if (!ACC_OUT) {
@@ -208,8 +217,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
                 for (int i = 0; i < XS; ++i) {
                     const v4u w = wreg[q][i];
                     wreg[q][i] = w_load(next, w_off[i]);
-                    const v4i w0 = w_operand(w.x, w.y);
-                    const v4i w1 = w_operand(w.z, w.w);
+                    const v4i w0 = TILED ? w_operand_tiled(w.x, w.y) : w_operand(w.x, w.y);
+                    const v4i w1 = TILED ? w_operand_tiled(w.z, w.w) : w_operand(w.z, w.w);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
                         acc[mt][0] = mfma_i8_16x16x64(w0, xop[i][mt][0], acc[mt][0]);
@@ -265,7 +274,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
 
 // ---------------------------------------------------------------------------------------------
 // General kernel: one workgroup per 16*T output channels, U k steps of loads in flight per wave.
-template <int MT, int T, int WAVES, int U, bool ACC_OUT>
+template <int MT, int T, int WAVES, int U, bool ACC_OUT, bool TILED>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_stream_kernel(DecodeArgs p) {
     constexpr int kThreads = WAVES * 64;
     __shared__ v4i red[WAVES * MT * T * 64];
@@ -283,7 +292,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_stream_kernel(DecodeAr
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         const int n = min(n0 + 16 * t + r, p.N - 1);
-        wrow[t] = p.wp + (size_t)n * w_stride + 16 * g;
+        wrow[t] = TILED ? p.wp + ((size_t)(n >> 5) * ks_total) * kTiledBlockBytes + (n & 31) * 16 + 512 * g
+                        : p.wp + (size_t)n * w_stride + 16 * g;
     }
     const int8_t *xrow[MT];
 #pragma unroll
@@ -306,7 +316,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_stream_kernel(DecodeAr
             const size_t ksafe = live ? (size_t)ks : 0;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                const v4u v = *(const v4u *)(wrow[t] + ksafe * 64 - (live ? 0 : 16 * g));
+                const v4u v = TILED ? *(const v4u *)(wrow[t] + ksafe * kTiledBlockBytes - (live ? 0 : 512 * g))
+                                    : *(const v4u *)(wrow[t] + ksafe * 64 - (live ? 0 : 16 * g));
                 wreg[u][t] = live ? v : v4u{0, 0, 0, 0};
             }
 #pragma unroll
@@ -322,10 +333,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_stream_kernel(DecodeAr
             for (int h = 0; h < 2; ++h) {
                 v4i xop[MT];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) xop[mt] = x_operand(xreg[u][mt][h]);
+                for (int mt = 0; mt < MT; ++mt) {
+                    const v4u x = xreg[u][mt][h];
+                    xop[mt] = TILED ? v4i{(int)x.x, (int)x.y, (int)x.z, (int)x.w} : x_operand(x);
+                }
 #pragma unroll
                 for (int t = 0; t < T; ++t) {
-                    const v4i wop = h == 0 ? w_operand(wreg[u][t].x, wreg[u][t].y) : w_operand(wreg[u][t].z, wreg[u][t].w);
+                    const v4u wf = wreg[u][t];
+                    const v4i wop = TILED ? (h == 0 ? w_operand_tiled(wf.x, wf.y) : w_operand_tiled(wf.z, wf.w))
+                                          : (h == 0 ? w_operand(wf.x, wf.y) : w_operand(wf.z, wf.w));
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) acc[mt][t] = mfma_i8_16x16x64(wop, xop[mt], acc[mt][t]);
                 }
@@ -356,30 +372,47 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_stream_kernel(DecodeAr
 
 // ---------------------------------------------------------------------------------------------
 
-template <int MT, int XS, int P, int WAVES>
-static hipError_t launch_resident(const DecodeArgs &p, bool acc_out, int grid, hipStream_t stream) {
-    if (acc_out)
-        hipLaunchKernelGGL((gemm_decode_resident_kernel<MT, XS, P, WAVES, true>), dim3(grid), dim3(WAVES * 64), 0, stream, p);
+template <int MT, int XS, int P, int WAVES, bool ACC_OUT>
+static hipError_t launch_resident_as(const DecodeArgs &p, bool tiled, int grid, hipStream_t stream) {
+    if (tiled)
+        hipLaunchKernelGGL((gemm_decode_resident_kernel<MT, XS, P, WAVES, ACC_OUT, true>), dim3(grid), dim3(WAVES * 64), 0,
+                           stream, p);
     else
-        hipLaunchKernelGGL((gemm_decode_resident_kernel<MT, XS, P, WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, stream, p);
+        hipLaunchKernelGGL((gemm_decode_resident_kernel<MT, XS, P, WAVES, ACC_OUT, false>), dim3(grid), dim3(WAVES * 64), 0,
+                           stream, p);
+    return hipGetLastError();
+}
+
+template <int MT, int XS, int P, int WAVES>
+static hipError_t launch_resident(const DecodeArgs &p, bool acc_out, bool tiled, int grid, hipStream_t stream) {
+    return acc_out ? launch_resident_as<MT, XS, P, WAVES, true>(p, tiled, grid, stream)
+                   : launch_resident_as<MT, XS, P, WAVES, false>(p, tiled, grid, stream);
+}
+
+template <int MT, int T, int WAVES, int U, bool ACC_OUT>
+static hipError_t launch_stream_as(const DecodeArgs &p, bool tiled, hipStream_t stream) {
+    dim3 grid((p.N + 16 * T - 1) / (16 * T));
+    if (tiled)
+        hipLaunchKernelGGL((gemm_decode_stream_kernel<MT, T, WAVES, U, ACC_OUT, true>), grid, dim3(WAVES * 64), 0, stream, p);
+    else
+        hipLaunchKernelGGL((gemm_decode_stream_kernel<MT, T, WAVES, U, ACC_OUT, false>), grid, dim3(WAVES * 64), 0, stream, p);
     return hipGetLastError();
 }
 
 template <int MT, int T, int WAVES, int U>
-static hipError_t launch_stream(const DecodeArgs &p, bool acc_out, hipStream_t stream) {
-    dim3 grid((p.N + 16 * T - 1) / (16 * T));
-    if (acc_out)
-        hipLaunchKernelGGL((gemm_decode_stream_kernel<MT, T, WAVES, U, true>), grid, dim3(WAVES * 64), 0, stream, p);
-    else
-        hipLaunchKernelGGL((gemm_decode_stream_kernel<MT, T, WAVES, U, false>), grid, dim3(WAVES * 64), 0, stream, p);
-    return hipGetLastError();
+static hipError_t launch_stream(const DecodeArgs &p, bool acc_out, bool tiled, hipStream_t stream) {
+    return acc_out ? launch_stream_as<MT, T, WAVES, U, true>(p, tiled, stream)
+                   : launch_stream_as<MT, T, WAVES, U, false>(p, tiled, stream);
 }
 
 bool decode_resident_supported(int M, int N, int K, const DecodeShape &s) {
     const int mt = (M + 15) / 16;
     const int steps = (((K + 127) / 128) + s.waves - 1) / s.waves;
     if (steps != s.x_steps || (s.waves != 8 && s.waves != 16)) return false;
-    if ((unsigned long long)N * (unsigned long long)(K >> 1) > 0xFFFF0000ull) return false;  // 32-bit buffer offsets
+    // 32-bit buffer offsets (the tiled array rounds N up to 32 and K up to 128)
+    const unsigned long long w_bytes = s.tiled ? (unsigned long long)tiled_weight_bytes(N, K)
+                                               : (unsigned long long)N * (unsigned long long)(K >> 1);
+    if (w_bytes > 0xFFFF0000ull) return false;
     if (s.rows_per_wg < 4 || (s.rows_per_wg & 3) || s.rows_per_wg > kResidentMaxRows) return false;
     if (s.waves == 8) return mt == 1 && s.x_steps >= 1 && s.x_steps <= 5;
     if (mt == 1) return s.x_steps >= 1 && s.x_steps <= 8;
@@ -392,7 +425,7 @@ hipError_t launch_gemm_decode(const DecodeArgs &p, bool acc_out, const DecodeSha
     if (s.resident) {
         if (!decode_resident_supported(p.M, p.N, p.K, s)) return hipErrorInvalidConfiguration;
 #define W4A8_RES(MT_, XS_, P_, WV_) \
-    if (mt == MT_ && s.x_steps == XS_ && s.waves == WV_) return launch_resident<MT_, XS_, P_, WV_>(p, acc_out, (p.N + s.rows_per_wg - 1) / s.rows_per_wg, stream);
+    if (mt == MT_ && s.x_steps == XS_ && s.waves == WV_) return launch_resident<MT_, XS_, P_, WV_>(p, acc_out, s.tiled, (p.N + s.rows_per_wg - 1) / s.rows_per_wg, stream);
         W4A8_RES(1, 1, 4, 8) W4A8_RES(1, 2, 4, 8) W4A8_RES(1, 3, 2, 8) W4A8_RES(1, 4, 2, 8) W4A8_RES(1, 5, 1, 8)
         W4A8_RES(1, 1, 4, 16) W4A8_RES(1, 2, 4, 16) W4A8_RES(1, 3, 3, 16) W4A8_RES(1, 4, 2, 16)
         W4A8_RES(1, 5, 1, 16) W4A8_RES(1, 6, 1, 16) W4A8_RES(1, 7, 1, 16) W4A8_RES(1, 8, 1, 16)
@@ -401,7 +434,7 @@ hipError_t launch_gemm_decode(const DecodeArgs &p, bool acc_out, const DecodeSha
         return hipErrorInvalidConfiguration;
     }
 #define W4A8_STR(MT_, T_, WV_, U_) \
-    if (mt == MT_ && s.row_tiles == T_ && s.waves == WV_) return launch_stream<MT_, T_, WV_, U_>(p, acc_out, stream);
+    if (mt == MT_ && s.row_tiles == T_ && s.waves == WV_) return launch_stream<MT_, T_, WV_, U_>(p, acc_out, s.tiled, stream);
     W4A8_STR(1, 1, 8, 4) W4A8_STR(1, 2, 8, 4) W4A8_STR(1, 1, 4, 4) W4A8_STR(1, 2, 4, 4)
     W4A8_STR(2, 1, 8, 4) W4A8_STR(2, 2, 8, 2) W4A8_STR(2, 1, 4, 4) W4A8_STR(2, 2, 4, 2)
     W4A8_STR(3, 1, 8, 2) W4A8_STR(3, 2, 8, 2) W4A8_STR(3, 1, 4, 2) W4A8_STR(3, 2, 4, 2)

@@ -47,16 +47,6 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// Two dwords of the tiled layout (16 codes) -> one MFMA operand: int8 values 16 * w in the natural k order.
-__device__ __forceinline__ v4i w_operand_tiled(unsigned w0, unsigned w1) {
-    v4i r;
-    r.x = (int)((w0 << 4) & 0xF0F0F0F0u);
-    r.y = (int)(w0 & 0xF0F0F0F0u);
-    r.z = (int)((w1 << 4) & 0xF0F0F0F0u);
-    r.w = (int)(w1 & 0xF0F0F0F0u);
-    return r;
-}
-
 // The same for the unsigned storage: each nibble holds u = w + 8 and the subtraction happens here, on four bytes at
 // a time: (u + 0x78) ^ 0x80 is u - 8 as a two's-complement byte, and u + 0x78 <= 0x87 never carries into the next byte.
 __device__ __forceinline__ v4i u_operand_tiled(unsigned w0, unsigned w1) {

@@ -25,6 +25,7 @@ struct DecodeShape {
     int x_steps;    // resident: k steps per wave = ceil(ceil(K/128) / waves)
     int rows_per_wg;  // resident: output channels per persistent workgroup, a multiple of 4
     int row_tiles;  // streaming: 16-row weight tiles per wave, 1 or 2
+    bool tiled;     // DecodeArgs::wp is the tiled weight array (2 KB blocks) instead of the row-major one
 };
 
 bool decode_resident_supported(int M, int N, int K, const DecodeShape &s);

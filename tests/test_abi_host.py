@@ -70,7 +70,7 @@ def test_argument_validation_happens_before_any_launch(L):
     assert g(odd, p, p, p, p, 1, 16, 32, p, big, null) == -3
     assert g(p, p, odd, p, p, 1, 16, 32, p, big, null) == -3
     t = L.w4a8_gemm_tuned
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 7, 0, p, big, null) == -7       # unknown tiling
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 8, 0, p, big, null) == -7       # unknown tiling
     assert t(p, p, p, p, p, null, 1, 16, 1024, 2, 303, p, big, null) == -7     # stream: 3 row tiles / 3 waves do not exist
     assert t(p, p, p, p, p, null, 1, 16, 1024, 3, 9, p, big, null) == -7       # prefill: unknown tile id
     assert t(p, p, p, p, p, null, 65, 16, 1024, 2, 0, p, big, null) == -7      # decode tilings are for M <= 64
