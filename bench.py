@@ -13,8 +13,10 @@ The same run also reports the decode side of the metric (M = 1, 4, 16 on the sam
 four shapes, weights rotated through more than the last-level cache so every byte
 comes from HBM), a roofline object for the dominant kernel, the layer stack at
 M = 1 .. 2048 replayed from a HIP graph (layer time and GEMM share), the per-GEMM
-ratio of the W8A8 comparison variant to W4A8, and the CPU oracle's throughput on
-a bounded sample of the workload.
+ratios of the W8A8 comparison variant and of the two ablation variants (unsigned
+nibble storage, fine-grained group scales) to W4A8, and the CPU oracle's
+throughput on a bounded sample of the workload.  Every GEMM of the run reads the
+one tiled copy of the weights, whatever its M.
 
 All inputs are seeded synthetic tensors generated on the host and resident in
 HBM before the timed region starts.
@@ -411,7 +413,7 @@ def main():
         mean_bytes = sum(gemm_bytes(r["M"], r["N"], r["K"]) for r in rows) / len(rows)
         result["roofline_decode"] = {"bound": "hbm", "achieved": round(mean_bytes / mean_us / 1e3, 1), "peak": HBM_PEAK_GBS,
                                      "unit": "GB/s", "frac": round(mean_bytes / mean_us / 1e3 / HBM_PEAK_GBS, 4),
-                                     "traffic": None, "kernel": "gemm_decode_kernel",
+                                     "traffic": None, "kernel": "gemm_decode_resident_kernel",
                                      "worst": worst, "best": best}
     if not args.no_w8a8:
         result["w4a8_vs_w8a8"] = time_w4_vs_w8(torch, w4a8, synth)
