@@ -67,6 +67,13 @@ const char *w4a8_strerror(int err);
 int w4a8_quantize_act(const void *x_fp16, int8_t *xq, float *s_a, int M, int K, void *stream);
 
 /*
+ * The same for an input whose rows are ldx elements apart (ldx >= K, ldx % 8 == 0): a block of K consecutive
+ * columns of a wider fp16 matrix, e.g. one projection's slice of a fused QKV output, quantised in place of a copy.
+ * xq and s_a are dense as above.
+ */
+int w4a8_quantize_act_strided(const void *x_fp16, long long ldx, int8_t *xq, float *s_a, int M, int K, void *stream);
+
+/*
  * Bytes of scratch memory w4a8_gemm / w4a8_gemm_acc_i32 / w4a8_gemm_tuned need
  * for this shape: a pure function of the shape.  The present tilings combine
  * their partial sums in LDS and need none, so this returns 0 and the

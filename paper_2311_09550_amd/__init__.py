@@ -41,6 +41,8 @@ def lib():
         L.w4a8_strerror.restype = ctypes.c_char_p
         L.w4a8_strerror.argtypes = [i]
         L.w4a8_quantize_act.argtypes = [vp, vp, vp, i, i, vp]
+        L.w4a8_quantize_act_strided.restype = i
+        L.w4a8_quantize_act_strided.argtypes = [vp, ctypes.c_longlong, vp, vp, i, i, vp]
         L.w4a8_gemm_workspace_bytes.restype = sz
         L.w4a8_gemm_workspace_bytes.argtypes = [i, i, i]
         L.w4a8_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, sz, vp]
@@ -156,6 +158,19 @@ def w4a8_quantize_act(x, xq=None, s_a=None):
     s_a = torch.empty((M,), dtype=torch.float32, device=x.device) if s_a is None else s_a
     _check(lib().w4a8_quantize_act(_dev(x, torch.float16, "x"), _dev(xq, torch.int8, "xq"),
                                    _dev(s_a, torch.float32, "s_a"), M, K, _stream()))
+    return xq, s_a
+
+
+def w4a8_quantize_act_strided(x, xq=None, s_a=None):
+    """fp16 [M][K] view whose rows are x.stride(0) elements apart (a column block of a wider matrix) -> (int8, fp32)."""
+    torch = _torch()
+    M, K = x.shape
+    if not (x.is_cuda and x.dtype == torch.float16 and x.stride(1) == 1):
+        raise TypeError("x: expected a device fp16 view with unit column stride")
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device) if xq is None else xq
+    s_a = torch.empty((M,), dtype=torch.float32, device=x.device) if s_a is None else s_a
+    _check(lib().w4a8_quantize_act_strided(ctypes.c_void_p(x.data_ptr()), x.stride(0), _dev(xq, torch.int8, "xq"),
+                                           _dev(s_a, torch.float32, "s_a"), M, K, _stream()))
     return xq, s_a
 
 

@@ -268,8 +268,17 @@ int w4a8_quantize_act(const void *x_fp16, int8_t *xq, float *s_a, int M, int K, 
     if (!x_fp16 || !xq || !s_a) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, 1, K)) return e;
     if (misaligned(x_fp16) || misaligned(xq)) return W4A8_ERR_ALIGN;
-    return launch_quantize_act(x_fp16, xq, s_a, M, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK
-                                                                                                         : W4A8_ERR_LAUNCH;
+    return launch_quantize_act(x_fp16, K, xq, s_a, M, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK
+                                                                                                            : W4A8_ERR_LAUNCH;
+}
+
+int w4a8_quantize_act_strided(const void *x_fp16, long long ldx, int8_t *xq, float *s_a, int M, int K, void *stream) {
+    if (!x_fp16 || !xq || !s_a) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(M, 1, K)) return e;
+    if (ldx < K || (ldx & 7) != 0) return W4A8_ERR_SHAPE;  // rows must not overlap and must start 16-byte aligned
+    if (misaligned(x_fp16) || misaligned(xq)) return W4A8_ERR_ALIGN;
+    return launch_quantize_act(x_fp16, ldx, xq, s_a, M, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK
+                                                                                                              : W4A8_ERR_LAUNCH;
 }
 
 size_t w4a8_gemm_workspace_bytes(int M, int N, int K) {

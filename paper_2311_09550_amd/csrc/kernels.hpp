@@ -101,7 +101,7 @@ hipError_t launch_splitk_epilogue(const int *part, int splits, const float *s_a,
 hipError_t launch_gemm_prefill(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
 hipError_t launch_prefill_dma_slice(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream);
 
-hipError_t launch_quantize_act(const void *x, int8_t *xq, float *s_a, int M, int K, hipStream_t stream);
+hipError_t launch_quantize_act(const void *x, long long ldx, int8_t *xq, float *s_a, int M, int K, hipStream_t stream);
 hipError_t launch_quantize_weights(const void *w, uint8_t *wp, float *s_w, int N, int K, hipStream_t stream);
 hipError_t launch_quantize_weights_clip(const void *w, const float *gamma, const float *beta, uint8_t *wp, float *s_w, int N,
                                         int K, hipStream_t stream);

@@ -109,12 +109,13 @@ __device__ __forceinline__ v4u silu_mul8(v4u gv, v4u uv) {
 }  // namespace
 
 // Per-token symmetric int8 quantisation (Sec. 3 "per token"; Eq. (2), z = 0).
+// Rows of x are ldx elements apart (ldx = K for a dense matrix; more when x is a column slice of a wider one).
 __global__ __launch_bounds__(kRowThreads, 8) void quantize_act_kernel(const uint16_t *__restrict__ x, int8_t *__restrict__ xq,
-                                                                   float *__restrict__ s_a, int K) {
+                                                                   float *__restrict__ s_a, int K, long long ldx) {
     __shared__ float scratch[kRowThreads / 64];
     const int m = blockIdx.x;
     const int chunks = K >> 3;  // 8 fp16 = 16 bytes
-    const v4u *src = (const v4u *)(x + (size_t)m * K);
+    const v4u *src = (const v4u *)(x + (size_t)m * (size_t)ldx);
 
     v4u cache[kCache];
     float amax = 0.f;
@@ -296,8 +297,8 @@ __global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const 
         emit(c, silu_mul8(gate[c], up[c]));
 }
 
-hipError_t launch_quantize_act(const void *x, int8_t *xq, float *s_a, int M, int K, hipStream_t stream) {
-    hipLaunchKernelGGL(quantize_act_kernel, dim3(M), dim3(kRowThreads), 0, stream, (const uint16_t *)x, xq, s_a, K);
+hipError_t launch_quantize_act(const void *x, long long ldx, int8_t *xq, float *s_a, int M, int K, hipStream_t stream) {
+    hipLaunchKernelGGL(quantize_act_kernel, dim3(M), dim3(kRowThreads), 0, stream, (const uint16_t *)x, xq, s_a, K, ldx);
     return hipGetLastError();
 }
 

@@ -84,6 +84,12 @@ def test_argument_validation_happens_before_any_launch(L):
     assert q(p, p, p, 0, 32, null) == -2
     assert q(p, p, p, 1, 40, null) == -2
     assert q(odd, p, p, 1, 32, null) == -3
+    qs = L.w4a8_quantize_act_strided
+    assert qs(null, 64, p, p, 1, 32, null) == -1
+    assert qs(p, 24, p, p, 1, 32, null) == -2      # rows would overlap
+    assert qs(p, 36, p, p, 1, 32, null) == -2      # rows would not start 16-byte aligned
+    assert qs(p, 64, p, p, 1, 40, null) == -2
+    assert qs(odd, 64, p, p, 1, 32, null) == -3
     assert L.w4a8_quantize_weights(p, p, null, 4, 32, null) == -1
     assert L.w4a8_quantize_weights(p, p, p, 4, 33, null) == -2
     assert L.w4a8_quantize_weights_clipped(p, null, null, p, null, 4, 32, null) == -1

@@ -169,3 +169,15 @@ def test_quantizers_on_adversarial_quotients(gpu, oracle):
     wq_o, sw_o = oracle.quantize_weights_rtn(w)
     assert_equal_bits(s_w.cpu().numpy().view(np.uint32), sw_o.view(np.uint32), "s_w")
     assert_equal_bits(wp.cpu().numpy(), oracle.pack_w4(wq_o), "wp")
+
+
+@pytest.mark.parametrize("M,K,ld,col0", [(1, 32, 96, 32), (5, 160, 480, 160), (16, 5120, 15360, 0), (130, 1024, 3080, 1032)])
+def test_quantize_act_strided_column_block(gpu, oracle, M, K, ld, col0):
+    """A block of K columns of a wider fp16 matrix, quantised in place: bit-exact against the oracle on that block."""
+    wide = synth.activations_fp16(M, ld, config_id=97, tag=5)
+    d = gpu.from_numpy(wide).cuda()
+    xq, s_a = w4a8.w4a8_quantize_act_strided(d[:, col0:col0 + K])
+    gpu.cuda.synchronize()
+    xq_o, s_a_o = oracle.quantize_act(np.ascontiguousarray(wide[:, col0:col0 + K]))
+    assert_equal_bits(xq.cpu().numpy(), xq_o, "strided quantiser codes")
+    assert_equal_bits(s_a.cpu().numpy().view(np.uint32), s_a_o.view(np.uint32), "strided quantiser scales")
