@@ -314,12 +314,13 @@ def cpu_baseline(synth, M, target_seconds):
         wq, s_w = oracle.quantize_weights_rtn(synth.weights_fp16(N, K, config_id=3))
         prepared[name] = (oracle.pack_w4(wq), s_w)
     H = shapes["qkv"][1]
-    xs = [synth.activations_fp16(M, H, config_id=3, tag=t)[:rows] for t in (1, 2, 3)]
+    x = synth.activations_fp16(M, H, config_id=3, tag=1)[:rows]
     t0 = time.perf_counter()
     out = None
-    for name, x in zip(("qkv", "o", "gate_up"), xs):
+    for name in ("qkv", "o", "gate_up"):   # the same chain as on the GPU: the Q slice feeds O, O feeds gate+up
         xq, s_a = oracle.quantize_act(x)
         _, _, out = oracle.gemm(xq, s_a, *prepared[name])
+        x = np.ascontiguousarray(out[:, :H])
     _, act = oracle.silu_mul(out)
     xq, s_a = oracle.quantize_act(act)   # the oracle keeps the two steps apart
     oracle.gemm(xq, s_a, *prepared["down"])
