@@ -256,7 +256,9 @@ def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
             x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
             xq, s_a = w4a8.w4a8_quantize_act(x)
             out = torch.empty((M, N), dtype=torch.float16, device="cuda")
-            calls = {4: lambda t: w4a8.w4a8_gemm_tiled(xq, s_a, t, s_w4, out=out),
+            # all four through the same kernel (the large-M one with the library's tile for the shape), also at M = 16,
+            # where w4a8_gemm_tiled itself would hand the signed format to the weight-streaming kernel
+            calls = {4: lambda t: w4a8.w4a8_gemm_tuned(xq, s_a, t, s_w4, w4a8.TILING_PREFILL_TILED, 0, N=N, out=out),
                      "u4": lambda t: w4a8.w4a8_gemm_tiled_unsigned(xq, s_a, t, s_w4, out=out),
                      "fg": lambda t: w4a8.w4a8_gemm_fine_grained(xq, s_a, t, s_g, out=out),
                      8: lambda t: w4a8.w8a8_gemm_tiled(xq, s_a, t, s_w8, out=out)}
