@@ -94,3 +94,20 @@ def test_llama13b_decode_shapes_over_tiled_weights(gpu, oracle):
         cols = sorted({0, 1, 31, 32, 33, N // 2, N - 33, N - 32, N - 1} | set(range(4097, N, 977)))
         acc_o, y32, _ = oracle.gemm(xq, s_a, wp[cols], s_w[cols])
         assert_fp16_close(out.cpu().numpy()[:, cols], y32, acc_o, f"13B {name} M=16 over tiled weights")
+
+
+@pytest.mark.parametrize("M", [8, 1024])
+@pytest.mark.parametrize("N,K", synth.PAPER_TABLE5_SHAPES)
+def test_paper_table5_shapes_over_tiled_weights(gpu, oracle, M, N, K):
+    """The GEMM sizes the paper itself times (Table 5; N = 11088 is not a multiple of 32, so the last weight block is
+    partly padding) at a token-generation and a context-decoding M, through the one-copy entry; rows sampled."""
+    t = gpu
+    xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=98)
+    wp = oracle.pack_w4(wq)
+    wt = w4a8.w4a8_tile_weights(t.from_numpy(wp).cuda())
+    ws = t.empty((max(16, w4a8.w4a8_gemm_tiled_workspace_bytes(M, N, K)),), dtype=t.uint8, device="cuda")
+    out = w4a8.w4a8_gemm_tiled_splitk(t.from_numpy(xq).cuda(), t.from_numpy(s_a).cuda(), wt, t.from_numpy(s_w).cuda(), ws=ws)
+    t.cuda.synchronize()
+    rows = sorted({0, 1, M // 2, M - 1})
+    acc_o, y32, _ = oracle.gemm(xq[rows], s_a[rows], wp, s_w)
+    assert_fp16_close(out.cpu().numpy()[rows], y32, acc_o, f"Table 5 shape N={N} K={K} M={M}")
