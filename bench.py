@@ -64,6 +64,7 @@ def parse_args():
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1,4,16 weight-streaming measurements")
     ap.add_argument("--no-layer-stack", action="store_true", help="skip the graph-replayed layer stack at M=1..2048")
     ap.add_argument("--no-w8a8", action="store_true", help="skip the per-GEMM W4A8 / W8A8 comparison")
+    ap.add_argument("--no-medium-m", action="store_true", help="skip the four linears at M = 32 .. 512")
     ap.add_argument("--no-table5", action="store_true", help="skip the GEMM sizes of the paper's Table 5")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
@@ -228,6 +229,51 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
                          "GBps": round(by / us / 1e3, 1), "hbm_frac": round(by / us / 1e3 / HBM_PEAK_GBS, 4),
                          "weight_copies": copies})
         del wps, wt
+        torch.cuda.empty_cache()
+    return rows
+
+
+def time_medium_m(torch, w4a8, synth, model="13b", Ms=(32, 64, 128, 256, 512), iters=4):
+    """Between token generation and context decoding: the four linears at M = 32 .. 512 from cold weights (rotating
+    copies as in time_decode), through the one-copy entry with its K slices.  Each row is set against the larger of
+    the two roofline times (bytes at the HBM peak, operations at the int8 MFMA peak)."""
+    rows = []
+    for name, (N, K) in synth.LLAMA_SHAPES[model].items():
+        w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).cuda()
+        wp, s_w = w4a8.w4a8_quantize_weights(w)
+        wt = w4a8.w4a8_tile_weights(wp)
+        del w, wp
+        copies = max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wt.numel()) + 1)
+        wts = [wt] + [wt.clone() for _ in range(copies - 1)]
+        for M in Ms:
+            x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
+            xq, s_a = w4a8.w4a8_quantize_act(x)
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            need = w4a8.w4a8_gemm_tiled_workspace_bytes(M, N, K)
+            ws = torch.empty((max(16, need),), dtype=torch.uint8, device="cuda")
+            call = lambda i: w4a8.w4a8_gemm_tiled_splitk(xq, s_a, wts[i % copies], s_w, ws=ws, out=out)
+            call(0)
+            torch.cuda.synchronize()
+            n = max(copies, 16)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(n):
+                    call(i)
+            graph.replay()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(iters):
+                graph.replay()
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / (n * iters)
+            del graph
+            roof_us = max(gemm_bytes(M, N, K) / HBM_PEAK_GBS / 1e3, gemm_ops(M, N, K) / INT8_PEAK_TOPS / 1e6)
+            rows.append({"linear": name, "M": M, "us": round(us, 2), "TOPS": round(gemm_ops(M, N, K) / us / 1e6, 1),
+                         "GBps": round(gemm_bytes(M, N, K) / us / 1e3, 1), "roofline_frac": round(roof_us / us, 4),
+                         "k_slices": need // (M * N * 4) if need else 1})
+        del wts, wt
         torch.cuda.empty_cache()
     return rows
 
@@ -467,6 +513,8 @@ def main():
                                      "unit": "GB/s", "frac": round(mean_bytes / mean_us / 1e3 / HBM_PEAK_GBS, 4),
                                      "traffic": None, "kernel": "gemm_decode_resident_kernel",
                                      "worst": worst, "best": best}
+    if not args.no_medium_m:
+        result["medium_m"] = time_medium_m(torch, w4a8, synth)
     if not args.no_table5:
         result["paper_table5_shapes"] = time_paper_table5(torch, w4a8, synth)
     if not args.no_w8a8:
