@@ -64,6 +64,7 @@ def parse_args():
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1,4,16 weight-streaming measurements")
     ap.add_argument("--no-layer-stack", action="store_true", help="skip the graph-replayed layer stack at M=1..2048")
     ap.add_argument("--no-w8a8", action="store_true", help="skip the per-GEMM W4A8 / W8A8 comparison")
+    ap.add_argument("--no-achievable", action="store_true", help="skip the probes of achievable HBM and MFMA rates")
     ap.add_argument("--no-medium-m", action="store_true", help="skip the four linears at M = 32 .. 512")
     ap.add_argument("--no-table5", action="store_true", help="skip the GEMM sizes of the paper's Table 5")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
@@ -231,6 +232,56 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
         del wps, wt
         torch.cuda.empty_cache()
     return rows
+
+
+def time_achievable(torch, w4a8):
+    """What the chip sustains, measured with the library's two probes, to set the datasheet fractions against: a
+    read-only streaming reduction over 2 GiB (eight times the last-level cache, so every pass comes from HBM) and over
+    cold pieces of the sizes of the 13B weight matrices, and a register-resident int8 MFMA loop on constant and on
+    random operands, long (about 2 ms) and as short as the GEMM kernels (about 50 us)."""
+    out = {}
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    big = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    big.fill_(7)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps   # seconds per call
+
+    out["hbm_read_GBps"] = round(big.numel() / timed(lambda: w4a8.w4a8_probe_stream_read(big, sink), 5) / 1e9, 1)
+    by_size = {}
+    for mb in (13, 39, 71):
+        size = mb * 1000 * 1000 // 4096 * 4096
+        n = big.numel() // size            # consecutive pieces: each is read once per pass over the 2 GiB
+        pieces = [big[i * size:(i + 1) * size] for i in range(n)]
+        graph = torch.cuda.CUDAGraph()
+        w4a8.w4a8_probe_stream_read(pieces[0], sink)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            for piece in pieces:
+                w4a8.w4a8_probe_stream_read(piece, sink)
+        by_size[f"{mb}MB"] = round(size * n / timed(graph.replay, 3) / 1e9, 1)
+        del graph
+    out["hbm_read_GBps_cold_pieces"] = by_size
+    del big
+    torch.cuda.empty_cache()
+    mfma = {}
+    for label, iters, pattern, reps in (("constant_2ms", 8000, 0, 3), ("random_2ms", 8000, 1, 3), ("random_50us", 200, 1, 40)):
+        ops = [0]
+
+        def run():
+            ops[0] = w4a8.w4a8_probe_mfma_int8(sink, iters, pattern)
+        t = timed(run, reps)
+        mfma[label] = round(ops[0] / t / 1e12, 1)
+    out["int8_mfma_TOPS"] = mfma
+    return out
 
 
 def time_medium_m(torch, w4a8, synth, model="13b", Ms=(32, 64, 128, 256, 512), iters=4):
@@ -513,6 +564,18 @@ def main():
                                      "unit": "GB/s", "frac": round(mean_bytes / mean_us / 1e3 / HBM_PEAK_GBS, 4),
                                      "traffic": None, "kernel": "gemm_decode_resident_kernel",
                                      "worst": worst, "best": best}
+    if not args.no_achievable:
+        ach = time_achievable(torch, w4a8)
+        result["achievable"] = ach
+        result["roofline"]["frac_of_achievable"] = round(result["roofline"]["achieved"] / ach["int8_mfma_TOPS"]["random_50us"], 4)
+        if "roofline_decode" in result:
+            # every decode case against the plain read of a cold piece of about its size
+            piece = {"o": "13MB", "qkv": "39MB", "down": "39MB", "gate_up": "71MB"}
+            for r in result["decode"]:
+                rate = ach["hbm_read_GBps_cold_pieces"][piece[r["linear"]]]
+                r["frac_of_stream_read"] = round(r["GBps"] / rate, 4)
+            result["roofline_decode"]["frac_of_achievable"] = round(
+                sum(r["frac_of_stream_read"] for r in result["decode"]) / len(result["decode"]), 4)
     if not args.no_medium_m:
         result["medium_m"] = time_medium_m(torch, w4a8, synth)
     if not args.no_table5:

@@ -257,6 +257,20 @@ int w4a8_gemm_fine_grained(const int8_t *xq, const float *s_a, const uint8_t *wt
                            void *out_fp16, int M, int N, int K, int variant, void *stream);
 
 /*
+ * Two probes of what the chip sustains, for a benchmark to set its figures against (they are no part of the path and
+ * compute nothing of use):
+ * w4a8_probe_stream_read: a read-only streaming reduction over buf (device, `bytes` long, 16-byte aligned) by 8
+ *   workgroups per compute unit; bytes / run time is the read rate a plain kernel reaches on this buffer.
+ * w4a8_probe_mfma_int8: a register-resident loop of `iters` x 8 int8 32x32x32 MFMAs per wave, 8 waves per compute
+ *   unit; operations = compute units * 8 waves * iters * 8 * 65536.  pattern 0 = constant operands, 1 = random int8
+ *   activations and random multiples of 16 as weights (what the W4A8 kernel feeds the matrix cores): the rate depends
+ *   on the operand values through the chip's power management.
+ * sink: 4 bytes of device memory that are practically never written.
+ */
+int w4a8_probe_stream_read(const void *buf, size_t bytes, void *sink, void *stream);
+int w4a8_probe_mfma_int8(void *sink, int iters, int pattern, void *stream);
+
+/*
  * Glue between the gate/up GEMM and the down GEMM of a LLaMA MLP:
  *   h[m][i] = fp16( silu(gate_up[m][i]) * gate_up[m][I + i] ),  fp32 arithmetic.
  *   gate_up_fp16 [M][2I] in, h_fp16 [M][I] out.  I % 8 == 0.

@@ -68,6 +68,10 @@ def lib():
         L.w4a8_gemm_tiled_workspace_bytes.argtypes = [i, i, i]
         L.w4a8_gemm_tiled_splitk.restype = i
         L.w4a8_gemm_tiled_splitk.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+        L.w4a8_probe_stream_read.restype = i
+        L.w4a8_probe_stream_read.argtypes = [vp, sz, vp, vp]
+        L.w4a8_probe_mfma_int8.restype = i
+        L.w4a8_probe_mfma_int8.argtypes = [vp, i, i, vp]
         L.w4a8_gemm_fine_grained.restype = i
         L.w4a8_gemm_fine_grained.argtypes = [vp, vp, vp, vp, i, vp, i, i, i, i, vp]
         L.w4a8_gemm_tiled_unsigned.restype = i
@@ -120,6 +124,20 @@ def bound_call(name: str, *args):
         if code != 0:
             _check(code)
     return call
+
+
+def w4a8_probe_stream_read(buf, sink):
+    """Read-only streaming reduction over a uint8 device buffer (a probe of the achievable read rate)."""
+    torch = _torch()
+    _check(lib().w4a8_probe_stream_read(_dev(buf, torch.uint8, "buf"), buf.numel(), _dev(sink, torch.int32, "sink"), _stream()))
+
+
+def w4a8_probe_mfma_int8(sink, iters: int, pattern: int = 1):
+    """Register-resident int8 MFMA loop on every compute unit; returns the operations it performs."""
+    torch = _torch()
+    _check(lib().w4a8_probe_mfma_int8(_dev(sink, torch.int32, "sink"), iters, pattern, _stream()))
+    cus = torch.cuda.get_device_properties(sink.device).multi_processor_count
+    return cus * 8 * iters * 8 * 65536
 
 
 def w4a8_version() -> int:

@@ -516,6 +516,23 @@ int w4a8_silu_mul_quantize(const void *gate_up_fp16, int8_t *xq, float *s_a, int
                : W4A8_ERR_LAUNCH;
 }
 
+// ---- probes of what the chip sustains (context for the measurements, no part of the path)
+
+int w4a8_probe_stream_read(const void *buf, size_t bytes, void *sink, void *stream) {
+    if (!buf || !sink) return W4A8_ERR_NULL;
+    if (bytes < 16) return W4A8_ERR_SHAPE;
+    if (misaligned(buf)) return W4A8_ERR_ALIGN;
+    return launch_probe_stream_read(buf, bytes, static_cast<unsigned *>(sink), 8 * compute_units(),
+                                    static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+}
+
+int w4a8_probe_mfma_int8(void *sink, int iters, int pattern, void *stream) {
+    if (!sink) return W4A8_ERR_NULL;
+    if (iters < 1 || iters > (1 << 24) || pattern < 0 || pattern > 1) return W4A8_ERR_ARG;
+    return launch_probe_mfma_i8(static_cast<int *>(sink), 2 * compute_units(), iters, pattern,
+                                static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+}
+
 int w4a8_pack_weights_host(const int8_t *wq_host, uint8_t *wp_host, int N, int K) {
     if (!wq_host || !wp_host) return W4A8_ERR_NULL;
     if (N < 1 || K < 2 || (K & 1)) return W4A8_ERR_SHAPE;

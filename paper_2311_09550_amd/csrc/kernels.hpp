@@ -106,6 +106,8 @@ hipError_t launch_quantize_weights(const void *w, uint8_t *wp, float *s_w, int N
 hipError_t launch_quantize_weights_clip(const void *w, const float *gamma, const float *beta, uint8_t *wp, float *s_w, int N,
                                         int K, hipStream_t stream);
 hipError_t launch_silu_mul(const void *gate_up, void *h, int M, int I, hipStream_t stream);
+hipError_t launch_probe_stream_read(const void *src, size_t bytes, unsigned *sink, int workgroups, hipStream_t stream);
+hipError_t launch_probe_mfma_i8(int *sink, int workgroups, int iters, int pattern, hipStream_t stream);
 hipError_t launch_silu_mul_quantize(const void *gate_up, int8_t *xq, float *s_a, int M, int I, hipStream_t stream);
 
 }  // namespace w4a8

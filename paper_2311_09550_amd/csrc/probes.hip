@@ -1,0 +1,88 @@
+// Two probes that measure what the chip sustains, for the measurements to be read against: a read-only streaming
+// reduction (achievable HBM read rate) and a register-resident int8 MFMA loop (achievable matrix-core rate, which on
+// this chip depends on the operand values through power management).  They compute nothing the library's callers use.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace w4a8 {
+
+namespace {
+
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ unsigned mix(unsigned x) {
+    x ^= x >> 16;
+    x *= 0x7feb352dU;
+    x ^= x >> 15;
+    x *= 0x846ca68bU;
+    x ^= x >> 16;
+    return x;
+}
+
+// Every thread walks the buffer with a grid-wide stride, four 16-byte loads in flight; the xor of everything read is
+// kept so that the loads cannot be dropped (it is stored only if it equals a value it practically never takes).
+__global__ __launch_bounds__(256) void probe_stream_read_kernel(const v4u *__restrict__ src, unsigned long long n16,
+                                                                unsigned *__restrict__ sink) {
+    const unsigned long long stride = (unsigned long long)gridDim.x * 256ull;
+    unsigned acc = 0;
+    for (unsigned long long i = (unsigned long long)blockIdx.x * 256ull + threadIdx.x; i < n16; i += 4 * stride) {
+        v4u v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const unsigned long long j = i + u * stride;
+            v[u] = j < n16 ? src[j] : v4u{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;
+}
+
+// 8 independent 32x32x32 int8 MFMAs per iteration on register operands (the operand shapes of the large-M kernel:
+// 4 activation-like and 2 weight-like fragments).  pattern 0: small constants; 1: random bytes for the activations and
+// random multiples of 16 for the weights, i.e. what the W4A8 kernel feeds the matrix cores.
+__global__ __launch_bounds__(256, 2) void probe_mfma_i8_kernel(int *__restrict__ sink, int iters, int pattern) {
+    v4i a[4], b[2];
+    const unsigned t = threadIdx.x + blockIdx.x * 256u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[i][j] = pattern == 0 ? i + j : (int)mix(t * 64 + i * 4 + j + 1);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[i][j] = pattern == 0 ? i + j + 1 : (int)(mix(t * 64 + 32 + i * 4 + j + 1) & 0xF0F0F0F0u);
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+                acc[n * 4 + m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[n], a[m], acc[n * 4 + m], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += acc[i][j];
+    if (s == 0x12345) sink[0] = s;
+}
+
+}  // namespace
+
+hipError_t launch_probe_stream_read(const void *src, size_t bytes, unsigned *sink, int workgroups, hipStream_t stream) {
+    hipLaunchKernelGGL(probe_stream_read_kernel, dim3(workgroups), dim3(256), 0, stream, (const v4u *)src,
+                       (unsigned long long)(bytes / 16), sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_mfma_i8(int *sink, int workgroups, int iters, int pattern, hipStream_t stream) {
+    hipLaunchKernelGGL(probe_mfma_i8_kernel, dim3(workgroups), dim3(256), 0, stream, sink, iters, pattern);
+    return hipGetLastError();
+}
+
+}  // namespace w4a8

@@ -161,3 +161,13 @@ def test_split_workspace_is_a_pure_function_of_shape(L):
     for shape in [(32, 5120, 5120), (128, 5120, 13824), (64, 4096, 4096)]:
         n = f(*shape)
         assert n == f(*shape) and n % (shape[0] * shape[1] * 4) == 0 and 2 <= n // (shape[0] * shape[1] * 4) <= 8
+
+
+def test_probe_arguments(L):
+    p, null, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0), ctypes.c_void_p(0x1008)
+    assert L.w4a8_probe_stream_read(null, ctypes.c_size_t(1 << 20), p, null) == -1
+    assert L.w4a8_probe_stream_read(p, ctypes.c_size_t(8), p, null) == -2
+    assert L.w4a8_probe_stream_read(odd, ctypes.c_size_t(1 << 20), p, null) == -3
+    assert L.w4a8_probe_mfma_int8(null, 10, 0, null) == -1
+    assert L.w4a8_probe_mfma_int8(p, 0, 0, null) == -7
+    assert L.w4a8_probe_mfma_int8(p, 10, 2, null) == -7
