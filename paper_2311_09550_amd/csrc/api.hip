@@ -196,8 +196,11 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
         DecodeShape s{};
         s.resident = false;
         s.tiled = decode_tiled;
-        s.row_tiles = variant ? variant / 100 : (M <= 8 ? 1 : 2);
-        s.waves = variant ? variant % 100 : ((mt >= 4 && s.row_tiles == 2) ? 4 : 8);
+        // K beyond the resident kernel's reach at token-generation sizes (70B down, K = 28672): two row tiles on four
+        // waves stream 7 % faster than the general default (measured, cold weights)
+        const bool long_k_decode = mt == 1 && K > 16384;
+        s.row_tiles = variant ? variant / 100 : ((M <= 8 && !long_k_decode) ? 1 : 2);
+        s.waves = variant ? variant % 100 : (((mt >= 4 && s.row_tiles == 2) || long_k_decode) ? 4 : 8);
         if ((s.row_tiles != 1 && s.row_tiles != 2) || (s.waves != 4 && s.waves != 8)) return W4A8_ERR_ARG;
         if (mt == 4 && s.row_tiles == 2 && s.waves == 8) return W4A8_ERR_ARG;  // would not fit in LDS
         pl->decode = s;
