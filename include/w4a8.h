@@ -111,39 +111,6 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * As the two calls above, with the tiling forced instead of chosen from the
- * shape.  For tuning sweeps and for tests that must cover every tiling at
- * every shape.  `tiling` is one of W4A8_TILING_*.  `variant` refines it
- * (0 = library default, W4A8_ERR_ARG if not available for the shape):
- *   DECODE_RESIDENT: waves * 100000 + workgroups, waves in {8, 16} (0 = default),
- *                    workgroups = size of the persistent grid (0 = default);
- *   DECODE_STREAM:   row_tiles * 100 + waves, row_tiles in {1, 2}, waves in {4, 8};
- *   PREFILL:         output tile (rows of X x channels): 1 = 128 x 256 as 1 x 4 waves, 2 = 128 x 128,
- *                    3 = 128 x 160, 4 = 128 x 256 as 2 x 2 waves (operands staged through registers);
- *                    5..8 = the shapes of 1, 4, 3, 2 with LDS-direct loads and a four-stage ring;
- *   PREFILL_TILED:   `wp` is the TILED weight array of w4a8_tile_weights; output tile 1 = 256 x 256 as
- *                    2 x 4 waves, 2 = 256 x 256 as 4 x 2 waves, 3 = 128 x 256, 4 = 128 x 160, 5 = 128 x 128,
- *                    6 = 64 x 128, 7 = 64 x 64, 8 = 32 x 128 (the small tiles are for medium M);
- *                    9, 10 = the tiles of 4, 5 run by two sets of waves that split every 128-k stage between
- *                    them and add their integer sums before the epilogue (same bits; never the library's choice).
- * Exactly one of out_fp16 / acc_i32 must be non-NULL (s_a and s_w may be NULL
- * when acc_i32 is requested).
- */
-#define W4A8_TILING_AUTO 0
-#define W4A8_TILING_DECODE_RESIDENT 1 /* persistent weight-streaming kernel, activations kept in registers:
-                                         M <= 16 with K <= 16384, or M <= 32 with K <= 8192              */
-#define W4A8_TILING_DECODE_STREAM 2   /* general weight-streaming kernel, M <= 64                         */
-#define W4A8_TILING_PREFILL 3         /* LDS-staged output tiles on 32x32x32 int8 MFMA, for large M       */
-#define W4A8_TILING_PREFILL_TILED 4   /* the same over the tiled weight layout (any M; meant for large M)  */
-#define W4A8_TILING_DECODE_RESIDENT_TILED 5 /* tilings 1 and 2 reading the TILED weight array (`wp` = wt);        */
-#define W4A8_TILING_DECODE_STREAM_TILED 6   /* same limits and variants as 1 and 2                                 */
-#define W4A8_TILING_AUTO_TILED 7      /* library's choice over the TILED array: 5 or 6 up to M = 16, 4 above   */
-int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w,
-                    void *out_fp16, int32_t *acc_i32, int M, int N, int K,
-                    int tiling, int variant,
-                    void *workspace, size_t workspace_bytes, void *stream);
-
-/*
  * Tiled weight layout for large M.  The weights are static, so, like the paper's offline weight format (Sec. 5.3),
  * they may be reordered once after packing into the order in which the large-M kernel consumes them; every wave
  * load then moves whole cache lines.  Same codes, same arithmetic, same results as the row-major array.
@@ -203,6 +170,14 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
                            void *stream);
 
 /*
+ * Optional set-up for the current device, once per device and process: asks the runtime for the LDS allowance of
+ * every kernel that needs more than the default, so that no
+ * later call has to (a first launch made under stream capture or from several threads at once is then as plain as
+ * any other).  Calls without it do the same on first use, serialised.  Launches nothing, allocates nothing.
+ */
+int w4a8_init(void);
+
+/*
  * W8A8 comparison variant (the paper sets its W4A8 against its own W8A8, Table 4): the same contraction and the
  * same epilogue (Eq. (6),(7)) with int8 weight codes,
  *   O[m][n] = fp16( float( sum_k Xq[m][k] * W8[n][k] ) * (s_a[m] * s_w[n]) ),   W8 in [-128, 127],
@@ -255,20 +230,6 @@ int w4a8_gemm_tiled_unsigned(const int8_t *xq, const float *s_a, const uint8_t *
  */
 int w4a8_gemm_fine_grained(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_g, int ldg,
                            void *out_fp16, int M, int N, int K, int variant, void *stream);
-
-/*
- * Two probes of what the chip sustains, for a benchmark to set its figures against (they are no part of the path and
- * compute nothing of use):
- * w4a8_probe_stream_read: a read-only streaming reduction over buf (device, `bytes` long, 16-byte aligned) by 8
- *   workgroups per compute unit; bytes / run time is the read rate a plain kernel reaches on this buffer.
- * w4a8_probe_mfma_int8: a register-resident loop of `iters` x 8 int8 32x32x32 MFMAs per wave, 8 waves per compute
- *   unit; operations = compute units * 8 waves * iters * 8 * 65536.  pattern 0 = constant operands, 1 = random int8
- *   activations and random multiples of 16 as weights (what the W4A8 kernel feeds the matrix cores): the rate depends
- *   on the operand values through the chip's power management.
- * sink: 4 bytes of device memory that are practically never written.
- */
-int w4a8_probe_stream_read(const void *buf, size_t bytes, void *sink, void *stream);
-int w4a8_probe_mfma_int8(void *sink, int iters, int pattern, void *stream);
 
 /*
  * Glue between the gate/up GEMM and the down GEMM of a LLaMA MLP:

@@ -2,7 +2,7 @@
 
 Only argument marshalling happens here: torch supplies device memory and the
 current HIP stream, every step of the path runs in the HIP kernels behind the C
-ABI declared in ``include/w4a8.h``.  There is no CPU fallback: if the library
+ABI declared in ``include/w4a8.h`` and ``include/w4a8_tuning.h``.  There is no CPU fallback: if the library
 has not been built (``python -m paper_2311_09550_amd.build`` or
 ``__graft_entry__.build()``), the first call raises.
 """
@@ -68,8 +68,12 @@ def lib():
         L.w4a8_gemm_tiled_workspace_bytes.argtypes = [i, i, i]
         L.w4a8_gemm_tiled_splitk.restype = i
         L.w4a8_gemm_tiled_splitk.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+        L.w4a8_init.restype = i
+        L.w4a8_init.argtypes = []
         L.w4a8_probe_stream_read.restype = i
         L.w4a8_probe_stream_read.argtypes = [vp, sz, vp, vp]
+        L.w4a8_probe_read_pattern.restype = i
+        L.w4a8_probe_read_pattern.argtypes = [vp, sz, vp, i, i, i, vp]
         L.w4a8_probe_mfma_int8.restype = i
         L.w4a8_probe_mfma_int8.argtypes = [vp, i, i, vp]
         L.w4a8_gemm_fine_grained.restype = i
@@ -130,6 +134,13 @@ def w4a8_probe_stream_read(buf, sink):
     """Read-only streaming reduction over a uint8 device buffer (a probe of the achievable read rate)."""
     torch = _torch()
     _check(lib().w4a8_probe_stream_read(_dev(buf, torch.uint8, "buf"), buf.numel(), _dev(sink, torch.int32, "sink"), _stream()))
+
+
+def w4a8_probe_read_pattern(buf, sink, pattern: int, loads: int, workgroups_per_cu: int):
+    """The read probe with the access pattern, loads in flight and workgroups per compute unit chosen by the caller."""
+    torch = _torch()
+    _check(lib().w4a8_probe_read_pattern(_dev(buf, torch.uint8, "buf"), buf.numel(), _dev(sink, torch.int32, "sink"),
+                                         pattern, loads, workgroups_per_cu, _stream()))
 
 
 def w4a8_probe_mfma_int8(sink, iters: int, pattern: int = 1):
@@ -374,6 +385,11 @@ def w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, variant: int = 0, splits: int = 0, 
                                         _dev(s_w, torch.float32, "s_w"), _dev(out, torch.float16, "out"), M, N, K, variant,
                                         splits, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
     return out
+
+
+def w4a8_init():
+    """Per-device set-up (LDS allowances of the kernels) for torch's current device."""
+    _check(lib().w4a8_init())
 
 
 def w4a8_gemm_fine_grained(xq, s_a, wt, s_g, N=None, variant: int = 0, out=None):

@@ -10,7 +10,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libw4a8.so")
 SOURCES = ["api.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_prefill_dma.hip", "gemm_prefill_tiled.hip", "probes.hip",
            "quantize.hip"]
-HEADERS = ["common.hpp", "kernels.hpp", os.path.join("..", "..", "include", "w4a8.h")]
+HEADERS = ["common.hpp", "kernels.hpp", os.path.join("..", "..", "include", "w4a8.h"),
+           os.path.join("..", "..", "include", "w4a8_tuning.h")]
 
 # -packed-fp32-ops: keep the compiler from forming packed fp32 VALU instructions.
 # -ffp-contract=off: no fused multiply-adds are formed from separate fp32 operations, as in the build of the CPU

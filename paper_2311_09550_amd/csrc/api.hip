@@ -1,8 +1,12 @@
 // C ABI of the W4A8 library: argument validation, tiling choice, launches.
 // Nothing here touches the data; every step of the path runs in the kernels.
 #include "../../include/w4a8.h"
+#include "../../include/w4a8_tuning.h"
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <mutex>
 
 #include "kernels.hpp"
 
@@ -19,18 +23,17 @@ inline int check_gemm_shape(int M, int N, int K) {
     return W4A8_OK;
 }
 
-// Compute units of the current device (256 on MI355X); queried once.
+// Compute units of the current device (256 on MI355X); queried once per device.
 int compute_units() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
+    static std::atomic<int> cus[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    int n = cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev].store(n, std::memory_order_relaxed);
     }
-    return cus;
+    return n;
 }
 
 struct Plan {
@@ -39,27 +42,48 @@ struct Plan {
     int prefill_tile;
 };
 
-// Shape of the persistent decode kernel for (M, K): 8 waves while a wave's k steps stay few (fewer
-// registers per wave, two workgroups per compute unit), else 16 waves.  Returns false when the
-// activations of a wave would not fit in registers.
-bool resident_shape(int M, int N, int K, int waves, int grid, DecodeShape *out, bool tiled = false) {
+// Shape of the persistent weight-streaming kernel for (M, N, K).  Returns false when a wave's share of the
+// activations would not fit in registers (then the general streaming kernel takes over).
+//   waves    : 8 or 16, 0 = library's choice: 8 while K <= 8192 and M <= 16, else 16;
+//   grid     : workgroups wanted, 0 = library's choice.  A workgroup's range is N / grid rounded up to whole cache
+//              lines of the weight array (8 channels in the tiled array, 4 in the row-major one).  The library's own
+//              choice is one workgroup per compute unit with the range rounded up to whole 16-channel chunks
+//              (measured on LLaMA-7B/13B/70B shapes, cold weights: within 4 % of the best grid everywhere; ranges of
+//              20 or 24 channels, i.e. chunks of 12, lose up to 13 % to ranges of 32 on fewer compute units);
+//   prefetch : chunks of weight loads a wave keeps in flight, 0 = library's choice: one, since a compute unit takes
+//              only some 40 to 50 outstanding wave-wide loads and one chunk per wave already is that many; two where a
+//              range is exactly two chunks and M <= 4 (everything is then requested at once: 4 % on 13B's O);
+//   whole16  : chunks of 16 channels even where the range does not divide evenly;
+//   aux      : cache policy of the weight loads, -1 = library's choice (non-temporal: 5 to 10 % faster).
+bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool whole16, int aux, bool tiled, DecodeShape *out) {
     const int ks_total = (K + 127) / 128;
+    const int mt = (M + 15) / 16;
     DecodeShape s{};
     s.resident = true;
     s.tiled = tiled;
-    if (waves == 0) waves = (M <= 16 && ks_total <= 40) ? 8 : 16;
+    s.aux = aux < 0 ? 2 : aux;
+    if (waves == 0) waves = (mt == 1 && ks_total <= 64) ? 8 : 16;
     s.waves = waves;
     s.x_steps = (ks_total + waves - 1) / waves;
-    // as many workgroups as fit on the chip at once, each with the same share of the output channels
-    // Measured: one workgroup per compute unit streams fastest, and whole 16-channel blocks per workgroup beat a
-    // finer split whose last block is partly empty (N = 5120: 160 workgroups of 32 channels are 6-8 % faster than 256
-    // of 20), so the library's own choice rounds the share up to whole blocks; a forced grid keeps its share as given.
-    const bool own_choice = grid <= 0;
-    if (own_choice) grid = compute_units();
-    int rows = ((N + grid - 1) / grid + 3) & ~3;
-    if (own_choice) rows = (rows + 15) & ~15;
-    if (rows < 4) rows = 4;
+    // In the tiled array a 128-byte line holds 16 bytes of each of 8 consecutive channels: ranges that start on
+    // multiples of 8 channels never share a line with a neighbour (which would fetch it a second time).
+    const int unit = tiled ? 8 : 4;
+    int rows;
+    if (grid <= 0) {
+        rows = ((N + compute_units() - 1) / compute_units() + 15) / 16 * 16;
+        if (rows > kResidentMaxRows) rows = kResidentMaxRows;
+    } else {
+        rows = ((N + grid - 1) / grid + unit - 1) / unit * unit;
+    }
+    if (rows < unit) rows = unit;
     s.rows_per_wg = rows;
+    const int chunks = (rows + 15) / 16;
+    s.chunk_rows = whole16 ? 16 : (((rows + chunks - 1) / chunks + 3) & ~3);
+    s.prefetch = prefetch;
+    if (prefetch == 0) {
+        s.prefetch = (chunks == 2 && M <= 4) ? 2 : 1;
+        if (s.prefetch == 2 && !decode_resident_supported(M, N, K, s)) s.prefetch = 1;
+    }
     if (!decode_resident_supported(M, N, K, s)) return false;
     *out = s;
     return true;
@@ -175,8 +199,8 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
         if (M > 16)
             pl->tiling = W4A8_TILING_PREFILL_TILED;
         else
-            pl->tiling = resident_shape(M, N, K, 0, 0, &pl->decode, true) ? W4A8_TILING_DECODE_RESIDENT_TILED
-                                                                           : W4A8_TILING_DECODE_STREAM_TILED;
+            pl->tiling = resident_shape(M, N, K, 0, 0, 0, false, -1, true, &pl->decode) ? W4A8_TILING_DECODE_RESIDENT_TILED
+                                                                                         : W4A8_TILING_DECODE_STREAM_TILED;
     }
     const bool decode_tiled = pl->tiling == W4A8_TILING_DECODE_RESIDENT_TILED || pl->tiling == W4A8_TILING_DECODE_STREAM_TILED;
     if (pl->tiling == W4A8_TILING_DECODE_RESIDENT_TILED) pl->tiling = W4A8_TILING_DECODE_RESIDENT;
@@ -185,11 +209,16 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
         if (M > kDecodeMaxM)
             pl->tiling = W4A8_TILING_PREFILL;
         else
-            pl->tiling = resident_shape(M, N, K, 0, 0, &pl->decode) ? W4A8_TILING_DECODE_RESIDENT : W4A8_TILING_DECODE_STREAM;
+            pl->tiling = resident_shape(M, N, K, 0, 0, 0, false, -1, false, &pl->decode) ? W4A8_TILING_DECODE_RESIDENT
+                                                                                          : W4A8_TILING_DECODE_STREAM;
     }
     if (pl->tiling == W4A8_TILING_DECODE_RESIDENT) {
-        if (M > kDecodeMaxM) return W4A8_ERR_ARG;
-        if (!resident_shape(M, N, K, variant / 100000, variant % 100000, &pl->decode, decode_tiled)) return W4A8_ERR_ARG;
+        if (M > 32) return W4A8_ERR_ARG;
+        const int flags = variant / 100000000, prefetch = variant / 10000000 % 10, waves = variant / 100000 % 100;
+        if (!resident_shape(M, N, K, waves, variant % 100000, prefetch, (flags & 1) != 0, (flags & 2) ? 2 : (flags & 8) ? 0 : -1,
+                            decode_tiled, &pl->decode))
+            return W4A8_ERR_ARG;
+        pl->decode.x_direct = (flags & 4) != 0;
     } else if (pl->tiling == W4A8_TILING_DECODE_STREAM) {
         if (M > kDecodeMaxM) return W4A8_ERR_ARG;
         const int mt = (M + 15) / 16;
@@ -241,6 +270,8 @@ int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float 
         a.out = out_fp16; a.acc_out = acc_i32;
         a.M = M; a.N = N; a.K = K;
         a.rows_per_wg = pl.decode.rows_per_wg;
+        a.chunk_rows = pl.decode.chunk_rows;
+        a.x_lds_pitch = pl.decode.x_direct ? -1 : 0;
         err = launch_gemm_decode(a, want_acc, pl.decode, st);
     } else {
         PrefillArgs a{};
@@ -416,6 +447,12 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
                                                                                                     : W4A8_ERR_LAUNCH;
 }
 
+int w4a8_init(void) {
+    (void)compute_units();
+    if (prepare_tiled_kernels() != hipSuccess || prepare_decode_kernels() != hipSuccess) return W4A8_ERR_LAUNCH;
+    return W4A8_OK;
+}
+
 // ---- W8A8 comparison variant: int8 weight codes in the tiled layout, the same kernels without the int4 conversion
 
 size_t w8a8_tiled_weight_bytes(int N, int K) {
@@ -532,6 +569,19 @@ int w4a8_probe_stream_read(const void *buf, size_t bytes, void *sink, void *stre
     if (misaligned(buf)) return W4A8_ERR_ALIGN;
     return launch_probe_stream_read(buf, bytes, static_cast<unsigned *>(sink), 8 * compute_units(),
                                     static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+}
+
+int w4a8_probe_read_pattern(const void *buf, size_t bytes, void *sink, int pattern, int loads, int workgroups_per_cu,
+                            void *stream) {
+    if (!buf || !sink) return W4A8_ERR_NULL;
+    if (bytes < 16 || bytes > 0xFFFFFFF0ull) return W4A8_ERR_SHAPE;
+    if (misaligned(buf)) return W4A8_ERR_ALIGN;
+    if (pattern < 0 || pattern > 5 || (loads != 4 && loads != 8 && loads != 16) || workgroups_per_cu < 1 || workgroups_per_cu > 64)
+        return W4A8_ERR_ARG;
+    return launch_probe_read_pattern(buf, bytes, static_cast<unsigned *>(sink), pattern, loads,
+                                     workgroups_per_cu * compute_units(), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? W4A8_OK
+               : W4A8_ERR_LAUNCH;
 }
 
 int w4a8_probe_mfma_int8(void *sink, int iters, int pattern, void *stream) {

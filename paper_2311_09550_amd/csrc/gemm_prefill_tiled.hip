@@ -601,16 +601,9 @@ hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     constexpr int kMeet = KS == 2 ? WM * WN * (32 * (64 * NTW + 16) + MTW * NTW * 16 * 256) : 0;
     constexpr int kLdsBytes = kRing > kMeet ? kRing : kMeet;
     static_assert(kLdsBytes <= 160 * 1024, "a workgroup's ring must fit the compute unit's LDS");
-    auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS, FG, KS>;
-    // more than 64 KB of LDS per workgroup has to be asked for, once per device
-    static bool raised[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!raised[dev]) {
-        const hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        raised[dev] = true;
-    }
+    constexpr auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS, FG, KS>;
+    if (const hipError_t e = allow_lds<kernel>(kLdsBytes); e != hipSuccess) return e;
+    if (p.prepare_only) return hipSuccess;
     hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN * KS), kLdsBytes, stream, p);
     return hipGetLastError();
 }
@@ -772,6 +765,22 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
             if (e != hipSuccess) return e;
         }
     }
+    return hipSuccess;
+}
+
+hipError_t prepare_tiled_kernels() {
+    PrefillArgs a{};
+    a.M = 32; a.N = 32; a.K = kTiledBlockK; a.ldc = 32; a.ldg = 32;
+    a.prepare_only = true;
+    struct Format { int wbits, tiles; bool acc; };
+    const Format formats[] = {{4, kTiledTileMax4, true}, {8, kTiledTileMax, true}, {kWeightsUnsigned4, kTiledTileMax, true},
+                              {kWeightsFineGrained4, kFineTileMax, false}};
+    for (const Format &f : formats)
+        for (int tile = 1; tile <= f.tiles; ++tile)
+            for (int acc = 0; acc <= (f.acc ? 1 : 0); ++acc) {
+                const hipError_t e = launch_gemm_prefill_tiled(a, acc != 0, tile, nullptr, f.wbits);
+                if (e != hipSuccess) return e;
+            }
     return hipSuccess;
 }
 

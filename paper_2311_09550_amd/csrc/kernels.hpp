@@ -4,7 +4,33 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 namespace w4a8 {
+
+constexpr int kMaxDevices = 64;  // device ordinals the per-device tables of the host code cover
+
+// A kernel that uses more than 64 KB of LDS per workgroup has to ask the runtime for it, once per device.  One
+// set of flags per kernel (the kernel is the template argument); the flags are atomic and the request itself is
+// serialised, so first launches from several threads are safe.  w4a8_init makes all requests up front, so that no
+// launch, in particular none under stream capture, has to.
+template <auto Kernel>
+inline hipError_t allow_lds(int bytes) {
+    static std::atomic<bool> raised[kMaxDevices];
+    static std::mutex raise_lock;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!raised[dev].load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> hold(raise_lock);
+        if (!raised[dev].load(std::memory_order_relaxed)) {
+            const hipError_t e = hipFuncSetAttribute((const void *)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+            if (e != hipSuccess) return e;
+            raised[dev].store(true, std::memory_order_release);
+        }
+    }
+    return hipSuccess;
+}
 
 struct DecodeArgs {
     const int8_t *xq;    // [M][K]
@@ -14,21 +40,32 @@ struct DecodeArgs {
     void *out;           // fp16 [M][N]
     int *acc_out;        // int32 [M][N]
     int M, N, K;
-    int rows_per_wg;     // resident kernel: output channels per workgroup (multiple of 4)
+    int rows_per_wg;     // persistent kernels: output channels per workgroup (multiple of 4)
+    int chunk_rows;      // persistent kernel: channels per chunk, 4, 8, 12 or 16
+    int x_lds_pitch;     // persistent kernel: > 0 = the activations are staged in LDS, rows this many bytes apart
+    int x_lds_offset;    //   ... starting at this byte of the kernel's dynamic LDS
 };
 
-constexpr int kResidentMaxRows = 4096;  // channels per workgroup whose scales fit the resident kernel's LDS staging
+constexpr int kResidentMaxRows = 512;  // channels per workgroup of the persistent kernel (their scales are staged in LDS,
+                                       // one load per thread of the smaller workgroup shape)
+
 
 struct DecodeShape {
     bool resident;  // persistent kernel with register-resident activations, else the general streaming kernel
+    int prefetch;   // resident: chunks of weight loads a wave keeps in flight (1, 2, 3, 4 or 8)
+    int chunk_rows; // resident: channels per chunk (4, 8, 12 or 16)
+    int aux;        // resident: cache-policy bits of the weight loads (0 or 2 = non-temporal)
+    bool x_direct;  // resident: never stage the activations in LDS (they are staged when they fit, otherwise)
     int waves;      // waves per workgroup: resident 8 or 16, streaming 4 or 8
     int x_steps;    // resident: k steps per wave = ceil(ceil(K/128) / waves)
-    int rows_per_wg;  // resident: output channels per persistent workgroup, a multiple of 4
+    int rows_per_wg;  // resident: output channels per persistent workgroup, a multiple of 4, at most kResidentMaxRows
     int row_tiles;  // streaming: 16-row weight tiles per wave, 1 or 2
     bool tiled;     // DecodeArgs::wp is the tiled weight array (2 KB blocks) instead of the row-major one
 };
 
 bool decode_resident_supported(int M, int N, int K, const DecodeShape &s);
+// Per-device preparations (LDS allowance) of every instantiation of the persistent kernel, for the current device.
+hipError_t prepare_decode_kernels();
 hipError_t launch_gemm_decode(const DecodeArgs &p, bool acc_out, const DecodeShape &s, hipStream_t stream);
 
 struct PrefillArgs {
@@ -44,6 +81,7 @@ struct PrefillArgs {
     int stages_per_split;  // taking this many 128-k stages and writing its own M x ldc slab of acc_out
     int ldg;           // fine-grained variant only: s_w then holds group scales [K / 128][ldg], ldg >= N, ldg % 4 == 0
     int tiles_m, tiles_n;
+    bool prepare_only;  // host side only: make the per-device preparations of the chosen kernel and launch nothing
 };
 
 constexpr int kPrefillBK = 128;
@@ -94,6 +132,8 @@ size_t tiled_weight_bytes(int N, int K, int wbits = 4);
 hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream);
 hipError_t launch_tile_weights8(const int8_t *w8, uint8_t *wt, int N, int K, hipStream_t stream);
 hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream, int wbits = 4);
+// Per-device preparations (LDS allowance) of every instantiation of the tiled kernel, for the current device.
+hipError_t prepare_tiled_kernels();
 // fp16 output from `splits` slabs [M][N] of raw int32 sums (what the tiled kernel writes when PrefillArgs::splits > 1)
 hipError_t launch_splitk_epilogue(const int *part, int splits, const float *s_a, const float *s_w, void *out, int M, int N,
                                   hipStream_t stream);
@@ -107,6 +147,8 @@ hipError_t launch_quantize_weights_clip(const void *w, const float *gamma, const
                                         int K, hipStream_t stream);
 hipError_t launch_silu_mul(const void *gate_up, void *h, int M, int I, hipStream_t stream);
 hipError_t launch_probe_stream_read(const void *src, size_t bytes, unsigned *sink, int workgroups, hipStream_t stream);
+hipError_t launch_probe_read_pattern(const void *src, size_t bytes, unsigned *sink, int pattern, int loads, int workgroups,
+                                     hipStream_t stream);
 hipError_t launch_probe_mfma_i8(int *sink, int workgroups, int iters, int pattern, hipStream_t stream);
 hipError_t launch_silu_mul_quantize(const void *gate_up, int8_t *xq, float *s_a, int M, int I, hipStream_t stream);
 

@@ -38,6 +38,46 @@ __global__ __launch_bounds__(256) void probe_stream_read_kernel(const v4u *__res
     if (acc == 0x9e3779b9u) sink[0] = acc;
 }
 
+// The same reduction with the access pattern, the loads in flight per thread and the load instruction as template
+// arguments, to find the read rate the chip really sustains and the pattern that reaches it:
+//   PATTERN 0: grid-wide stride (all workgroups sweep the buffer together), global loads;
+//           1: every workgroup owns one contiguous run of the buffer, global loads;
+//           2, 3: the patterns 0, 1 with bounds-checked buffer loads (what the weight-streaming kernels use);
+//           4, 5: the patterns 2, 3 with the non-temporal cache policy.
+//   U loads of 16 bytes per thread are issued before the first one is used.
+template <int PATTERN, int U>
+__global__ __launch_bounds__(256) void probe_read_pattern_kernel(const v4u *__restrict__ src, unsigned long long n16,
+                                                                 unsigned *__restrict__ sink) {
+    constexpr bool kOwnRun = (PATTERN & 1) != 0;
+    constexpr bool kBuffer = PATTERN >= 2;
+    constexpr int kAux = PATTERN >= 4 ? 2 : 0;
+    // a workgroup's share: everything (stride = the whole grid) or its own run (stride = the workgroup)
+    const unsigned long long per = (n16 + gridDim.x - 1) / gridDim.x;
+    const unsigned long long begin = kOwnRun ? per * blockIdx.x : 0ull;
+    const unsigned long long end = kOwnRun ? (begin + per < n16 ? begin + per : n16) : n16;
+    const unsigned long long stride = kOwnRun ? 256ull : (unsigned long long)gridDim.x * 256ull;
+    const unsigned long long first = begin + (kOwnRun ? 0ull : (unsigned long long)blockIdx.x * 256ull) + threadIdx.x;
+    // buffer loads address at most 4 GiB from their base: the probe's buffers are smaller
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)src, 0, (unsigned)(n16 * 16ull > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : n16 * 16ull),
+                                          0x00020000);
+    unsigned acc = 0;
+    for (unsigned long long i = first; i < end; i += U * stride) {
+        v4u v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned long long j = i + u * stride;
+            if (kBuffer)
+                v[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, j < end ? (unsigned)(j * 16ull) : 0xFFFFFFF0u, 0, kAux);
+            else
+                v[u] = j < end ? src[j] : v4u{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;
+}
+
 // 8 independent 32x32x32 int8 MFMAs per iteration on register operands (the operand shapes of the large-M kernel:
 // 4 activation-like and 2 weight-like fragments).  pattern 0: small constants; 1: random bytes for the activations and
 // random multiples of 16 for the weights, i.e. what the W4A8 kernel feeds the matrix cores.
@@ -78,6 +118,33 @@ hipError_t launch_probe_stream_read(const void *src, size_t bytes, unsigned *sin
     hipLaunchKernelGGL(probe_stream_read_kernel, dim3(workgroups), dim3(256), 0, stream, (const v4u *)src,
                        (unsigned long long)(bytes / 16), sink);
     return hipGetLastError();
+}
+
+template <int PATTERN>
+static hipError_t launch_read_pattern(const v4u *src, unsigned long long n16, unsigned *sink, int loads, int workgroups,
+                                      hipStream_t stream) {
+    switch (loads) {
+        case 4: hipLaunchKernelGGL((probe_read_pattern_kernel<PATTERN, 4>), dim3(workgroups), dim3(256), 0, stream, src, n16, sink); break;
+        case 8: hipLaunchKernelGGL((probe_read_pattern_kernel<PATTERN, 8>), dim3(workgroups), dim3(256), 0, stream, src, n16, sink); break;
+        case 16: hipLaunchKernelGGL((probe_read_pattern_kernel<PATTERN, 16>), dim3(workgroups), dim3(256), 0, stream, src, n16, sink); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_read_pattern(const void *src, size_t bytes, unsigned *sink, int pattern, int loads, int workgroups,
+                                     hipStream_t stream) {
+    const v4u *s = (const v4u *)src;
+    const unsigned long long n16 = bytes / 16;
+    switch (pattern) {
+        case 0: return launch_read_pattern<0>(s, n16, sink, loads, workgroups, stream);
+        case 1: return launch_read_pattern<1>(s, n16, sink, loads, workgroups, stream);
+        case 2: return launch_read_pattern<2>(s, n16, sink, loads, workgroups, stream);
+        case 3: return launch_read_pattern<3>(s, n16, sink, loads, workgroups, stream);
+        case 4: return launch_read_pattern<4>(s, n16, sink, loads, workgroups, stream);
+        case 5: return launch_read_pattern<5>(s, n16, sink, loads, workgroups, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_probe_mfma_i8(int *sink, int workgroups, int iters, int pattern, hipStream_t stream) {

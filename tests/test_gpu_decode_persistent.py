@@ -1,0 +1,94 @@
+"""GPU parity of the persistent weight-streaming kernel over all its knobs (depth of the weight prefetch, evenly split
+chunks or chunks of 16, wave count, grid, cache policy, activations staged in LDS or read directly): raw int32 sums bit-exact and fp16 within 2^-10 against the CPU oracle, over the row-major and
+over the tiled weight array, for every prefetch depth, both wave counts, both chunkings and the non-temporal loads,
+through the C ABI."""
+import numpy as np
+import pytest
+
+import paper_2311_09550_amd as w4a8
+from paper_2311_09550_amd import synth
+
+from parity import assert_equal_bits, assert_fp16_close
+
+pytestmark = pytest.mark.gpu
+
+EPOCH, EPOCH_T = w4a8.TILING_DECODE_RESIDENT, w4a8.TILING_DECODE_RESIDENT_TILED
+
+
+def variant(grid=0, waves=0, prefetch=0, whole16=False, nt=None, x_direct=False):
+    flags = (1 if whole16 else 0) + (0 if nt is None else 2 if nt else 8) + (4 if x_direct else 0)
+    return grid + 100000 * waves + 10000000 * prefetch + 100000000 * flags
+
+
+def _run(torch, oracle, M, N, K, tiled, var, tag, what, acc_too=True):
+    xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=tag)
+    wp = oracle.pack_w4(wq)
+    acc_o, y32, _ = oracle.gemm(xq, s_a, wp, s_w)
+    dxq, dsa, dsw = torch.from_numpy(xq).cuda(), torch.from_numpy(s_a).cuda(), torch.from_numpy(s_w).cuda()
+    w = torch.from_numpy(wp).cuda()
+    tiling = EPOCH
+    if tiled:
+        w, tiling = w4a8.w4a8_tile_weights(w), EPOCH_T
+    try:
+        out = w4a8.w4a8_gemm_tuned(dxq, dsa, w, dsw, tiling, var, N=N)
+        acc = w4a8.w4a8_gemm_tuned(dxq, None, w, None, tiling, var, want_acc=True, N=N) if acc_too else None
+    except w4a8.W4A8Error as e:
+        if e.code == -7:
+            pytest.skip("the library refuses this variant for this shape (registers or LDS)")
+        raise
+    torch.cuda.synchronize()
+    if acc is not None:
+        assert_equal_bits(acc.cpu().numpy(), acc_o, what + " acc")
+    assert_fp16_close(out.cpu().numpy(), y32, acc_o, what + " out")
+
+
+@pytest.mark.parametrize("tiled", [False, True])
+@pytest.mark.parametrize("M", [1, 3, 8, 16])
+@pytest.mark.parametrize("N,K", [(1, 32), (16, 32), (17, 64), (24, 96), (1000, 128), (1001, 160), (30, 4128), (4096, 1024),
+                                 (8200, 2048), (5120, 5120), (300, 11008), (520, 13824), (40, 16384)])
+def test_persistent_kernel_librarys_choice(gpu, oracle, M, N, K, tiled):
+    _run(gpu, oracle, M, N, K, tiled, 0, 60, f"epoch tiled={tiled} M={M} N={N} K={K}")
+
+
+@pytest.mark.parametrize("tiled", [False, True])
+@pytest.mark.parametrize("M", [17, 24, 32])
+@pytest.mark.parametrize("N,K", [(16, 32), (1001, 160), (520, 5120), (700, 8192)])
+def test_persistent_kernel_two_column_tiles(gpu, oracle, M, N, K, tiled):
+    _run(gpu, oracle, M, N, K, tiled, 0, 61, f"epoch tiled={tiled} M={M} N={N} K={K}")
+
+
+@pytest.mark.parametrize("prefetch", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("waves", [8, 16])
+@pytest.mark.parametrize("grid", [1, 7, 64, 256, 1000])
+@pytest.mark.parametrize("M,N,K", [(1, 5120, 512), (16, 1000, 2080), (9, 1300, 5120), (4, 516, 8192)])
+def test_persistent_kernel_prefetch_wave_and_grid_variants(gpu, oracle, M, N, K, waves, grid, prefetch):
+    """Ranges of 4 .. N channels per workgroup: one-shot walks (no more chunks than the prefetch holds), walks of several
+    epochs that alternate between the two sets of LDS slots, ranges that end in a partial chunk."""
+    if -(-N // grid) > 512:
+        pytest.skip("more than 512 channels per workgroup: outside this kernel's reach")
+    for whole16 in (False, True):
+        _run(gpu, oracle, M, N, K, True, variant(grid, waves, prefetch, whole16), 62,
+             f"epoch {waves}w grid={grid} P={prefetch} whole16={whole16} M={M} N={N} K={K}", acc_too=not whole16)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 700, 2080), (16, 5120, 5120), (5, 130, 13824)])
+def test_persistent_kernel_cache_policies_and_activation_paths(gpu, oracle, M, N, K):
+    for nt in (True, False):
+        for x_direct in (False, True):
+            _run(gpu, oracle, M, N, K, True, variant(nt=nt, x_direct=x_direct), 63,
+                 f"nt={nt} x_direct={x_direct} M={M} N={N} K={K}", acc_too=False)
+    _run(gpu, oracle, M, N, K, True, variant(256, 0, 2, False, True), 63, f"nt P=2 M={M} N={N} K={K}", acc_too=False)
+    _run(gpu, oracle, M, N, K, False, variant(100, 0, 2, False, False, True), 63, f"row-major P=2 direct M={M} N={N} K={K}")
+
+
+def test_persistent_kernel_extreme_codes_at_the_longest_k(gpu, oracle):
+    """All activations -128 and all weights -8 at the longest K the kernel takes with registers to spare: the
+    sixteen-fold sums stay inside int32 (Sec. 5.3) and come back exact."""
+    t = gpu
+    M, N, K = 2, 40, 16384
+    xq = np.full((M, K), -128, np.int8)
+    wq = np.full((N, K), -8, np.int8)
+    wt = w4a8.w4a8_tile_weights(t.from_numpy(oracle.pack_w4(wq)).cuda())
+    acc = w4a8.w4a8_gemm_tuned(t.from_numpy(xq).cuda(), None, wt, None, EPOCH_T, 0, want_acc=True, N=N)
+    t.cuda.synchronize()
+    assert np.all(acc.cpu().numpy() == 128 * 8 * K)

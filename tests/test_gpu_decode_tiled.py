@@ -43,8 +43,8 @@ def test_resident_over_tiled_weights_two_column_tiles(gpu, oracle, M, N, K):
 @pytest.mark.parametrize("waves,grid", [(8, 1), (8, 7), (16, 3), (16, 256), (16, 4096)])
 @pytest.mark.parametrize("M,N,K", [(1, 5120, 512), (16, 1000, 2080), (9, 130, 5120)])
 def test_resident_over_tiled_weights_grid_and_wave_variants(gpu, oracle, M, N, K, waves, grid):
-    if -(-N // grid) > 4096:
-        pytest.skip("more than 4096 channels per workgroup: refused (covered for the row-major array)")
+    if -(-N // grid) > 512:
+        pytest.skip("more than 512 channels per workgroup: refused (covered for the row-major array)")
     _run(gpu, oracle, M, N, K, RESIDENT_T, waves * 100000 + grid, 92, f"resident/tiled {waves}w grid={grid}")
 
 
