@@ -170,8 +170,24 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
                            void *stream);
 
 /*
+ * w4a8_gemm_tiled_splitk for callers that cannot allocate device memory and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
+ * same kernels, same output bits.  The slabs of the K slices live in a scratch array inside the library instead:
+ * W4A8_STATIC_SCRATCH_BYTES of device memory per GPU, present from the moment the library is loaded until the process
+ * ends.  The call allocates and frees nothing (the first call on a device looks up the array's address, as
+ * w4a8_init does).  A shape whose slabs (splits * M * N * 4 bytes, splits being the library's choice or the forced
+ * count) exceed the array is refused with W4A8_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share the
+ * one array: calls that may overlap in time on the same GPU (different streams, different threads) race on it and
+ * must be serialised by the caller; calls on one stream are ordered and safe.  The array's contents carry over from
+ * call to call and are never read before they are rewritten.
+ */
+#define W4A8_STATIC_SCRATCH_BYTES (16u << 20)
+int w4a8_gemm_tiled_splitk_static(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
+                                  int M, int N, int K, int variant, int splits, void *stream);
+
+/*
  * Optional set-up for the current device, once per device and process: asks the runtime for the LDS allowance of
- * every kernel that needs more than the default, so that no
+ * every kernel that needs more than the default and looks up the address of the static scratch array, so that no
  * later call has to (a first launch made under stream capture or from several threads at once is then as plain as
  * any other).  Calls without it do the same on first use, serialised.  Launches nothing, allocates nothing.
  */

@@ -68,6 +68,8 @@ def lib():
         L.w4a8_gemm_tiled_workspace_bytes.argtypes = [i, i, i]
         L.w4a8_gemm_tiled_splitk.restype = i
         L.w4a8_gemm_tiled_splitk.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+        L.w4a8_gemm_tiled_splitk_static.restype = i
+        L.w4a8_gemm_tiled_splitk_static.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp]
         L.w4a8_init.restype = i
         L.w4a8_init.argtypes = []
         L.w4a8_probe_stream_read.restype = i
@@ -387,9 +389,28 @@ def w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, variant: int = 0, splits: int = 0, 
     return out
 
 
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
 def w4a8_init():
-    """Per-device set-up (LDS allowances of the kernels) for torch's current device."""
+    """Per-device set-up (LDS allowances, address of the static scratch array) for torch's current device."""
     _check(lib().w4a8_init())
+
+
+def w4a8_gemm_tiled_splitk_static(xq, s_a, wt, s_w, out, variant: int = 0, splits: int = 0):
+    """w4a8_gemm_tiled_splitk without a workspace argument: the slabs live in the library's static scratch array.
+    `out` (fp16 [M][N]) is the caller's; nothing is allocated here or in the library."""
+    torch = _torch()
+    M, K = xq.shape
+    N = s_w.shape[0]
+    if wt.numel() != w4a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (N, K)")
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    _check(lib().w4a8_gemm_tiled_splitk_static(_dev(xq, torch.int8, "xq"), _dev(s_a, torch.float32, "s_a"),
+                                               _dev(wt, torch.uint8, "wt"), _dev(s_w, torch.float32, "s_w"),
+                                               _dev(out, torch.float16, "out"), M, N, K, variant, splits, _stream()))
+    return out
 
 
 def w4a8_gemm_fine_grained(xq, s_a, wt, s_g, N=None, variant: int = 0, out=None):

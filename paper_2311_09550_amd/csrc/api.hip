@@ -36,6 +36,34 @@ int compute_units() {
     return n;
 }
 
+// Scratch memory of the entry point that allocates nothing (w4a8_gemm_tiled_splitk_static): the slabs of raw sums
+// that the K slices of one GEMM exchange.  One array per GPU, held from the moment the library is loaded until the
+// process ends.  `scratch` is only the host-side name of the symbol; the device address is looked up once per device
+// and every use below goes through that address.
+constexpr size_t kStaticScratchBytes = W4A8_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device (NULL and an error code if the lookup fails).
+int static_scratch(void **ptr) {
+    static void *addr[kMaxDevices];
+    static std::atomic<bool> known[kMaxDevices];
+    static std::mutex lookup_lock;
+    int dev = 0;
+    *ptr = nullptr;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return W4A8_ERR_LAUNCH;
+    if (!known[dev].load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> hold(lookup_lock);
+        if (!known[dev].load(std::memory_order_relaxed)) {
+            void *p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return W4A8_ERR_LAUNCH;
+            addr[dev] = p;
+            known[dev].store(true, std::memory_order_release);
+        }
+    }
+    *ptr = addr[dev];
+    return W4A8_OK;
+}
+
 struct Plan {
     int tiling;
     DecodeShape decode;
@@ -447,7 +475,23 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
                                                                                                     : W4A8_ERR_LAUNCH;
 }
 
+int w4a8_gemm_tiled_splitk_static(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
+                                  int M, int N, int K, int variant, int splits, void *stream) {
+    if (!xq || !s_a || !wt || !s_w || !out_fp16) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(M, N, K)) return e;
+    if (variant < 0 || variant > kTiledTileMax4 || splits < 0 || splits > 64) return W4A8_ERR_ARG;
+    const bool streams_weights = M <= 16 && variant == 0 && splits == 0;  // then no slabs are used at all
+    const SplitPlan pl = plan_split(M, N, K, variant, splits);
+    const size_t need = (streams_weights || pl.splits <= 1) ? 0 : (size_t)pl.splits * (size_t)M * (size_t)N * sizeof(int32_t);
+    if (need > kStaticScratchBytes) return W4A8_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (int e = static_scratch(&ws)) return e;
+    return w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, out_fp16, M, N, K, variant, splits, ws, kStaticScratchBytes, stream);
+}
+
 int w4a8_init(void) {
+    void *ws = nullptr;
+    if (int e = static_scratch(&ws)) return e;
     (void)compute_units();
     if (prepare_tiled_kernels() != hipSuccess || prepare_decode_kernels() != hipSuccess) return W4A8_ERR_LAUNCH;
     return W4A8_OK;
