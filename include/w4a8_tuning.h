@@ -32,7 +32,9 @@ extern "C" {
  *                    2 x 4 waves, 2 = 256 x 256 as 4 x 2 waves, 3 = 128 x 256, 4 = 128 x 160, 5 = 128 x 128,
  *                    6 = 64 x 128, 7 = 64 x 64, 8 = 32 x 128 (the small tiles are for medium M);
  *                    9, 10 = the tiles of 4, 5 run by two sets of waves that split every 128-k stage between
- *                    them and add their integer sums before the epilogue (same bits; never the library's choice).
+ *                    them and add their integer sums before the epilogue (same bits; never the library's choice);
+ *                    11 = 256 x 192 as 4 x 2 waves (the library pairs it with 1 where whole rounds of 256 x 256 tiles
+ *                    leave columns over).
  * Exactly one of out_fp16 / acc_i32 must be non-NULL (s_a and s_w may be NULL
  * when acc_i32 is requested).
  */

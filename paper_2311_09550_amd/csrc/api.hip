@@ -271,6 +271,32 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
     return W4A8_OK;
 }
 
+// The library's own launch of the large-M kernel over tiled int4 weights.  Where 256 x 256 tiles fill the chip more
+// than once, the last, partial round costs as much as a full one (LLaMA-13B gate+up at M = 1024: 432 tiles on 256
+// compute units, i.e. two rounds for 1.69 rounds of work).  Then the columns that whole rounds cover go to one launch
+// and the columns left over to a second launch with 256 x 192 tiles, if those fit into a single round: the second
+// round shrinks to three quarters.  Two launches of the same kernel on disjoint column ranges of the same output:
+// same arithmetic, same bits.
+hipError_t launch_tiled_in_phases(const PrefillArgs &a, bool want_acc, int tile, hipStream_t st) {
+    const int cus = compute_units();
+    const long long tiles_m = (a.M + 255) / 256, cols = (a.N + 255) / 256;
+    const long long per_round = tiles_m > 0 ? cus / tiles_m : 0;  // column tiles of 256 that one round holds
+    if (tile != kTiled256x256 || per_round == 0 || cols <= per_round || cols % per_round == 0)
+        return launch_gemm_prefill_tiled(a, want_acc, tile, st);
+    const long long n_first = (cols / per_round) * per_round * 256;     // covered by whole rounds
+    const long long rest = a.N - n_first;
+    if ((rest + 191) / 192 > per_round) return launch_gemm_prefill_tiled(a, want_acc, tile, st);  // 192 wide would need two rounds too
+    PrefillArgs first = a, second = a;
+    first.N = (int)n_first;
+    second.N = (int)rest;
+    second.wp = a.wp + (size_t)(n_first / 32) * (size_t)((a.K + kTiledBlockK - 1) / kTiledBlockK) * (size_t)kTiledBlockBytes;
+    if (a.s_w) second.s_w = a.s_w + n_first;
+    if (a.out) second.out = (unsigned short *)a.out + n_first;
+    if (a.acc_out) second.acc_out = a.acc_out + n_first;
+    if (const hipError_t e = launch_gemm_prefill_tiled(first, want_acc, kTiled256x256, st); e != hipSuccess) return e;
+    return launch_gemm_prefill_tiled(second, want_acc, kTiled256x192, st);
+}
+
 int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w, void *out_fp16, int32_t *acc_i32,
              int M, int N, int K, int tiling, int variant, void *stream) {
     const bool want_acc = acc_i32 != nullptr;
@@ -291,7 +317,8 @@ int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float 
         a.xq = xq; a.s_a = s_a; a.wp = wp; a.s_w = s_w;
         a.out = out_fp16; a.acc_out = acc_i32;
         a.M = M; a.N = N; a.K = K; a.ldc = N;
-        err = launch_gemm_prefill_tiled(a, want_acc, pl.prefill_tile, st);
+        err = variant == 0 ? launch_tiled_in_phases(a, want_acc, pl.prefill_tile, st)
+                           : launch_gemm_prefill_tiled(a, want_acc, pl.prefill_tile, st);
     } else if (pl.tiling != W4A8_TILING_PREFILL) {
         DecodeArgs a{};
         a.xq = xq; a.s_a = s_a; a.wp = wp; a.s_w = s_w;
@@ -418,8 +445,8 @@ SplitPlan plan_split(int M, int N, int K, int variant, int splits) {
     }
     int s = splits;
     if (s == 0) {
-        static const int bm[] = {0, 256, 256, 128, 128, 128, 64, 64, 32, 128, 128};
-        static const int bn[] = {0, 256, 256, 256, 160, 128, 128, 64, 128, 160, 128};
+        static const int bm[] = {0, 256, 256, 128, 128, 128, 64, 64, 32, 128, 128, 256};
+        static const int bn[] = {0, 256, 256, 256, 160, 128, 128, 64, 128, 160, 128, 192};
         const long long tiles = count(bm[pl.tile], bn[pl.tile]);
         s = 1;
         if (M <= 512 && tiles <= (long_k ? cus : cus / 2)) {
@@ -461,7 +488,9 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
     a.M = M; a.N = N; a.K = K; a.ldc = N;
     if (pl.splits <= 1) {
         a.out = out_fp16;
-        return launch_gemm_prefill_tiled(a, false, pl.tile, st) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+        const hipError_t e = variant == 0 ? launch_tiled_in_phases(a, false, pl.tile, st)
+                                          : launch_gemm_prefill_tiled(a, false, pl.tile, st);
+        return e == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
     }
     // one launch must cover the problem (slabs are whole M x N matrices)
     if ((long long)M * K > 0xF0000000ll || (long long)tiled_weight_bytes(N, K, 4) > 0xF0000000ll) return W4A8_ERR_SHAPE;

@@ -137,6 +137,11 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
     constexpr int kSpare = STAGES * (A_STAGE + B_STAGE);  // 1 KB that absorbs the surplus loads of an uneven split
     constexpr int kScaleBase = kSpare + 1024;             // FG: per ring slot and wave, 32 NTW group scales
     constexpr int kScaleWave = NTW * 128;
+    // behind everything else: the tile's s_a and s_w for the epilogue (see below); mirrors launch_one's layout
+    constexpr int kRingBytes = STAGES * (A_STAGE + B_STAGE) + 1024 + (FG ? STAGES * kOutWaves * NTW * 128 + 1024 : 0);
+    constexpr int kMeetBytes = KS == 2 ? kOutWaves * (32 * (64 * NTW + 16) + MTW * NTW * 16 * 256) : 0;
+    constexpr int kEpiScales = kRingBytes > kMeetBytes ? kRingBytes : kMeetBytes;
+    static_assert(kWaves * 64 >= BM && kWaves * 64 >= BN, "one thread per row and per channel of the tile");
     static_assert(STAGES >= 2 && (STAGES - 1) * kLoads < 64, "outstanding loads must fit the counter");
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
@@ -160,6 +165,15 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
     const int tile_m = logical - tile_n * p.tiles_m;
     const int bm0 = tile_m * BM;
     const int bn0 = tile_n * BN;
+
+    // The epilogue needs s_a of the tile's rows and s_w of its channels.  Fetched there, each of its passes would
+    // start with a trip to memory (measured: 5 to 10 us of epilogue per tile).  So they are requested here, ahead of
+    // everything, ride in two registers through the main loop and are parked in LDS when the ring has gone idle.
+    float sa_mine = 0.f, sw_mine = 0.f;
+    if (!ACC_OUT) {
+        if (tid < BM && bm0 + tid < p.M) sa_mine = p.s_a[bm0 + tid];
+        if (!FG && tid < BN && bn0 + tid < p.N) sw_mine = p.s_w[bn0 + tid];
+    }
 
     // Split of K across workgroups (p.splits > 1, raw sums only): blockIdx.y takes the stages
     // [st_begin, st_begin + st_total) and writes its partial sums to its own M x ldc slab of acc_out.
@@ -446,6 +460,21 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
     }
     wait_vmcnt<0>();
 
+    // The ring is idle: the last barrier of the loop lies behind every wave's last fragment read and every load has
+    // landed.  Park the scales behind it; the barrier that makes them visible is the one of the k halves' meeting
+    // where there is one.
+    float *const sa_lds = (float *)(lds + kEpiScales);
+    float *const sw_lds = sa_lds + BM;
+    if (!ACC_OUT) {
+        if (tid < BM) sa_lds[tid] = sa_mine;
+        if (tid < BN) sw_lds[tid] = sw_mine;
+        if constexpr (KS == 1) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        }
+    }
+
     if constexpr (KS == 2) {
         // The two k halves meet: the ring is idle (the last barrier lies behind every wave's last fragment read and
         // every load has landed), the upper set parks its sums behind the area the epilogue's slabs will use and leaves.
@@ -497,25 +526,14 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt) {
             const int m_slab = bm0 + wm * (32 * MTW) + 32 * mt;
-            const int m = m_slab + idx;
-            const float sa = m < p.M ? p.s_a[m] : 0.f;
+            const float sa = sa_lds[wm * (32 * MTW) + 32 * mt + idx];  // 0 for rows past M
 #pragma unroll
             for (int t = 0; t < NTW; ++t) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int nl = 32 * t + 8 * q + 4 * g;
-                    const int n = n_wave + nl;
-                    float4 sw = float4{0.f, 0.f, 0.f, 0.f};
-                    if constexpr (FG) {
-                    } else if (n + 3 < p.N) {
-                        sw = *(const float4 *)(p.s_w + n);
-                    } else {  // values past N are formed but never stored; keep their scale reads in bounds
-                        const int last = p.N - 1;
-                        sw.x = p.s_w[n < last ? n : last];
-                        sw.y = p.s_w[n + 1 < last ? n + 1 : last];
-                        sw.z = p.s_w[n + 2 < last ? n + 2 : last];
-                        sw.w = p.s_w[last];
-                    }
+                    // channels past N carry scale 0: their values are formed but never stored
+                    const float4 sw = FG ? float4{0.f, 0.f, 0.f, 0.f} : *(const float4 *)(sw_lds + wn * (32 * NTW) + nl);
                     v2u o;
                     o.x = pack_f16x2(value(mt, t, 4 * q, sa, sw.x), value(mt, t, 4 * q + 1, sa, sw.y));
                     o.y = pack_f16x2(value(mt, t, 4 * q + 2, sa, sw.z), value(mt, t, 4 * q + 3, sa, sw.w));
@@ -550,7 +568,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
     for (int mt = 0; mt < MTW; ++mt) {
         const int m = bm0 + wm * (32 * MTW) + 32 * mt + idx;
         if (m >= p.M) continue;
-        const float sa = ACC_OUT ? 0.f : p.s_a[m];
+        const float sa = ACC_OUT ? 0.f : sa_lds[wm * (32 * MTW) + 32 * mt + idx];
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
 #pragma unroll
@@ -573,7 +591,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
                 } else {
                     unsigned short *dst = (unsigned short *)p.out + (size_t)m * p.ldc + n;
                     if (vec_ok && n + 3 < p.N) {
-                        const float4 sw = FG ? float4{0.f, 0.f, 0.f, 0.f} : *(const float4 *)(p.s_w + n);
+                        const float4 sw = FG ? float4{0.f, 0.f, 0.f, 0.f} : *(const float4 *)(sw_lds + (n - bn0));
                         v2u o;
                         o.x = pack_f16x2(value(mt, t, 4 * q, sa, sw.x), value(mt, t, 4 * q + 1, sa, sw.y));
                         o.y = pack_f16x2(value(mt, t, 4 * q + 2, sa, sw.z), value(mt, t, 4 * q + 3, sa, sw.w));
@@ -582,7 +600,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
                             if (n + j < p.N)
-                                dst[j] = f32_to_f16_bits(value(mt, t, 4 * q + j, sa, FG ? 0.f : p.s_w[n + j]));
+                                dst[j] = f32_to_f16_bits(value(mt, t, 4 * q + j, sa, FG ? 0.f : sw_lds[n + j - bn0]));
                     }
                 }
             }
@@ -599,7 +617,7 @@ hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     constexpr int kRing = STAGES * (BM * 128 + BN * 16 * WBITS) + 1024 + (FG ? STAGES * WM * WN * NTW * 128 + 1024 : 0);
     // k split: the epilogue's slabs and, behind them, the parked sums of the upper wave set
     constexpr int kMeet = KS == 2 ? WM * WN * (32 * (64 * NTW + 16) + MTW * NTW * 16 * 256) : 0;
-    constexpr int kLdsBytes = kRing > kMeet ? kRing : kMeet;
+    constexpr int kLdsBytes = (kRing > kMeet ? kRing : kMeet) + (BM + BN) * 4;  // + the epilogue's s_a and s_w
     static_assert(kLdsBytes <= 160 * 1024, "a workgroup's ring must fit the compute unit's LDS");
     constexpr auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS, FG, KS>;
     if (const hipError_t e = allow_lds<kernel>(kLdsBytes); e != hipSuccess) return e;
@@ -694,7 +712,7 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
         return hipErrorInvalidValue;
     long long m_rows = kMaxBytes / p.K, n_rows = kMaxBytes / (kb_total * (block_bytes / 32));
     m_rows -= m_rows % 256;
-    n_rows -= n_rows % 1280;  // a multiple of every tile width
+    n_rows -= n_rows % 3840;  // a multiple of every tile width
     for (long long n0 = 0; n0 < p.N; n0 += n_rows) {
         for (long long m0 = 0; m0 < p.M; m0 += m_rows) {
             PrefillArgs q = p;
@@ -720,6 +738,7 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
                     case kTiled32x128: e = launch_tile<1, 1, 1, 4, 4>(q, acc_out, stream); break;
                     case kTiled128x160K2: e = launch_tile<1, 5, 4, 1, 3, 4, false, false, 2>(q, acc_out, stream); break;
                     case kTiled128x128K2: e = launch_tile<2, 2, 2, 2, 3, 4, false, false, 2>(q, acc_out, stream); break;
+                    case kTiled256x192: e = launch_tile<2, 3, 4, 2, 3>(q, acc_out, stream); break;
                     default: e = hipErrorInvalidConfiguration;
                 }
             } else if (wbits == 8) {

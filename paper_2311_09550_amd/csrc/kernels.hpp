@@ -112,8 +112,10 @@ constexpr int kTiled64x64 = 7;          // 4 waves of 32 x 32
 constexpr int kTiled32x128 = 8;         // 4 waves of 32 x 32 side by side
 constexpr int kTiled128x160K2 = 9;      // 128 x 160 with two wave sets of 4 splitting each stage's k (int4 weights only)
 constexpr int kTiled128x128K2 = 10;     // 128 x 128 likewise
+constexpr int kTiled256x192 = 11;       // 8 waves of 64 x 96 (int4 weights only): the narrower partner of 1 for the columns
+                                        // that whole rounds of 256 x 256 tiles leave over
 constexpr int kTiledTileMax = 8;        // tiles every weight format has
-constexpr int kTiledTileMax4 = 10;      // tiles of the signed int4 format
+constexpr int kTiledTileMax4 = 11;      // tiles of the signed int4 format
 
 // wbits = 4: packed int4 codes (blocks of 2 KB); wbits = 8: int8 codes of the W8A8 comparison variant (blocks of 4 KB);
 // wbits = kWeightsUnsigned4: the 2 KB blocks with unsigned nibbles u = w + 8 (the paper's vanilla storage, GEMM only)
