@@ -70,6 +70,8 @@ def lib():
         L.w4a8_gemm_tiled_splitk.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
         L.w4a8_gemm_tiled_splitk_static.restype = i
         L.w4a8_gemm_tiled_splitk_static.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp]
+        L.w4a8_linear_tiled_fp16.restype = i
+        L.w4a8_linear_tiled_fp16.argtypes = [vp, ctypes.c_longlong, vp, vp, vp, vp, i, i, i, vp]
         L.w4a8_init.restype = i
         L.w4a8_init.argtypes = []
         L.w4a8_probe_stream_read.restype = i
@@ -386,6 +388,28 @@ def w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, variant: int = 0, splits: int = 0, 
     _check(lib().w4a8_gemm_tiled_splitk(_dev(xq, torch.int8, "xq"), _dev(s_a, torch.float32, "s_a"), _dev(wt, torch.uint8, "wt"),
                                         _dev(s_w, torch.float32, "s_w"), _dev(out, torch.float16, "out"), M, N, K, variant,
                                         splits, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
+    return out
+
+
+def w4a8_linear_tiled_fp16(x, wt, s_w, out=None, s_a_out=None):
+    """fp16 [M][K] view (unit column stride, rows x.stride(0) apart), tiled weights, fp32 [N] -> fp16 [M][N]: per-token
+    quantisation and W4A8 GEMM in one launch (M <= 16, K <= 8192).  s_a_out (fp32 [M]) also receives the scales."""
+    torch = _torch()
+    M, K = x.shape
+    N = s_w.shape[0]
+    if not (x.is_cuda and x.dtype == torch.float16 and x.stride(1) == 1):
+        raise TypeError("x: expected a device fp16 view with unit column stride")
+    if wt.numel() != w4a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (N, K)")
+    out = torch.empty((M, N), dtype=torch.float16, device=x.device) if out is None else out
+    if out.shape != (M, N):
+        raise ValueError("out shape mismatch")
+    if s_a_out is not None and tuple(s_a_out.shape) != (M,):
+        raise ValueError("s_a_out shape mismatch")
+    _check(lib().w4a8_linear_tiled_fp16(ctypes.c_void_p(x.data_ptr()), x.stride(0), _dev(wt, torch.uint8, "wt"),
+                                        _dev(s_w, torch.float32, "s_w"), _dev(out, torch.float16, "out"),
+                                        None if s_a_out is None else _dev(s_a_out, torch.float32, "s_a_out"), M, N, K,
+                                        _stream()))
     return out
 
 

@@ -89,6 +89,7 @@ bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool
     DecodeShape s{};
     s.resident = true;
     s.tiled = tiled;
+    s.fused_quant = out->fused_quant;  // set by the caller that wants the kernel to quantise its own activations
     s.aux = aux < 0 ? 2 : aux;
     if (waves == 0) waves = (mt == 1 && ks_total <= 64) ? 8 : 16;
     s.waves = waves;
@@ -502,6 +503,28 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
     if (launch_gemm_prefill_tiled(a, true, pl.tile, st) != hipSuccess) return W4A8_ERR_LAUNCH;
     return launch_splitk_epilogue(a.acc_out, pl.splits, s_a, s_w, out_fp16, M, N, st) == hipSuccess ? W4A8_OK
                                                                                                     : W4A8_ERR_LAUNCH;
+}
+
+int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16,
+                           float *s_a_out, int M, int N, int K, void *stream) {
+    if (!x_fp16 || !wt || !s_w || !out_fp16) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(M, N, K)) return e;
+    if (ldx < K || (ldx & 7) != 0) return W4A8_ERR_SHAPE;  // rows must not overlap and must start 16-byte aligned
+    if (misaligned(x_fp16) || misaligned(wt) || misaligned(out_fp16) || misaligned(s_w)) return W4A8_ERR_ALIGN;
+    if (M > 16) return W4A8_ERR_ARG;
+    if (((unsigned long long)(M - 1) * (unsigned long long)ldx + (unsigned long long)K) * 2ull > 0xFFFF0000ull) return W4A8_ERR_SHAPE;
+    DecodeShape shape{};
+    shape.fused_quant = true;
+    if (!resident_shape(M, N, K, 8, 0, 0, false, -1, true, &shape)) return W4A8_ERR_ARG;
+    DecodeArgs a{};
+    a.x16 = static_cast<const uint16_t *>(x_fp16);
+    a.ldx = ldx;
+    a.s_a_out = s_a_out;
+    a.wp = wt; a.s_w = s_w; a.out = out_fp16;
+    a.M = M; a.N = N; a.K = K;
+    a.rows_per_wg = shape.rows_per_wg;
+    a.chunk_rows = shape.chunk_rows;
+    return launch_gemm_decode(a, false, shape, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
 }
 
 int w4a8_gemm_tiled_splitk_static(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,

@@ -92,4 +92,66 @@ __device__ __forceinline__ unsigned pack_f16x2(float lo, float hi) {
     return (unsigned)f32_to_f16_bits(lo) | ((unsigned)f32_to_f16_bits(hi) << 16);
 }
 
+// ---- per-token / per-channel symmetric quantisation, shared by the row-wise quantisers and by the
+// token-generation GEMM that quantises its own activations
+
+__device__ __forceinline__ float half_bits_to_float(unsigned short h) { return __half2float(__ushort_as_half(h)); }
+__device__ __forceinline__ float lo_half(unsigned w) { return half_bits_to_float((unsigned short)(w & 0xFFFFu)); }
+__device__ __forceinline__ float hi_half(unsigned w) { return half_bits_to_float((unsigned short)(w >> 16)); }
+
+// absolute maximum of eight fp16 values held in four words
+__device__ __forceinline__ float absmax8(v4u c, float m) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        m = fmaxf(m, fabsf(lo_half(c[j])));
+        m = fmaxf(m, fabsf(hi_half(c[j])));
+    }
+    return m;
+}
+
+// Symmetric quantisation of one row (Eq. (2) with zero point 0): code = clamp(rne(fl32(x / scale)), lo, hi).
+//
+// The definition divides.  A correctly rounded fp32 division costs about ten instructions, so the common case
+// takes a shortcut that provably gives the same integer: with r = fl32(1/scale) and q' = fl32(x * r),
+// |q' - x/scale| <= |x/scale| * (2^-23 + 2^-48) < 1.6e-5 for |x/scale| <= 128, and the definition's quotient
+// fl32(x/scale) lies within 3.9e-6 of x/scale.  So when q' is at least 1e-4 away from the nearest half-integer,
+// both quotients round to the same integer; otherwise (about 2 in 10^4 elements, or rows whose quotients are
+// exact halves) the eight values of the chunk are redone with the division.
+struct RowQuantizer {
+    float scale, recip, lo, hi;
+    __device__ __forceinline__ RowQuantizer(float amax, float qmax, float lo_, float hi_) : lo(lo_), hi(hi_) {
+        scale = __fdiv_rn(amax, qmax);
+        recip = __fdiv_rn(1.0f, scale);  // unused when amax == 0
+    }
+    __device__ __forceinline__ void codes8(const float (&x)[8], int (&q)[8]) const {
+        bool near_tie = false;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float qp = x[j] * recip;
+            const float n = rintf(qp);
+            near_tie |= fabsf(qp - n) > 0.5f - 1e-4f;
+            q[j] = (int)fminf(fmaxf(n, lo), hi);
+        }
+        if (near_tie) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = (int)fminf(fmaxf(rintf(__fdiv_rn(x[j], scale)), lo), hi);
+        }
+    }
+};
+
+__device__ __forceinline__ void halves8(v4u v, float (&x)[8]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        x[2 * j] = lo_half(v[j]);
+        x[2 * j + 1] = hi_half(v[j]);
+    }
+}
+
+__device__ __forceinline__ v2u pack_i8x8(const int (&q)[8]) {
+    v2u o;
+    o.x = (q[0] & 255) | ((q[1] & 255) << 8) | ((q[2] & 255) << 16) | ((unsigned)(q[3] & 255) << 24);
+    o.y = (q[4] & 255) | ((q[5] & 255) << 8) | ((q[6] & 255) << 16) | ((unsigned)(q[7] & 255) << 24);
+    return o;
+}
+
 }  // namespace w4a8

@@ -114,6 +114,7 @@ __device__ __forceinline__ void lds_barrier() {
 // AUX: cache-policy bits of the weight loads (0 = default, 2 = non-temporal: weights are read once per launch and
 // should not displace anything; measured 5 to 10 % faster, and a plain read probe gains 30 % from it).
 constexpr int kEpochScaleBytes = 4 * kResidentMaxRows;
+constexpr int kEpochAmaxBytes = 1024;  // 16 waves x 16 rows of fp32
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
@@ -124,11 +125,18 @@ __device__ __forceinline__ void wait_vmcnt_at_most() {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX>
+// FQ: the kernel is handed fp16 activations (p.x16, rows p.ldx apart) and quantises them per token itself, exactly as
+// quantize_act_kernel would (Sec. 3 "per token"; Eq. (2), z = 0): every wave fetches the k steps it multiplies, the
+// waves exchange their row maxima through LDS, and each lane then quantises its own 32 XS values with the row's
+// scale.  One launch instead of two for a linear at token-generation sizes (the kind of fusion across operators
+// the paper's engine relies on, Sec. 6.1).  M <= 16 only.
+template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(DecodeArgs p) {
+    static_assert(!FQ || (MT == 1 && !ACC_OUT), "the fused quantiser serves one column tile and the fp16 output");
     extern __shared__ __attribute__((aligned(16))) uint8_t epoch_lds[];
     float *sw_lds = (float *)epoch_lds;
-    v4i *part = (v4i *)(epoch_lds + kEpochScaleBytes);  // [set][q][mt][wave][lane]
+    float *amax_lds = (float *)(epoch_lds + kEpochScaleBytes);  // FQ: [wave][16] row maxima of the waves' k steps
+    v4i *part = (v4i *)(epoch_lds + kEpochScaleBytes + kEpochAmaxBytes);  // [set][q][mt][wave][lane]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -162,8 +170,23 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     // lanes fetch the same row.  So, when they fit, the workgroup copies the M rows into LDS once with LDS-direct
     // loads of whole 1 KB pieces (p.x_lds_pitch > 0) and every wave picks its operands from there.
     v4u xraw[XS][MT][2];
-    const int pitch = p.x_lds_pitch;
-    if (pitch > 0) {
+    v4u xhalf[FQ ? XS : 1][4];  // FQ: the lane's 32 fp16 values of each of its k steps
+    const int pitch = FQ ? 0 : p.x_lds_pitch;
+    if constexpr (FQ) {
+        // rows past M are not fetched (an offset beyond the buffer returns zeros): they meet real weights, but what
+        // they produce lands in output columns that are never stored
+        const unsigned long long x_bytes = ((unsigned long long)(p.M - 1) * (unsigned long long)p.ldx + (unsigned long long)p.K) * 2ull;
+        const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.x16, 0, (unsigned)x_bytes, 0x00020000);
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            const unsigned at = (live[i] && r < p.M)
+                                    ? (unsigned)(((unsigned long long)r * (unsigned long long)p.ldx + (unsigned)(k_step(i) * 128 + 32 * g)) * 2ull)
+                                    : kNowhere;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xhalf[i][j] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, at >= kNowhere ? kNowhere : at + 16 * j, 0, 0);
+        }
+    } else if (pitch > 0) {
         const v4i x_rsrc = [&] {
             const unsigned long long b = (unsigned long long)p.xq;
             v4i r;
@@ -206,8 +229,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     float sa[MT];
     if (!ACC_OUT) {
         if (tid < n_sw) sw_first = p.s_w[row0 + tid];
+        if constexpr (!FQ) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) sa[mt] = p.s_a[min(16 * mt + r, p.M - 1)];
+            for (int mt = 0; mt < MT; ++mt) sa[mt] = p.s_a[min(16 * mt + r, p.M - 1)];
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -239,7 +264,43 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
         for (int i = 0; i < XS; ++i) wreg[q][i] = w_load(row, w_off[i]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (pitch > 0) {
+    if constexpr (FQ) {
+        // row maxima: over the lane's values, over the four K groups of the row (lanes r, r + 16, r + 32, r + 48), over
+        // the waves (through LDS); every lane of row r ends up with the maximum of the whole row
+        float amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < XS; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) amax = absmax8(xhalf[i][j], amax);
+        amax = fmaxf(amax, __shfl_xor(amax, 16, 64));
+        amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+        if (g == 0) amax_lds[wave * 16 + r] = amax;
+        if (tid < n_sw) sw_lds[tid] = sw_first;
+        lds_barrier();
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) amax = fmaxf(amax, amax_lds[w * 16 + r]);
+        const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
+        sa[0] = rq.scale;  // amax == 0 gives scale 0
+        if (p.s_a_out != nullptr && blockIdx.x == 0 && wave == 0 && g == 0 && r < p.M) p.s_a_out[r] = rq.scale;
+        const bool zero_row = amax == 0.f;
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            v2u codes[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                codes[j] = v2u{0u, 0u};
+                if (!zero_row) {
+                    float xf[8];
+                    int q8[8];
+                    halves8(xhalf[i][j], xf);
+                    rq.codes8(xf, q8);
+                    codes[j] = pack_i8x8(q8);
+                }
+            }
+            xraw[i][0][0] = v4u{codes[0].x, codes[0].y, codes[1].x, codes[1].y};
+            xraw[i][0][1] = v4u{codes[2].x, codes[2].y, codes[3].x, codes[3].y};
+        }
+    } else if (pitch > 0) {
         // The copy, and the scales behind it, are in once at most the P XS weight loads issued after them are
         // outstanding (loads return in order).  The compiler does not know of the copy, so the wait is spelled out;
         // the scales are parked in LDS behind it, where the compiler's own wait for them is already satisfied.
@@ -465,14 +526,14 @@ constexpr bool epoch_fits(int mt, int xs, int prefetch, int waves) {
 }
 
 constexpr int epoch_lds_bytes(int mt, int prefetch, int waves, int sets) {
-    return kEpochScaleBytes + sets * prefetch * mt * waves * 1024;
+    return kEpochScaleBytes + kEpochAmaxBytes + sets * prefetch * mt * waves * 1024;
 }
 
 constexpr int kCuLdsBytes = 160 * 1024;
 
-template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX>
+template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false>
 static hipError_t launch_epoch_one(const DecodeArgs &p, int grid, int sets, bool prepare_only, hipStream_t stream) {
-    constexpr auto kernel = gemm_decode_resident_kernel<MT, XS, P, WAVES, ACC_OUT, TILED, AUX>;
+    constexpr auto kernel = gemm_decode_resident_kernel<MT, XS, P, WAVES, ACC_OUT, TILED, AUX, FQ>;
     static_assert(epoch_lds_bytes(MT, P, WAVES, 2) <= kCuLdsBytes, "both sets of slots must fit the compute unit's LDS");
     if (const hipError_t e = allow_lds<kernel>(kCuLdsBytes); e != hipSuccess) return e;
     if (prepare_only) return hipSuccess;
@@ -484,7 +545,7 @@ static hipError_t launch_epoch_one(const DecodeArgs &p, int grid, int sets, bool
     const long long pitch = ((p.K + 1023) / 1024) * 1024 + 16;
     a.x_lds_pitch = 0;
     a.x_lds_offset = 0;
-    if (p.x_lds_pitch >= 0 && lds + pitch * p.M <= kCuLdsBytes) {
+    if (!FQ && p.x_lds_pitch >= 0 && lds + pitch * p.M <= kCuLdsBytes) {
         a.x_lds_pitch = (int)pitch;
         a.x_lds_offset = lds;
         lds += (int)(pitch * p.M);
@@ -493,10 +554,27 @@ static hipError_t launch_epoch_one(const DecodeArgs &p, int grid, int sets, bool
     return hipGetLastError();
 }
 
+// The fused quantiser holds a lane's 32 XS fp16 values (16 XS registers) until the row maxima are known.
+constexpr bool fused_quant_fits(int mt, int xs, int prefetch, int waves) {
+    return mt == 1 && waves == 8 && 4 * prefetch * xs + 16 * xs + 8 * xs + 45 <= 270;
+}
+
 template <int MT, int XS, int P, int WAVES>
-static hipError_t launch_epoch_p(const DecodeArgs &p, bool acc_out, bool tiled, int aux, int grid, int sets, bool prepare_only,
-                                 hipStream_t stream) {
+static hipError_t launch_epoch_p(const DecodeArgs &p, bool acc_out, bool tiled, int aux, bool fq, int grid, int sets,
+                                 bool prepare_only, hipStream_t stream) {
     if constexpr (epoch_fits(MT, XS, P, WAVES)) {
+        if constexpr (fused_quant_fits(MT, XS, P, WAVES)) {
+            if (prepare_only) {
+                if (const hipError_t e = launch_epoch_one<MT, XS, P, WAVES, false, true, 2, true>(p, grid, sets, true, stream);
+                    e != hipSuccess)
+                    return e;
+            } else if (fq) {
+                return (tiled && !acc_out) ? launch_epoch_one<MT, XS, P, WAVES, false, true, 2, true>(p, grid, sets, false, stream)
+                                           : hipErrorInvalidConfiguration;
+            }
+        } else if (fq && !prepare_only) {
+            return hipErrorInvalidConfiguration;
+        }
         // Non-temporal weight loads everywhere; the default cache policy is kept, for measurements, on the path the
         // benchmarks time (tiled weights, fp16 output) and ignored elsewhere.
         if (prepare_only) {  // every variant of the shape
@@ -522,19 +600,19 @@ template <int MT, int XS, int WAVES>
 static hipError_t launch_epoch_xs(const DecodeArgs &p, bool acc_out, const DecodeShape &s, int grid, int sets, bool prepare_only,
                                   hipStream_t stream) {
     if (prepare_only) {
-        hipError_t e = launch_epoch_p<MT, XS, 1, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, true, stream);
-        if (e == hipSuccess) e = launch_epoch_p<MT, XS, 2, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, true, stream);
-        if (e == hipSuccess) e = launch_epoch_p<MT, XS, 3, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, true, stream);
-        if (e == hipSuccess) e = launch_epoch_p<MT, XS, 4, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, true, stream);
-        if (e == hipSuccess) e = launch_epoch_p<MT, XS, 8, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, true, stream);
+        hipError_t e = launch_epoch_p<MT, XS, 1, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, true, stream);
+        if (e == hipSuccess) e = launch_epoch_p<MT, XS, 2, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, true, stream);
+        if (e == hipSuccess) e = launch_epoch_p<MT, XS, 3, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, true, stream);
+        if (e == hipSuccess) e = launch_epoch_p<MT, XS, 4, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, true, stream);
+        if (e == hipSuccess) e = launch_epoch_p<MT, XS, 8, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, true, stream);
         return e;
     }
     switch (s.prefetch) {
-        case 1: return launch_epoch_p<MT, XS, 1, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, false, stream);
-        case 2: return launch_epoch_p<MT, XS, 2, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, false, stream);
-        case 3: return launch_epoch_p<MT, XS, 3, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, false, stream);
-        case 4: return launch_epoch_p<MT, XS, 4, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, false, stream);
-        case 8: return launch_epoch_p<MT, XS, 8, WAVES>(p, acc_out, s.tiled, s.aux, grid, sets, false, stream);
+        case 1: return launch_epoch_p<MT, XS, 1, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, false, stream);
+        case 2: return launch_epoch_p<MT, XS, 2, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, false, stream);
+        case 3: return launch_epoch_p<MT, XS, 3, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, false, stream);
+        case 4: return launch_epoch_p<MT, XS, 4, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, false, stream);
+        case 8: return launch_epoch_p<MT, XS, 8, WAVES>(p, acc_out, s.tiled, s.aux, s.fused_quant, grid, sets, false, stream);
         default: return hipErrorInvalidConfiguration;
     }
 }
@@ -577,6 +655,7 @@ static bool epoch_supported(int mt, const DecodeShape &s) {
     if (s.rows_per_wg > kResidentMaxRows) return false;
     if (s.x_steps < 1 || s.x_steps > 8) return false;
     if (mt == 2 && (s.waves != 16 || s.x_steps > 4)) return false;
+    if (s.fused_quant && !(s.tiled && fused_quant_fits(mt, s.x_steps, s.prefetch, s.waves))) return false;
     return epoch_fits(mt, s.x_steps, s.prefetch, s.waves);
 }
 

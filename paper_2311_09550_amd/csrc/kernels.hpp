@@ -33,6 +33,9 @@ inline hipError_t allow_lds(int bytes) {
 }
 
 struct DecodeArgs {
+    const uint16_t *x16; // fused-quantiser form only: fp16 activations, rows ldx elements apart (xq, s_a unused)
+    long long ldx;
+    float *s_a_out;      // fused-quantiser form only: where the per-token scales are also written, or NULL
     const int8_t *xq;    // [M][K]
     const float *s_a;    // [M]     (unused when the raw sums are requested)
     const uint8_t *wp;   // [N][K/2]
@@ -56,6 +59,7 @@ struct DecodeShape {
     int chunk_rows; // resident: channels per chunk (4, 8, 12 or 16)
     int aux;        // resident: cache-policy bits of the weight loads (0 or 2 = non-temporal)
     bool x_direct;  // resident: never stage the activations in LDS (they are staged when they fit, otherwise)
+    bool fused_quant;  // resident: the kernel quantises fp16 activations itself (M <= 16, 8 waves, tiled weights)
     int waves;      // waves per workgroup: resident 8 or 16, streaming 4 or 8
     int x_steps;    // resident: k steps per wave = ceil(ceil(K/128) / waves)
     int rows_per_wg;  // resident: output channels per persistent workgroup, a multiple of 4, at most kResidentMaxRows

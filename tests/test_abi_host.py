@@ -99,7 +99,20 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_silu_mul(p, p, 1, 12, null) == -2
     assert L.w4a8_silu_mul_quantize(p, null, p, 1, 32, null) == -1
     assert L.w4a8_silu_mul_quantize(p, p, p, 1, 24, null) == -2
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 4, 11, p, big, null) == -7      # tiled layout: unknown tile id
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 4, 12, p, big, null) == -7      # tiled layout: unknown tile id
+    f = L.w4a8_linear_tiled_fp16
+    assert f(null, 1024, p, p, p, null, 1, 16, 1024, null) == -1
+    assert f(p, 1024, p, p, null, null, 1, 16, 1024, null) == -1
+    assert f(p, 1000, p, p, p, null, 1, 16, 1024, null) == -2                   # rows would overlap
+    assert f(p, 1028, p, p, p, null, 1, 16, 1024, null) == -2                   # rows not 16-byte aligned
+    assert f(odd, 1024, p, p, p, null, 1, 16, 1024, null) == -3
+    assert f(p, 1024, p, p, p, null, 17, 16, 1024, null) == -7                  # M beyond token generation
+    assert f(p, 16384, p, p, p, null, 4, 16, 16384, null) == -7                 # K beyond what a wave can hold
+    g2 = L.w4a8_gemm_tiled_splitk_static
+    assert g2(null, p, p, p, p, 64, 512, 1024, 0, 0, null) == -1
+    assert g2(p, p, p, p, p, 64, 512, 1000, 0, 0, null) == -2
+    assert g2(p, p, p, p, p, 64, 512, 1024, 99, 0, null) == -7
+    assert g2(p, p, p, p, p, 512, 4096, 1024, 6, 8, null) == -4                  # slabs beyond the static array
     assert L.w4a8_tile_weights(null, p, 32, 128, null) == -1
     assert L.w4a8_tile_weights(p, p, 32, 100, null) == -2
     assert L.w4a8_tile_weights(p, odd, 32, 128, null) == -3
@@ -110,7 +123,7 @@ def test_argument_validation_happens_before_any_launch(L):
     sk = L.w4a8_gemm_tiled_splitk
     assert sk(p, p, p, p, null, 1, 16, 256, 0, 0, p, big, null) == -1
     assert sk(p, p, p, p, p, 1, 16, 48, 0, 0, p, big, null) == -2
-    assert sk(p, p, p, p, p, 1, 16, 256, 11, 0, p, big, null) == -7          # unknown tile
+    assert sk(p, p, p, p, p, 1, 16, 256, 12, 0, p, big, null) == -7          # unknown tile
     assert sk(p, p, p, p, p, 1, 16, 256, 0, 65, p, big, null) == -7          # too many slices
     assert sk(p, p, p, p, p, 1, 16, 256, 0, 2, null, big, null) == -1        # two slices need a workspace
     assert sk(p, p, p, p, p, 1, 16, 256, 0, 2, p, ctypes.c_size_t(127), null) == -4
