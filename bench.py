@@ -11,12 +11,15 @@ work of a step (2*M*N*K summed over the four linears) divided by the step time.
 
 The same run also reports the decode side of the metric (M = 1, 4, 16 on the same
 four shapes, weights rotated through more than the last-level cache so every byte
-comes from HBM), a roofline object for the dominant kernel, the layer stack at
-M = 1 .. 2048 replayed from a HIP graph (layer time and GEMM share), the per-GEMM
-ratios of the W8A8 comparison variant and of the two ablation variants (unsigned
-nibble storage, fine-grained group scales) to W4A8, and the CPU oracle's
-throughput on a bounded sample of the workload.  Every GEMM of the run reads the
-one tiled copy of the weights, whatever its M.
+comes from HBM), the same for the LLaMA-7B shapes, a sweep of M = 1 .. 4096 over the
+LLaMA-70B shapes, the 13B GEMMs at M = 2048 and 4096, the row-major entry
+(w4a8_gemm over Wp[N][K/2]) beside the tiled one, a roofline object for the dominant
+kernel, the layer stack at M = 1 .. 2048 replayed from a HIP graph (layer time and
+GEMM share), the per-GEMM ratios of the W8A8 comparison variant and of the two
+ablation variants (unsigned nibble storage, fine-grained group scales) to W4A8, and
+the CPU oracle's throughput on a bounded sample of the workload.  Except for the
+row-major rows, every GEMM of the run reads the one tiled copy of the weights,
+whatever its M.
 
 All inputs are seeded synthetic tensors generated on the host and resident in
 HBM before the timed region starts.
@@ -48,11 +51,30 @@ def gemm_ops(M, N, K):
 
 
 COPY_CALIBRATION_BYTES = 256 << 20
-# L2 fill + write-back bytes per GEMM launch of the default workload (mean over its four linears), from the two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/gemm_prefill_tiled_13b_counters.md, each scaled by
-# what the counter reads for the 256 MiB copy of --copy-calibration.  Counters cannot be read from inside this
-# process, so the figure is carried here and reported only for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("13b", 1024): 139.5e6}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_counters.json")
+
+
+def kernel_source_hash():
+    """Hash of the kernel sources and headers: ties a counter profile to the build it was taken from."""
+    from paper_2311_09550_amd.build import source_hash
+    return source_hash()
+
+
+def measured_traffic(key):
+    """HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) of the kernel
+    named `key`, from the counter profile written by paper_2311_09550_amd/counters.py.  Counters cannot be read from
+    inside this process, so the figure comes from that file, and only if the file was made from the very sources this
+    build was made from; otherwise the line says null and why."""
+    try:
+        prof = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        return None, "no counter profile (profiles/traffic_counters.json)"
+    if prof.get("source_hash") != kernel_source_hash():
+        return None, "counter profile is older than the kernel sources"
+    entry = prof.get("kernels", {}).get(key)
+    if entry is None:
+        return None, "kernel not in the counter profile"
+    return entry["traffic_bytes_per_launch"], prof.get("summary", "profiles/")
 
 
 def parse_args():
@@ -67,6 +89,12 @@ def parse_args():
     ap.add_argument("--no-achievable", action="store_true", help="skip the probes of achievable HBM and MFMA rates")
     ap.add_argument("--no-medium-m", action="store_true", help="skip the four linears at M = 32 .. 512")
     ap.add_argument("--no-table5", action="store_true", help="skip the GEMM sizes of the paper's Table 5")
+    ap.add_argument("--no-7b", action="store_true", help="skip the LLaMA-7B decode linears")
+    ap.add_argument("--no-70b", action="store_true", help="skip the LLaMA-70B sweep over M")
+    ap.add_argument("--no-large-m", action="store_true", help="skip the 13B GEMMs at M = 2048 and 4096")
+    ap.add_argument("--no-row-major", action="store_true", help="skip the row-major entry (w4a8_gemm over Wp)")
+    ap.add_argument("--only", default="", help="comma-separated sections to run besides the timed step "
+                    "(decode, layer_stack, 7b, 70b, large_m, row_major, achievable, medium_m, table5, w8a8, cpu); empty = all")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -92,18 +120,24 @@ def prepare_weights(torch, w4a8, synth, model="13b"):
 
 
 class LayerStack:
-    """Device buffers of one 13B-shaped decoder layer's linears and the eight launches of a step."""
+    """Device buffers of one 13B-shaped decoder layer's linears and the launches of a step.
 
-    def __init__(self, torch, w4a8, synth, M, weights, model="13b"):
+    Eight launches (three per-token quantisers, the fused SiLU*up + quantiser, four GEMMs).  M <= 2 with fuse=True:
+    five launches -- the linears fed by fp16 hidden states (QKV, O, gate+up) quantise their own activations inside the
+    weight-streaming GEMM (w4a8_linear_tiled_fp16); only the SiLU*up + quantiser in front of the down projection stays
+    a launch of its own (its input is twice as wide as its output)."""
+
+    def __init__(self, torch, w4a8, synth, M, weights, model="13b", fuse=False):
         self.torch, self.w4a8, self.M = torch, w4a8, M
         self.shapes = synth.LLAMA_SHAPES[model]
+        self.fused = bool(fuse and M <= 2)   # measured: 41 against 47 us per layer at M = 1, 45 against 49.5 at M = 2, slower from M = 3
         dev = "cuda"
         self.wp = {k: v[0] for k, v in weights.items()}
         self.s_w = {k: v[1] for k, v in weights.items()}
         H = self.shapes["qkv"][1]
         I = self.shapes["down"][1]
         # fp16 hidden states enter the stack; attention itself is not modelled: the Q slice of the QKV output stands in
-        # for its result, and every later linear is fed by the one before it, so the eight launches form one chain
+        # for its result, and every later linear is fed by the one before it, so the launches form one chain
         self.h = torch.from_numpy(synth.activations_fp16(M, H, config_id=3, tag=1)).to(dev)
         e = lambda *s, dt: torch.empty(s, dtype=dt, device=dev)
         self.xq_h, self.sa_h = e(M, H, dt=torch.int8), e(M, dt=torch.float32)
@@ -113,7 +147,7 @@ class LayerStack:
         self.ws = {name: e(max(16, w4a8.w4a8_gemm_tiled_workspace_bytes(M, N, K)), dt=torch.uint8)
                    for name, (N, K) in self.shapes.items()}
         self.gemm_events = []   # (name, start, stop) around GEMM launches, filled when record=True
-        # the eight launches with their arguments marshalled once: the timed loop then spends its host time in the
+        # the launches with their arguments marshalled once: the timed loop then spends its host time in the
         # library, not in Python
         b = w4a8.bound_call
         self.quant = {"qkv": b("w4a8_quantize_act", self.h, self.xq_h, self.sa_h, M, H),
@@ -125,6 +159,11 @@ class LayerStack:
             xq, sa = (self.xq_i, self.sa_i) if name == "down" else (self.xq_h, self.sa_h)
             self.gemm[name] = b("w4a8_gemm_tiled_splitk", xq, sa, self.wp[name], self.s_w[name], self.out[name], M, N, K,
                                 0, 0, self.ws[name], self.ws[name].numel())
+        if self.fused:
+            src = {"qkv": (self.h, H), "o": (self.out["qkv"], self.shapes["qkv"][0]), "gate_up": (self.out["o"], H)}
+            self.linear = {name: b("w4a8_linear_tiled_fp16", x, ldx, self.wp[name], self.s_w[name], self.out[name], None,
+                                   M, self.shapes[name][0], self.shapes[name][1]) for name, (x, ldx) in src.items()}
+        self.launches_per_step = 5 if self.fused else 8
 
     def _gemm(self, name, record=False):
         if record:
@@ -137,8 +176,11 @@ class LayerStack:
             self.gemm_events.append((name, a, b))
 
     def step(self, record=None):
-        """One pass over the eight launches; `record` names the GEMM to bracket with timing events (None: none)."""
+        """One pass over the launches; `record` names the GEMM to bracket with timing events (None: none)."""
         for name in ("qkv", "o", "gate_up", "down"):
+            if self.fused and name != "down":
+                self.linear[name]()      # per-token quantiser inside the weight-streaming GEMM
+                continue
             self.quant[name]()           # "down": SiLU*up and its quantiser in one pass
             self._gemm(name, record == name)
 
@@ -150,41 +192,76 @@ class LayerStack:
         return sum(gemm_ops(self.M, N, K) for N, K in self.shapes.values())
 
 
-def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 16, 64, 128, 1024, 2048), steps_per_graph=8, replays=6):
+def graph_time_us(torch, fn_of_i, launches, replays):
+    """Per-launch time of `launches` calls fn_of_i(0..launches-1) captured in one HIP graph and replayed `replays`
+    times between two events on the launch stream (gaps between dependent kernels included)."""
+    fn_of_i(0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(launches):
+            fn_of_i(i)
+    graph.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(replays):
+        graph.replay()
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / (launches * replays)
+    del graph
+    return us
+
+
+def cold_copies(torch, wt, at_least=2):
+    """Copies of a weight array that together exceed the last-level cache three times: rotating through them, every
+    launch finds its weights in HBM."""
+    copies = max(at_least, -(-3 * LAST_LEVEL_CACHE_BYTES // wt.numel()) + 1)
+    return [wt] + [wt.clone() for _ in range(copies - 1)]
+
+
+def roofline_row(M, N, K, us):
+    by, ops = gemm_bytes(M, N, K), gemm_ops(M, N, K)
+    t_mem, t_mfma = by / HBM_PEAK_GBS / 1e3, ops / INT8_PEAK_TOPS / 1e6
+    return {"us": round(us, 2), "TOPS": round(ops / us / 1e6, 1), "GBps": round(by / us / 1e3, 1),
+            "bound": "hbm" if t_mem >= t_mfma else "mfma", "roofline_frac": round(max(t_mem, t_mfma) / us, 4)}
+
+
+def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 2, 16, 64, 128, 1024, 2048), steps_per_graph=8, replays=6):
     """The decoder layer's linear stack at several M, replayed from a HIP graph (what a serving loop does; at small M
-    the eight launches would otherwise be timed by the interpreter).  Layer time = graph time / steps; the GEMM share
-    is the time of a second graph that holds only the four GEMMs, over the layer time.  One layer's weights (158 MB)
-    stay resident in the last-level cache across replays: the small-M rows are a warm-cache figure, the HBM-bound
-    figure is the `decode` list."""
+    the launches would otherwise be timed by the interpreter).  Layer time = graph time / steps; the GEMM share is the
+    time of a second graph that holds only the four plain GEMMs (pre-quantised inputs), over the layer time.  At
+    M <= 2 the layer runs with the quantisers folded into the GEMMs (5 launches), and the unfused form (8 launches)
+    is timed beside it.  One layer's weights (158 MB) stay resident in the last-level cache across replays: the small-M
+    rows are a warm-cache figure, the HBM-bound figure is the `decode` list."""
     rows = []
     for M in Ms:
-        stack = LayerStack(torch, w4a8, synth, M, weights)
-        for _ in range(3):
-            stack.step()
-        torch.cuda.synchronize()
+        stack = LayerStack(torch, w4a8, synth, M, weights, fuse=True)
+        plain = LayerStack(torch, w4a8, synth, M, weights, fuse=False) if stack.fused else None
         times = {}
-        for what, fn in (("layer", stack.step), ("gemms", stack.gemms_only)):
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                for _ in range(steps_per_graph):
-                    fn()
-            graph.replay()
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(replays):
-                graph.replay()
-            b.record()
-            torch.cuda.synchronize()
-            times[what] = a.elapsed_time(b) * 1e3 / (replays * steps_per_graph)
-            del graph
-        rows.append({"M": M, "layer_us": round(times["layer"], 2), "gemm_us": round(times["gemms"], 2),
-                     "gemm_share": round(times["gemms"] / times["layer"], 4),
-                     "TOPS": round(stack.ops_per_step() / times["layer"] / 1e6, 2),
-                     "weights": "tiled"})
-        del stack
+        todo = [("layer", stack.step), ("gemms", stack.gemms_only)]
+        if plain is not None:
+            todo.append(("unfused", plain.step))
+        for what, fn in todo:
+            for _ in range(3):
+                fn()
+            times[what] = graph_time_us(torch, lambda i: fn(), steps_per_graph, replays)
+        row = {"M": M, "layer_us": round(times["layer"], 2), "gemm_us": round(times["gemms"], 2),
+               "gemm_share": round(times["gemms"] / times["layer"], 4),
+               "TOPS": round(stack.ops_per_step() / times["layer"] / 1e6, 2),
+               "launches": stack.launches_per_step, "weights": "tiled"}
+        if plain is not None:
+            row["unfused_layer_us"] = round(times["unfused"], 2)
+        rows.append(row)
+        del stack, plain
         torch.cuda.empty_cache()
     return rows
+
+
+def quantised_tiled(torch, w4a8, w):
+    wp, s_w = w4a8.w4a8_quantize_weights(w)
+    return w4a8.w4a8_tile_weights(wp), wp, s_w
 
 
 def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
@@ -195,50 +272,143 @@ def time_decode(torch, w4a8, synth, model="13b", Ms=(1, 4, 16), iters=5):
     rows = []
     for name, (N, K) in synth.LLAMA_SHAPES[model].items():
         w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).cuda()
-        wp, s_w = w4a8.w4a8_quantize_weights(w)
-        wt = w4a8.w4a8_tile_weights(wp)   # the same array the large-M kernel reads
+        wt, wp, s_w = quantised_tiled(torch, w4a8, w)   # wt: the same array the large-M kernel reads
         del w, wp
-        wbytes = N * K // 2
-        copies = max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wbytes) + 1)
-        wps = [wt] + [wt.clone() for _ in range(copies - 1)]
+        wts = cold_copies(torch, wt)
+        copies = len(wts)
         for M in Ms:
             x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
             xq, s_a = w4a8.w4a8_quantize_act(x)
             out = torch.empty((M, N), dtype=torch.float16, device="cuda")
             for i in range(min(copies, 4)):
-                w4a8.w4a8_gemm_tiled(xq, s_a, wps[i], s_w, out=out)
-            torch.cuda.synchronize()
+                w4a8.w4a8_gemm_tiled(xq, s_a, wts[i], s_w, out=out)
             # One graph holds a back-to-back batch of launches (a decode loop is replayed from a graph as well; launching
             # each 5-15 us kernel from Python would time the interpreter, not the GPU).
-            n = max(copies, 24)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                for i in range(n):
-                    w4a8.w4a8_gemm_tiled(xq, s_a, wps[i % copies], s_w, out=out)
-            graph.replay()
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(iters):
-                graph.replay()
-            b.record()
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / (n * iters)
-            del graph
+            us = graph_time_us(torch, lambda i: w4a8.w4a8_gemm_tiled(xq, s_a, wts[i % copies], s_w, out=out),
+                               max(copies, 24), iters)
             by = gemm_bytes(M, N, K)
             rows.append({"linear": name, "M": M, "N": N, "K": K, "us": round(us, 3),
                          "GBps": round(by / us / 1e3, 1), "hbm_frac": round(by / us / 1e3 / HBM_PEAK_GBS, 4),
                          "weight_copies": copies})
-        del wps, wt
+        del wts, wt
         torch.cuda.empty_cache()
     return rows
 
 
+def decode_roofline(rows, kernel):
+    worst = min(rows, key=lambda r: r["hbm_frac"])
+    best = max(rows, key=lambda r: r["hbm_frac"])
+    mean_us = sum(r["us"] for r in rows) / len(rows)
+    mean_bytes = sum(gemm_bytes(r["M"], r["N"], r["K"]) for r in rows) / len(rows)
+    return {"bound": "hbm", "achieved": round(mean_bytes / mean_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(mean_bytes / mean_us / 1e3 / HBM_PEAK_GBS, 4),
+            "mean_of_row_fracs": round(sum(r["hbm_frac"] for r in rows) / len(rows), 4),
+            "algorithmic_bytes_per_launch": round(mean_bytes), "kernel": kernel, "worst": worst, "best": best}
+
+
+def device_weights_fp16(torch, N, K, seed, sigma=0.02):
+    """fp16 N(0, sigma) weights drawn on the device from a seeded generator (the 70B matrices are too large to draw on
+    the host within the run's time): same distribution as synth.weights_fp16, another stream."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    w = torch.empty((N, K), dtype=torch.float16, device="cuda")
+    rows = max(1, (64 << 20) // K)
+    for r0 in range(0, N, rows):
+        r1 = min(N, r0 + rows)
+        w[r0:r1] = (torch.randn((r1 - r0, K), generator=g, device="cuda", dtype=torch.float32) * sigma).to(torch.float16)
+    return w
+
+
+def device_activations_fp16(torch, synth, M, K, seed):
+    """fp16 N(0,1) activations with the fixed outlier channels of the workload x50, drawn on the device."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32)
+    x[:, torch.from_numpy(synth.outlier_channels(K, 4)).cuda()] *= 50.0
+    return x.to(torch.float16)
+
+
+def time_llama70b_sweep(torch, w4a8, synth, Ms=(1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096)):
+    """The four LLaMA-70B-shaped linears (GQA: 64 query and 8 KV heads of 128) over M = 1 .. 4096 through the one-copy
+    entry, cold weights (rotating copies), one graph-replayed timing per point.  Each row is set against the larger of
+    its two roofline times."""
+    rows = []
+    for idx, (name, (N, K)) in enumerate(synth.LLAMA_SHAPES["70b"].items()):
+        w = device_weights_fp16(torch, N, K, seed=7000 + idx)
+        wt, wp, s_w = quantised_tiled(torch, w4a8, w)
+        del w, wp
+        wts = cold_copies(torch, wt)
+        copies = len(wts)
+        for M in Ms:
+            x = device_activations_fp16(torch, synth, M, K, seed=7100 + idx)
+            xq, s_a = w4a8.w4a8_quantize_act(x)
+            del x
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            ws = torch.empty((max(16, w4a8.w4a8_gemm_tiled_workspace_bytes(M, N, K)),), dtype=torch.uint8, device="cuda")
+            us = graph_time_us(torch, lambda i: w4a8.w4a8_gemm_tiled_splitk(xq, s_a, wts[i % copies], s_w, ws=ws, out=out),
+                               max(copies, 4 if M >= 1024 else 12), 2)
+            rows.append({"linear": name, "M": M, "N": N, "K": K, **roofline_row(M, N, K, us)})
+            del xq, s_a, out, ws
+        del wts, wt
+        torch.cuda.empty_cache()
+    return rows
+
+
+def time_large_m(torch, w4a8, synth, weights, Ms=(2048, 4096)):
+    """The 13B linears as single GEMMs at M = 2048 and 4096 (warm weights: at these sizes the operands are re-read
+    from cache many times within one launch anyway)."""
+    rows = []
+    for name, (N, K) in synth.LLAMA_SHAPES["13b"].items():
+        wt, s_w = weights[name]
+        for M in Ms:
+            x = device_activations_fp16(torch, synth, M, K, seed=1300 + M)
+            xq, s_a = w4a8.w4a8_quantize_act(x)
+            del x
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            us = graph_time_us(torch, lambda i: w4a8.w4a8_gemm_tiled(xq, s_a, wt, s_w, out=out), 4, 3)
+            rows.append({"linear": name, "M": M, "N": N, "K": K, **roofline_row(M, N, K, us)})
+            del xq, s_a, out
+        torch.cuda.empty_cache()
+    return rows
+
+
+def time_row_major(torch, w4a8, synth, Ms=(1, 16, 1024)):
+    """The entry the problem statement names, w4a8_gemm over the row-major packed array Wp[N][K/2], beside the tiled
+    entry on the same codes: what a caller pays for not reordering the weights offline.  Cold weights, graph replay."""
+    rows = []
+    for name, (N, K) in synth.LLAMA_SHAPES["13b"].items():
+        w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).cuda()
+        wt, wp, s_w = quantised_tiled(torch, w4a8, w)
+        del w
+        wps, wts = cold_copies(torch, wp), cold_copies(torch, wt)
+        copies = len(wps)
+        for M in Ms:
+            x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
+            xq, s_a = w4a8.w4a8_quantize_act(x)
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            n = max(copies, 24) if M <= 16 else max(copies, 8)
+            us_row = graph_time_us(torch, lambda i: w4a8.w4a8_gemm(xq, s_a, wps[i % copies], s_w, out=out), n, 3)
+            us_tiled = graph_time_us(torch, lambda i: w4a8.w4a8_gemm_tiled(xq, s_a, wts[i % copies], s_w, out=out), n, 3)
+            rows.append({"linear": name, "M": M, "N": N, "K": K, "row_major": roofline_row(M, N, K, us_row),
+                         "tiled_us": round(us_tiled, 2), "row_major_over_tiled": round(us_row / us_tiled, 3)})
+        del wps, wts, wp, wt
+        torch.cuda.empty_cache()
+    return rows
+
+
+READ_PATTERNS = {0: "grid-wide stride, global loads", 1: "one contiguous run per workgroup, global loads",
+                 2: "grid-wide stride, buffer loads", 3: "one run per workgroup, buffer loads",
+                 4: "grid-wide stride, buffer loads, non-temporal", 5: "one run per workgroup, buffer loads, non-temporal"}
+
+
 def time_achievable(torch, w4a8):
-    """What the chip sustains, measured with the library's two probes, to set the datasheet fractions against: a
-    read-only streaming reduction over 2 GiB (eight times the last-level cache, so every pass comes from HBM) and over
-    cold pieces of the sizes of the 13B weight matrices, and a register-resident int8 MFMA loop on constant and on
-    random operands, long (about 2 ms) and as short as the GEMM kernels (about 50 us)."""
+    """What the chip sustains, measured with the library's probes, to set the datasheet fractions against.
+    Reads: a streaming reduction over 2 GiB (eight times the last-level cache, so every pass comes from HBM) in a
+    handful of access patterns (grid-wide stride or one run per workgroup; plain or non-temporal loads; 4 / 8 / 16 loads
+    in flight per thread; 1 .. 8 workgroups per compute unit), the best of which is the read ceiling, and the same best
+    pattern over cold pieces of the sizes of the 13B weight matrices, launched back to back from a graph (what one
+    weight-streaming GEMM launch could reach at most).  An independent figure: a plain 256 MiB device-to-device copy
+    (read + write).  Matrix cores: a register-resident int8 MFMA loop on constant and on random operands."""
     out = {}
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     big = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
@@ -255,23 +425,38 @@ def time_achievable(torch, w4a8):
         torch.cuda.synchronize()
         return a.elapsed_time(b) * 1e-3 / reps   # seconds per call
 
-    out["hbm_read_GBps"] = round(big.numel() / timed(lambda: w4a8.w4a8_probe_stream_read(big, sink), 5) / 1e9, 1)
+    variants = [(p, l, g) for p in (0, 1, 4, 5) for l in (4, 8, 16) for g in (1, 2, 8)]
+    rates = {v: big.numel() / timed(lambda: w4a8.w4a8_probe_read_pattern(big, sink, *v), 2) / 1e9 for v in variants}
+    best = max(rates, key=rates.get)
+    out["hbm_read_GBps"] = round(rates[best], 1)
+    out["hbm_read_pattern"] = {"pattern": READ_PATTERNS[best[0]], "loads_in_flight_per_thread": best[1],
+                               "workgroups_per_cu": best[2]}
+    out["hbm_read_GBps_by_pattern"] = {READ_PATTERNS[p]: round(max(r for v, r in rates.items() if v[0] == p), 1)
+                                       for p in (0, 1, 4, 5)}
+    out["hbm_read_GBps_plain_probe"] = round(big.numel() / timed(lambda: w4a8.w4a8_probe_stream_read(big, sink), 3) / 1e9, 1)
     by_size = {}
     for mb in (13, 39, 71):
         size = mb * 1000 * 1000 // 4096 * 4096
         n = big.numel() // size            # consecutive pieces: each is read once per pass over the 2 GiB
         pieces = [big[i * size:(i + 1) * size] for i in range(n)]
-        graph = torch.cuda.CUDAGraph()
-        w4a8.w4a8_probe_stream_read(pieces[0], sink)
-        torch.cuda.synchronize()
-        with torch.cuda.graph(graph):
-            for piece in pieces:
-                w4a8.w4a8_probe_stream_read(piece, sink)
-        by_size[f"{mb}MB"] = round(size * n / timed(graph.replay, 3) / 1e9, 1)
-        del graph
+        best_rate = 0.0
+        for v in ((4, 8, 2), (4, 4, 2), (5, 8, 2), (5, 4, 8)):
+            w4a8.w4a8_probe_read_pattern(pieces[0], sink, *v)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for piece in pieces:
+                    w4a8.w4a8_probe_read_pattern(piece, sink, *v)
+            best_rate = max(best_rate, size * n / timed(graph.replay, 2) / 1e9)
+            del graph
+        by_size[f"{mb}MB"] = round(best_rate, 1)
     out["hbm_read_GBps_cold_pieces"] = by_size
     del big
     torch.cuda.empty_cache()
+    src = torch.full((COPY_CALIBRATION_BYTES,), 3, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    out["copy_256MiB_read_plus_write_GBps"] = round(2 * COPY_CALIBRATION_BYTES / timed(lambda: dst.copy_(src), 5) / 1e9, 1)
+    del src, dst
     mfma = {}
     for label, iters, pattern, reps in (("constant_2ms", 8000, 0, 3), ("random_2ms", 8000, 1, 3), ("random_50us", 200, 1, 40)):
         ops = [0]
@@ -291,38 +476,19 @@ def time_medium_m(torch, w4a8, synth, model="13b", Ms=(32, 64, 128, 256, 512), i
     rows = []
     for name, (N, K) in synth.LLAMA_SHAPES[model].items():
         w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).cuda()
-        wp, s_w = w4a8.w4a8_quantize_weights(w)
-        wt = w4a8.w4a8_tile_weights(wp)
+        wt, wp, s_w = quantised_tiled(torch, w4a8, w)
         del w, wp
-        copies = max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wt.numel()) + 1)
-        wts = [wt] + [wt.clone() for _ in range(copies - 1)]
+        wts = cold_copies(torch, wt)
+        copies = len(wts)
         for M in Ms:
             x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=4)).cuda()
             xq, s_a = w4a8.w4a8_quantize_act(x)
             out = torch.empty((M, N), dtype=torch.float16, device="cuda")
             need = w4a8.w4a8_gemm_tiled_workspace_bytes(M, N, K)
             ws = torch.empty((max(16, need),), dtype=torch.uint8, device="cuda")
-            call = lambda i: w4a8.w4a8_gemm_tiled_splitk(xq, s_a, wts[i % copies], s_w, ws=ws, out=out)
-            call(0)
-            torch.cuda.synchronize()
-            n = max(copies, 16)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                for i in range(n):
-                    call(i)
-            graph.replay()
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(iters):
-                graph.replay()
-            b.record()
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / (n * iters)
-            del graph
-            roof_us = max(gemm_bytes(M, N, K) / HBM_PEAK_GBS / 1e3, gemm_ops(M, N, K) / INT8_PEAK_TOPS / 1e6)
-            rows.append({"linear": name, "M": M, "us": round(us, 2), "TOPS": round(gemm_ops(M, N, K) / us / 1e6, 1),
-                         "GBps": round(gemm_bytes(M, N, K) / us / 1e3, 1), "roofline_frac": round(roof_us / us, 4),
+            us = graph_time_us(torch, lambda i: w4a8.w4a8_gemm_tiled_splitk(xq, s_a, wts[i % copies], s_w, ws=ws, out=out),
+                               max(copies, 16), iters)
+            rows.append({"linear": name, "M": M, **roofline_row(M, N, K, us),
                          "k_slices": need // (M * N * 4) if need else 1})
         del wts, wt
         torch.cuda.empty_cache()
@@ -495,6 +661,12 @@ def main():
         sys.exit(2)
     w4a8.lib()
     torch.cuda.set_device(0)
+    w4a8.w4a8_init()
+    only = {s for s in args.only.split(",") if s}
+
+    def wanted(section, disabled):
+        return not disabled and (not only or section in only)
+
     M = args.M
     if args.copy_calibration:
         src = torch.full((COPY_CALIBRATION_BYTES,), 3, dtype=torch.uint8, device="cuda")
@@ -527,13 +699,16 @@ def main():
     avg_us = sum(gemm_us.values()) / len(gemm_us)      # mean over the linears of each linear's mean launch
     ops_per_launch = sum(gemm_ops(M, *stack.shapes[k]) for k in gemm_us) / len(gemm_us)
     achieved = ops_per_launch / avg_us / 1e6   # TOPS
+    traffic, traffic_note = measured_traffic(f"gemm_prefill_tiled_kernel@13b,M={M}")
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(("13b", M)),
-                "traffic_unit": "bytes per launch (L2 fills + write-backs)",
+                "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": traffic,
+                "traffic_unit": "bytes per launch (L2 fills + write-backs)", "traffic_source": traffic_note,
                 "algorithmic_bytes_per_launch": round(sum(gemm_bytes(M, *stack.shapes[k]) for k in gemm_us) / len(gemm_us)),
                 "kernel": "gemm_prefill_tiled_kernel", "avg_launch_us": round(avg_us, 2),
                 "per_linear_us": {k: round(v, 2) for k, v in gemm_us.items()},
-                "per_linear_tops": {k: round(gemm_ops(M, *stack.shapes[k]) / v / 1e6, 1) for k, v in gemm_us.items()}}
+                "per_linear_tops": {k: round(gemm_ops(M, *stack.shapes[k]) / v / 1e6, 1) for k, v in gemm_us.items()},
+                "per_linear_frac": {k: round(gemm_ops(M, *stack.shapes[k]) / v / 1e6 / INT8_PEAK_TOPS, 4)
+                                    for k, v in gemm_us.items()}}
 
     result = {
         "metric": "W4A8 GEMM TOPS + HBM GB/s vs roofline, LLaMA-13B shapes, M=1..1024",
@@ -545,44 +720,51 @@ def main():
                                "weights quantised, packed and reordered into the tiled layout offline",
                    "M": M, "linears": {k: list(v) for k, v in stack.shapes.items()}, "launches_per_step": 8},
         "gemm_share_of_step": round(sum(gemm_us.values()) / (ms_per_step * 1e3), 4),
+        "kernel_source_hash": kernel_source_hash(),
         "roofline": roofline,
     }
     del stack
     torch.cuda.empty_cache()
-    if not args.no_layer_stack:
+    if wanted("layer_stack", args.no_layer_stack):
         result["layer_stack"] = time_layer_stack(torch, w4a8, synth, weights)
+    if wanted("large_m", args.no_large_m):
+        result["llama13b_large_m"] = time_large_m(torch, w4a8, synth, weights)
     del weights
     torch.cuda.empty_cache()
-    if not args.no_decode:
+    if wanted("decode", args.no_decode):
         rows = time_decode(torch, w4a8, synth)
         result["decode"] = rows
-        worst = min(rows, key=lambda r: r["hbm_frac"])
-        best = max(rows, key=lambda r: r["hbm_frac"])
-        mean_us = sum(r["us"] for r in rows) / len(rows)
-        mean_bytes = sum(gemm_bytes(r["M"], r["N"], r["K"]) for r in rows) / len(rows)
-        result["roofline_decode"] = {"bound": "hbm", "achieved": round(mean_bytes / mean_us / 1e3, 1), "peak": HBM_PEAK_GBS,
-                                     "unit": "GB/s", "frac": round(mean_bytes / mean_us / 1e3 / HBM_PEAK_GBS, 4),
-                                     "traffic": None, "kernel": "gemm_decode_resident_kernel",
-                                     "worst": worst, "best": best}
-    if not args.no_achievable:
+        result["roofline_decode"] = decode_roofline(rows, "gemm_decode_resident_kernel")
+        t, note = measured_traffic("gemm_decode_resident_kernel@13b,M=1..16")
+        result["roofline_decode"]["traffic"] = t
+        result["roofline_decode"]["traffic_source"] = note
+    if wanted("7b", args.no_7b):
+        rows = time_decode(torch, w4a8, synth, model="7b")
+        result["llama7b_decode"] = rows
+        result["roofline_llama7b_decode"] = decode_roofline(rows, "gemm_decode_resident_kernel")
+    if wanted("70b", args.no_70b):
+        result["llama70b_sweep"] = time_llama70b_sweep(torch, w4a8, synth)
+    if wanted("row_major", args.no_row_major):
+        result["row_major"] = time_row_major(torch, w4a8, synth)
+    if wanted("achievable", args.no_achievable):
         ach = time_achievable(torch, w4a8)
         result["achievable"] = ach
-        result["roofline"]["frac_of_achievable"] = round(result["roofline"]["achieved"] / ach["int8_mfma_TOPS"]["random_50us"], 4)
+        result["roofline"]["frac_of_achievable"] = round(result["roofline"]["achieved"] / ach["int8_mfma_TOPS"]["random_2ms"], 4)
         if "roofline_decode" in result:
-            # every decode case against the plain read of a cold piece of about its size
+            # every decode case against the best plain read of a cold piece of about its size
             piece = {"o": "13MB", "qkv": "39MB", "down": "39MB", "gate_up": "71MB"}
             for r in result["decode"]:
                 rate = ach["hbm_read_GBps_cold_pieces"][piece[r["linear"]]]
                 r["frac_of_stream_read"] = round(r["GBps"] / rate, 4)
             result["roofline_decode"]["frac_of_achievable"] = round(
                 sum(r["frac_of_stream_read"] for r in result["decode"]) / len(result["decode"]), 4)
-    if not args.no_medium_m:
+    if wanted("medium_m", args.no_medium_m):
         result["medium_m"] = time_medium_m(torch, w4a8, synth)
-    if not args.no_table5:
+    if wanted("table5", args.no_table5):
         result["paper_table5_shapes"] = time_paper_table5(torch, w4a8, synth)
-    if not args.no_w8a8:
+    if wanted("w8a8", args.no_w8a8):
         result["w4a8_vs_w8a8"] = time_w4_vs_w8(torch, w4a8, synth)
-    if not args.no_cpu_baseline:
+    if wanted("cpu", args.no_cpu_baseline):
         result["cpu_baseline"] = cpu_baseline(synth, M, args.cpu_seconds)
     print(json.dumps(result))
 

@@ -393,7 +393,7 @@ def w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, variant: int = 0, splits: int = 0, 
 
 def w4a8_linear_tiled_fp16(x, wt, s_w, out=None, s_a_out=None):
     """fp16 [M][K] view (unit column stride, rows x.stride(0) apart), tiled weights, fp32 [N] -> fp16 [M][N]: per-token
-    quantisation and W4A8 GEMM in one launch (M <= 16, K <= 8192).  s_a_out (fp32 [M]) also receives the scales."""
+    quantisation and W4A8 GEMM in one launch (M <= 4, rows small enough for LDS).  s_a_out (fp32 [M]) also receives the scales."""
     torch = _torch()
     M, K = x.shape
     N = s_w.shape[0]

@@ -511,11 +511,15 @@ int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt,
     if (int e = check_gemm_shape(M, N, K)) return e;
     if (ldx < K || (ldx & 7) != 0) return W4A8_ERR_SHAPE;  // rows must not overlap and must start 16-byte aligned
     if (misaligned(x_fp16) || misaligned(wt) || misaligned(out_fp16) || misaligned(s_w)) return W4A8_ERR_ALIGN;
-    if (M > 16) return W4A8_ERR_ARG;
+    if (M > 4) return W4A8_ERR_ARG;
     if (((unsigned long long)(M - 1) * (unsigned long long)ldx + (unsigned long long)K) * 2ull > 0xFFFF0000ull) return W4A8_ERR_SHAPE;
     DecodeShape shape{};
     shape.fused_quant = true;
-    if (!resident_shape(M, N, K, 8, 0, 0, false, -1, true, &shape)) return W4A8_ERR_ARG;
+    if (!resident_shape(M, N, K, 0, 0, 0, false, -1, true, &shape)) return W4A8_ERR_ARG;
+    // both copies of the rows (fp16 and int8, padded to the 1 KB pieces of the copy) must fit in LDS beside the slots
+    // of the partial sums
+    const long long row_bytes = ((K + 1023) / 1024) * 1024 + 16 + ((2ll * K + 1023) / 1024) * 1024;
+    if (row_bytes * M + 3 * 1024 + 2ll * shape.prefetch * shape.waves * 1024 > 160 * 1024) return W4A8_ERR_ARG;
     DecodeArgs a{};
     a.x16 = static_cast<const uint16_t *>(x_fp16);
     a.ldx = ldx;

@@ -126,13 +126,15 @@ __device__ __forceinline__ void wait_vmcnt_at_most() {
 }
 
 // FQ: the kernel is handed fp16 activations (p.x16, rows p.ldx apart) and quantises them per token itself, exactly as
-// quantize_act_kernel would (Sec. 3 "per token"; Eq. (2), z = 0): every wave fetches the k steps it multiplies, the
-// waves exchange their row maxima through LDS, and each lane then quantises its own 32 XS values with the row's
-// scale.  One launch instead of two for a linear at token-generation sizes (the kind of fusion across operators
-// the paper's engine relies on, Sec. 6.1).  M <= 16 only.
+// quantize_act_kernel would (Sec. 3 "per token"; Eq. (2), z = 0): the workgroup copies the fp16 rows into LDS, finds
+// the row maxima, quantises the rows into a second LDS area (every thread its share), and the waves pick their
+// operands from there as in the staged form.  One launch instead of two for a linear at token-generation sizes (the
+// kind of fusion across operators the paper's engine relies on, Sec. 6.1).  M <= 4: every workgroup repeats the
+// quantisation, which costs about ten vector instructions per value, so beyond a few rows a launch of its own is
+// cheaper.
 template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(DecodeArgs p) {
-    static_assert(!FQ || (MT == 1 && !ACC_OUT), "the fused quantiser serves one column tile and the fp16 output");
+    static_assert(!FQ || (MT == 1 && !ACC_OUT), "the fused quantiser serves up to four tokens and the fp16 output");
     extern __shared__ __attribute__((aligned(16))) uint8_t epoch_lds[];
     float *sw_lds = (float *)epoch_lds;
     float *amax_lds = (float *)(epoch_lds + kEpochScaleBytes);  // FQ: [wave][16] row maxima of the waves' k steps
@@ -170,21 +172,31 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     // lanes fetch the same row.  So, when they fit, the workgroup copies the M rows into LDS once with LDS-direct
     // loads of whole 1 KB pieces (p.x_lds_pitch > 0) and every wave picks its operands from there.
     v4u xraw[XS][MT][2];
-    v4u xhalf[FQ ? XS : 1][4];  // FQ: the lane's 32 fp16 values of each of its k steps
-    const int pitch = FQ ? 0 : p.x_lds_pitch;
+    const int pitch = p.x_lds_pitch;  // FQ: always staged (the launcher sees to it that the rows fit)
     if constexpr (FQ) {
-        // rows past M are not fetched (an offset beyond the buffer returns zeros): they meet real weights, but what
-        // they produce lands in output columns that are never stored
+        // the fp16 rows go to LDS in 1 KB pieces, as the int8 rows do in the other form
         const unsigned long long x_bytes = ((unsigned long long)(p.M - 1) * (unsigned long long)p.ldx + (unsigned long long)p.K) * 2ull;
-        const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.x16, 0, (unsigned)x_bytes, 0x00020000);
-#pragma unroll
-        for (int i = 0; i < XS; ++i) {
-            const unsigned at = (live[i] && r < p.M)
-                                    ? (unsigned)(((unsigned long long)r * (unsigned long long)p.ldx + (unsigned)(k_step(i) * 128 + 32 * g)) * 2ull)
-                                    : kNowhere;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                xhalf[i][j] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, at >= kNowhere ? kNowhere : at + 16 * j, 0, 0);
+        const v4i x_rsrc = [&] {
+            const unsigned long long b = (unsigned long long)p.x16;
+            v4i r;
+            r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)b);
+            r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)((b >> 32) & 0xFFFFu));
+            r.z = __builtin_amdgcn_readfirstlane((int)(unsigned)x_bytes);
+            r.w = 0x00020000;
+            return r;
+        }();
+        const unsigned x_base = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)(lds_ptr_t)(epoch_lds + p.x16_lds_offset));
+        const int per_row = (2 * p.K + 1023) >> 10;
+        const int pieces = p.M * per_row;
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+        for (int j = wave_u; j < pieces; j += WAVES) {
+            const int m = j / per_row, c = j - m * per_row;
+            const unsigned in_row = (unsigned)(c * 1024 + lane * 16);
+            const unsigned src = in_row < 2u * (unsigned)p.K ? (unsigned)((unsigned long long)m * (unsigned long long)p.ldx * 2ull) + in_row : kNowhere;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                         :
+                         : "s"(x_base + (unsigned)(m * p.x16_lds_pitch + c * 1024)), "v"(src), "s"(x_rsrc)
+                         : "memory", "m0");
         }
     } else if (pitch > 0) {
         const v4i x_rsrc = [&] {
@@ -265,40 +277,62 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     }
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (FQ) {
-        // row maxima: over the lane's values, over the four K groups of the row (lanes r, r + 16, r + 32, r + 48), over
-        // the waves (through LDS); every lane of row r ends up with the maximum of the whole row
-        float amax = 0.f;
-#pragma unroll
-        for (int i = 0; i < XS; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) amax = absmax8(xhalf[i][j], amax);
-        amax = fmaxf(amax, __shfl_xor(amax, 16, 64));
-        amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
-        if (g == 0) amax_lds[wave * 16 + r] = amax;
+        // The workgroup quantises the M <= 4 rows together, each thread its share (were every lane to quantise the
+        // operands it multiplies, a wave would spend some 1600 vector instructions on it whatever M is, and all
+        // workgroups repeat the work: measured slower than a quantiser launch of its own).
+        constexpr int T = WAVES * 64;
+        wait_vmcnt_at_most<P * XS>();  // the copy and the scales are in: only the weight loads issued behind them remain
+        __builtin_amdgcn_sched_barrier(0);
         if (tid < n_sw) sw_lds[tid] = sw_first;
         lds_barrier();
+        const uint8_t *x16 = epoch_lds + p.x16_lds_offset;
+        uint8_t *xq_lds = epoch_lds + p.x_lds_offset;
+        const int chunks_row = p.K >> 3;  // 8 fp16 = 16 bytes
+        float *scale_lds = amax_lds + 64;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) amax = fmaxf(amax, amax_lds[w * 16 + r]);
-        const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
-        sa[0] = rq.scale;  // amax == 0 gives scale 0
-        if (p.s_a_out != nullptr && blockIdx.x == 0 && wave == 0 && g == 0 && r < p.M) p.s_a_out[r] = rq.scale;
-        const bool zero_row = amax == 0.f;
+        for (int m = 0; m < 4; ++m) {
+            if (m < p.M) {  // uniform
+                float pm = 0.f;
+                for (int c = tid; c < chunks_row; c += T) pm = absmax8(*(const v4u *)(x16 + m * p.x16_lds_pitch + c * 16), pm);
 #pragma unroll
-        for (int i = 0; i < XS; ++i) {
-            v2u codes[4];
+                for (int off = 32; off > 0; off >>= 1) pm = fmaxf(pm, __shfl_xor(pm, off, 64));
+                if (lane == 0) amax_lds[wave * 4 + m] = pm;
+            }
+        }
+        lds_barrier();
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                codes[j] = v2u{0u, 0u};
-                if (!zero_row) {
-                    float xf[8];
-                    int q8[8];
-                    halves8(xhalf[i][j], xf);
-                    rq.codes8(xf, q8);
-                    codes[j] = pack_i8x8(q8);
+        for (int m = 0; m < 4; ++m) {
+            if (m < p.M) {
+                float amax = 0.f;
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) amax = fmaxf(amax, amax_lds[w * 4 + m]);
+                const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);  // amax == 0 gives scale 0
+                if (tid == 0) {
+                    scale_lds[m] = rq.scale;
+                    if (p.s_a_out != nullptr && blockIdx.x == 0) p.s_a_out[m] = rq.scale;
+                }
+                const bool zero_row = amax == 0.f;
+                for (int c = tid; c < chunks_row; c += T) {
+                    v2u codes = v2u{0u, 0u};
+                    if (!zero_row) {
+                        float xf[8];
+                        int q8[8];
+                        halves8(*(const v4u *)(x16 + m * p.x16_lds_pitch + c * 16), xf);
+                        rq.codes8(xf, q8);
+                        codes = pack_i8x8(q8);
+                    }
+                    *(v2u *)(xq_lds + m * pitch + c * 8) = codes;
                 }
             }
-            xraw[i][0][0] = v4u{codes[0].x, codes[0].y, codes[1].x, codes[1].y};
-            xraw[i][0][1] = v4u{codes[2].x, codes[2].y, codes[3].x, codes[3].y};
+        }
+        lds_barrier();
+        sa[0] = scale_lds[min(r, p.M - 1)];
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            const int m = min(r, p.M - 1);
+            const v4u *px = (const v4u *)(xq_lds + m * pitch + (live[i] ? k_step(i) * 128 + 32 * g : 0));
+            xraw[i][0][0] = px[0];
+            xraw[i][0][1] = px[1];
         }
     } else if (pitch > 0) {
         // The copy, and the scales behind it, are in once at most the P XS weight loads issued after them are
@@ -545,7 +579,16 @@ static hipError_t launch_epoch_one(const DecodeArgs &p, int grid, int sets, bool
     const long long pitch = ((p.K + 1023) / 1024) * 1024 + 16;
     a.x_lds_pitch = 0;
     a.x_lds_offset = 0;
-    if (!FQ && p.x_lds_pitch >= 0 && lds + pitch * p.M <= kCuLdsBytes) {
+    if (FQ) {
+        // fused quantiser: the int8 rows and, behind them, the fp16 rows (whole 1 KB pieces) must both fit
+        const long long pitch16 = ((2ll * p.K + 1023) / 1024) * 1024;
+        if (p.M > 4 || lds + (pitch + pitch16) * p.M > kCuLdsBytes) return hipErrorInvalidConfiguration;
+        a.x_lds_pitch = (int)pitch;
+        a.x_lds_offset = lds;
+        a.x16_lds_pitch = (int)pitch16;
+        a.x16_lds_offset = lds + (int)(pitch * p.M);
+        lds += (int)((pitch + pitch16) * p.M);
+    } else if (p.x_lds_pitch >= 0 && lds + pitch * p.M <= kCuLdsBytes) {
         a.x_lds_pitch = (int)pitch;
         a.x_lds_offset = lds;
         lds += (int)(pitch * p.M);
@@ -554,9 +597,9 @@ static hipError_t launch_epoch_one(const DecodeArgs &p, int grid, int sets, bool
     return hipGetLastError();
 }
 
-// The fused quantiser holds a lane's 32 XS fp16 values (16 XS registers) until the row maxima are known.
+// The fused quantiser exists for one column tile; whether the rows fit in LDS is decided at the launch.
 constexpr bool fused_quant_fits(int mt, int xs, int prefetch, int waves) {
-    return mt == 1 && waves == 8 && 4 * prefetch * xs + 16 * xs + 8 * xs + 45 <= 270;
+    return mt == 1 && epoch_fits(mt, xs, prefetch, waves);
 }
 
 template <int MT, int XS, int P, int WAVES>

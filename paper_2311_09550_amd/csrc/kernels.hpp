@@ -47,6 +47,8 @@ struct DecodeArgs {
     int chunk_rows;      // persistent kernel: channels per chunk, 4, 8, 12 or 16
     int x_lds_pitch;     // persistent kernel: > 0 = the activations are staged in LDS, rows this many bytes apart
     int x_lds_offset;    //   ... starting at this byte of the kernel's dynamic LDS
+    int x16_lds_pitch;   // fused-quantiser form: the fp16 rows are staged too, rows this many bytes apart
+    int x16_lds_offset;  //   ... starting here
 };
 
 constexpr int kResidentMaxRows = 512;  // channels per workgroup of the persistent kernel (their scales are staged in LDS,
@@ -59,7 +61,7 @@ struct DecodeShape {
     int chunk_rows; // resident: channels per chunk (4, 8, 12 or 16)
     int aux;        // resident: cache-policy bits of the weight loads (0 or 2 = non-temporal)
     bool x_direct;  // resident: never stage the activations in LDS (they are staged when they fit, otherwise)
-    bool fused_quant;  // resident: the kernel quantises fp16 activations itself (M <= 16, 8 waves, tiled weights)
+    bool fused_quant;  // resident: the kernel quantises fp16 activations itself (M <= 4, tiled weights, rows must fit LDS)
     int waves;      // waves per workgroup: resident 8 or 16, streaming 4 or 8
     int x_steps;    // resident: k steps per wave = ceil(ceil(K/128) / waves)
     int rows_per_wg;  // resident: output channels per persistent workgroup, a multiple of 4, at most kResidentMaxRows

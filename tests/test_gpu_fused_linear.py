@@ -33,9 +33,11 @@ def _check(t, oracle, x, w, what, view=None):
     assert_equal_bits(out.cpu().numpy().view(np.uint16), ref.cpu().numpy().view(np.uint16), what + " vs two calls")
 
 
-@pytest.mark.parametrize("M", [1, 2, 3, 4, 7, 8, 15, 16])
-@pytest.mark.parametrize("N,K", [(16, 32), (100, 160), (520, 2080), (1001, 4096), (5120, 5120), (300, 8192)])
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+@pytest.mark.parametrize("N,K", [(16, 32), (100, 160), (520, 2080), (1001, 4096), (5120, 5120), (300, 8192), (136, 11008)])
 def test_fused_linear_matches_oracle_and_two_calls(gpu, oracle, M, N, K):
+    if M * K > 40000:
+        pytest.skip("the rows do not fit in LDS twice over: refused (see test_fused_linear_refuses_what_it_cannot_hold)")
     x = synth.activations_fp16(M, K, config_id=2, tag=70)
     w = synth.weights_fp16(N, K, config_id=70)
     _check(gpu, oracle, x, w, f"fused linear M={M} N={N} K={K}")
@@ -43,14 +45,14 @@ def test_fused_linear_matches_oracle_and_two_calls(gpu, oracle, M, N, K):
 
 def test_fused_linear_rounding_ties_zero_rows_and_strided_input(gpu, oracle):
     t = gpu
-    M, N, K = 6, 264, 1024
+    M, N, K = 4, 264, 1024
     x = synth.activations_fp16(M, K, config_id=2, tag=71)
-    x[1, :] = 0                        # an all-zero token: scale 0, codes 0, output 0
-    x[2, :] = 0
-    x[2, 5], x[2, 6], x[2, 7], x[2, 8], x[2, 9] = 127.0, 0.5, 1.5, 2.5, -3.5   # scale 1: exact halves, round to even
-    x[3, :] = np.float16(1e-7)         # fp16 subnormals
-    x[4, :] = np.linspace(-63.5, 63.5, K).astype(np.float16)
-    x[4, 0] = 127.0                    # scale 1 again: many quotients on or near halves
+    x[0, :] = 0                        # an all-zero token: scale 0, codes 0, output 0
+    x[1, :] = 0
+    x[1, 5], x[1, 6], x[1, 7], x[1, 8], x[1, 9] = 127.0, 0.5, 1.5, 2.5, -3.5   # scale 1: exact halves, round to even
+    x[2, :] = np.float16(1e-7)         # fp16 subnormals
+    x[3, :] = np.linspace(-63.5, 63.5, K).astype(np.float16)
+    x[3, 0] = 127.0                    # scale 1 again: many quotients on or near halves
     w = synth.weights_fp16(N, K, config_id=71)
     _check(t, oracle, x, w, "fused linear special rows")
     # the same rows as a column slice of a wider matrix (ldx > K)
@@ -62,7 +64,7 @@ def test_fused_linear_rounding_ties_zero_rows_and_strided_input(gpu, oracle):
 
 def test_fused_linear_refuses_what_it_cannot_hold(gpu):
     t = gpu
-    for M, N, K in [(17, 64, 1024), (4, 64, 8192 + 128)]:
+    for M, N, K in [(5, 64, 1024), (4, 64, 16384), (4, 136, 11008), (3, 64, 28672)]:
         x = t.zeros((M, K), dtype=t.float16, device="cuda")
         wt = t.zeros((w4a8.w4a8_tiled_weight_bytes(N, K),), dtype=t.uint8, device="cuda")
         s_w = t.ones((N,), dtype=t.float32, device="cuda")
@@ -71,7 +73,7 @@ def test_fused_linear_refuses_what_it_cannot_hold(gpu):
         assert e.value.code == -7
 
 
-@pytest.mark.parametrize("M", [1, 4, 16])
+@pytest.mark.parametrize("M", [1, 4])
 @pytest.mark.parametrize("name", ["qkv", "o", "gate_up"])
 def test_fused_linear_llama13b_shapes_sampled(gpu, oracle, name, M):
     """Full size: all M rows, a seeded sample of output channels against the oracle; everything against the two calls."""
