@@ -546,7 +546,7 @@ def time_paper_table5(torch, w4a8, synth, iters=5):
 
 def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
     """The paper sets its W4A8 against its own W8A8 (Table 4) and its signed storage against the vanilla unsigned one
-    ("Asym GEMM", Sec. 6.4) and the fine-grained recipe (group scales, Eq. (2)).  Here, per GEMM: the same large-M kernel
+    ("Asym GEMM", Sec. 7.2) and the fine-grained recipe (group scales, Eq. (5)).  Here, per GEMM: the same large-M kernel
     over tiled int4 (signed), tiled unsigned int4, signed int4 with group scales, and tiled int8 weights of the same
     fp16 matrix, every launch on a different weight copy (copies exceed the last-level
     cache three times, so weights come from HBM), batches replayed from a HIP graph."""
@@ -559,7 +559,7 @@ def time_w4_vs_w8(torch, w4a8, synth, model="13b", Ms=(16, 1024), iters=4):
         # "u4": the vanilla unsigned storage, u = w + 8, i.e. bit 3 of every two's-complement nibble flipped
         wt = {4: w4a8.w4a8_tile_weights(wp), 8: w4a8.w8a8_tile_weights(w8), "u4": w4a8.w4a8_tile_weights(wp ^ 0x88)}
         del wp, w8
-        # "fg": the fine-grained recipe (one scale per group of 128 k and channel, Eq. (2)) over the signed codes
+        # "fg": the fine-grained recipe (one scale per group of 128 k and channel, Eq. (5)) over the signed codes
         s_g = torch.from_numpy(synth.group_scales(N, K, 128, config_id=3)).cuda()
         fmts = (4, "u4", "fg", 8)
         copies = {b: max(2, -(-3 * LAST_LEVEL_CACHE_BYTES // wt[b].numel()) + 1) for b in (4, "u4", 8)}

@@ -234,7 +234,7 @@ int w8a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const
                     void *out_fp16, int32_t *acc_i32, int M, int N, int K, int variant, void *stream);
 
 /*
- * Ablation of the weight storage (the paper's "Asym GEMM", Sec. 5.3 / App. A.1 / Sec. 6.4): the vanilla unsigned
+ * Ablation of the weight storage (the paper's "Asym GEMM", Sec. 5.3 / App. A.1 / Sec. 7.2): the vanilla unsigned
  * format stores u = Wq + 8 in [0, 15] in each nibble and subtracts 8 again in registers before the multiplication,
  *   O[m][n] = fp16( float( sum_k Xq[m][k] * (u[n][k] - 8) ) * (s_a[m] * s_w[n]) ),
  * i.e. the result of w4a8_gemm_tiled for Wq = u - 8, at a higher conversion cost (7 instead of 3 vector operations per
@@ -246,7 +246,7 @@ int w4a8_gemm_tiled_unsigned(const int8_t *xq, const float *s_a, const uint8_t *
                              void *out_fp16, int32_t *acc_i32, int M, int N, int K, int variant, void *stream);
 
 /*
- * Ablation of the scale granularity (the paper's "fine-grained" GEMM: Eq. (2), Fig. 2(b), Sec. 4.1 and 6.4): the
+ * Ablation of the scale granularity (the paper's "fine-grained" GEMM: Eq. (5), Fig. 2(b), Sec. 4.2 and 7.2): the
  * weights carry one scale per group of 128 consecutive k and output channel instead of one per channel, so each
  * group's integer sum has to be made floating point and scaled before it can be added to the others:
  *   f[m][n]  = sum over groups g = 0 .. K/128 - 1, in ascending order, in fp32 with one fused multiply-add per group, of

@@ -388,7 +388,7 @@ int oracle_quantize_weights_groups(const uint16_t *w_half, int group, int8_t *wq
     return 0;
 }
 
-/* The fine-grained W4A8 product the paper sets its per-channel kernel against (Eq. (2), Fig. 2(b), Sec. 6.4):
+/* The fine-grained W4A8 product the paper sets its per-channel kernel against (Eq. (5), Fig. 2(b), Sec. 7.2):
  *     O[m][n] = sum_g Dq( sum_{k in group g} xq[m][k] * W_q[n][k],  s_a[m],  s_g[g][n] ),
  * an exact integer sum per group, made floating point and scaled group by group.
  *   y64  : the definition in fp64, s_a[m] * sum_g (acc_g * s_g[g][n]);

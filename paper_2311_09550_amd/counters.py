@@ -7,7 +7,7 @@ for `--kernel-trace --stats`).  This script reads them, never the GPU:
         HBM-side bytes per GEMM call of the kernel whose name contains NAME: FETCH_SIZE and WRITE_SIZE (KiB-like units
         per dispatch), each scaled by what the same counter reads for the 256 MiB `__amd_rocclr_copyBuffer` dispatches
         of `bench.py --copy-calibration` in the same run, summed over all dispatches of the kernel and divided by the
-        N GEMM calls of the run (a GEMM call may be more than one dispatch).  Merges the result under KEY into
+        N GEMM calls of the run (a GEMM call may be more than one dispatch; N = 0: one call per dispatch).  Merges the result under KEY into
         profiles/traffic_counters.json together with the hash of the kernel sources, which `bench.py` checks before it
         reports the figure.  Prints a markdown table per (kernel, grid size).
 
@@ -50,7 +50,7 @@ def _counter_rows(directory):
 
 
 def _short(name):
-    name = name.replace("void ", "").replace("w4a8::", "")
+    name = name.replace("void ", "").replace("(anonymous namespace)::", "").replace("w4a8::", "")
     return name.split("(")[0]
 
 
@@ -64,6 +64,8 @@ def _per_dispatch(directory, counter):
         if COPY_KERNEL in r["Kernel_Name"] and v > 1000:
             copies.append(v)
         rows.append((r["Kernel_Name"], int(r["Grid_Size"]), v))
+    # other device copies of the run (clones of weight arrays) are smaller than the 256 MiB calibration copy
+    copies = [v for v in copies if v >= 0.9 * max(copies)]
     return rows, (sum(copies) / len(copies) if copies else None)
 
 
@@ -94,7 +96,7 @@ def cmd_traffic(a):
     n_w = sum(len(g["write"]) for g in groups.values())
     if n_f != n_w:
         print(f"\n(the two runs saw {n_f} and {n_w} dispatches: each total is divided by its own run's GEMM calls)")
-    gemms = a.gemms
+    gemms = a.gemms if a.gemms > 0 else n_f   # 0: every dispatch is one GEMM call
     per_f, per_w = total_f / gemms, total_w * (n_f / n_w if n_w else 1.0) / gemms
     print(f"\nPer GEMM call ({gemms} calls in the run): {per_f / 1e6:.2f} MB fetched + {per_w / 1e6:.2f} MB written = "
           f"{(per_f + per_w) / 1e6:.2f} MB.")
@@ -157,7 +159,7 @@ def main():
     t.add_argument("--write", required=True)
     t.add_argument("--kernel", required=True)
     t.add_argument("--key", required=True)
-    t.add_argument("--gemms", type=int, required=True)
+    t.add_argument("--gemms", type=int, default=0, help="GEMM calls in the run; 0 = one per dispatch")
     t.add_argument("--summary", default="profiles/")
     s = sub.add_parser("sq")
     s.add_argument("--dir", required=True)

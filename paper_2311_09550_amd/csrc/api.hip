@@ -582,7 +582,7 @@ int w4a8_gemm_tiled_unsigned(const int8_t *xq, const float *s_a, const uint8_t *
     return gemm_tiled_variant(xq, s_a, ut, s_w, out_fp16, acc_i32, M, N, K, variant, stream, kWeightsUnsigned4);
 }
 
-// ---- ablation: fine-grained (group-wise) weight scales, Eq. (2)
+// ---- ablation: fine-grained (group-wise) weight scales, Eq. (5)
 
 int w4a8_gemm_fine_grained(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_g, int ldg, void *out_fp16,
                            int M, int N, int K, int variant, void *stream) {

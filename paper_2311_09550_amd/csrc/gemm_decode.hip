@@ -148,7 +148,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     const int R = p.chunk_rows;
     const int row0 = blockIdx.x * p.rows_per_wg;
     const int row_end = min(p.N, row0 + p.rows_per_wg);
-    const int chunks = (row_end - row0 + R - 1) / R;
+    const int chunks = max(0, (row_end - row0 + R - 1) / R);
 
     constexpr unsigned kNowhere = 0xFFFFFFF0u;  // beyond the buffer: such a load returns zeros and touches no memory
     const int ks_total = (p.K + 127) >> 7;
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    const int n_sw = ACC_OUT ? 0 : row_end - row0;
+    const int n_sw = ACC_OUT ? 0 : max(0, row_end - row0);
     float sw_first = 0.f;
     float sa[MT];
     if (!ACC_OUT) {

@@ -97,9 +97,9 @@ __global__ __launch_bounds__(256) void tile_weights_kernel(const uint8_t *__rest
 // W4A8 against W8A8): int8 weight codes in blocks of 32 channels x 128 k = 4 KB, chunk (c, r), c = 0..7, at
 // (c * 32 + r) * 16 holding k = 128 kb + 16 c .. + 15 of channel 32 nb + r; a fragment is an MFMA operand as it is.
 // UNS (with WBITS = 4): the "vanilla" unsigned storage the paper measures FastGEMM against (Sec. 5.3, App. A.1,
-// Fig. 4(b), "Asym GEMM" of Sec. 6.4): the nibbles hold u = w + 8 and 8 is subtracted from every byte after
+// Fig. 4(b), "Asym GEMM" of Sec. 7.2): the nibbles hold u = w + 8 and 8 is subtracted from every byte after
 // unpacking, 7 VALU operations per 8 weights instead of 3; the sums are then true sums, not sixteen-fold ones.
-// FG (with WBITS = 4, signed): the fine-grained recipe the paper argues against (Eq. (2), Fig. 2(b), Sec. 6.4): one
+// FG (with WBITS = 4, signed): the fine-grained recipe the paper argues against (Eq. (5), Fig. 2(b), Sec. 7.2): one
 // weight scale per group of 128 k and channel, p.s_w = s_g[K / 128][p.ldg].  A stage of the ring is exactly one
 // group, so every stage starts its integer sums from zero and ends by folding them, converted to fp32 and multiplied
 // by the group's scales, into a second, floating-point set of accumulators: per MFMA 8 extra VALU operations, twice
@@ -446,7 +446,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
             mfma_step(x1, w1, 1);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (FG) {
-                // Dq of Eq. (2) for this group: a group's sums are below 2^24 in magnitude, so the conversion is exact
+                // Dq of Eq. (5) for this group: a group's sums are below 2^24 in magnitude, so the conversion is exact
 #pragma unroll
                 for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll

@@ -127,7 +127,7 @@ constexpr int kTiledTileMax4 = 11;      // tiles of the signed int4 format
 // wbits = kWeightsUnsigned4: the 2 KB blocks with unsigned nibbles u = w + 8 (the paper's vanilla storage, GEMM only)
 constexpr int kWeightsUnsigned4 = 104;
 // wbits = kWeightsFineGrained4: signed int4 blocks with one scale per group of 128 k and channel (the fine-grained
-// recipe of Eq. (2)); its accumulators take twice the registers, hence its own, smaller set of tiles
+// recipe of Eq. (5)); its accumulators take twice the registers, hence its own, smaller set of tiles
 constexpr int kWeightsFineGrained4 = 204;
 constexpr int kFine128x256 = 1;  // 8 waves of 64 x 64
 constexpr int kFine256x128 = 2;  // 8 waves of 64 x 64, four down and two across

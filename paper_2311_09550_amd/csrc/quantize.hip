@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kRowThreads, 8) void quantize_act_kernel(const uint
     for (int i = 0; i < kCache; ++i) {
         const int c = threadIdx.x + i * kRowThreads;
         cache[i] = v4u{0, 0, 0, 0};
-        if (c < chunks) cache[i] = __builtin_nontemporal_load(src + c);  // read once: nothing worth keeping in the caches
+        if (c < chunks) cache[i] = src[c];
         amax = absmax8(cache[i], amax);
     }
     for (int c = threadIdx.x + kCache * kRowThreads; c < chunks; c += kRowThreads) amax = absmax8(src[c], amax);
@@ -186,14 +186,14 @@ __global__ __launch_bounds__(kRowThreads) void silu_mul_kernel(const uint16_t *_
 
 // The glue and the quantiser behind it in one pass: h = fp16(silu(gate) * up) is formed in registers (the same
 // arithmetic as silu_mul_kernel, so the same fp16 bits), then quantised per token exactly as quantize_act_kernel
-// would quantise it.  The fp16 intermediate never goes to memory.  A row is spread over 512 threads, so that two
-// workgroups share a compute unit and one's loads overlap the other's reduction and stores (with 1024 threads a
-// compute unit held one workgroup at a time and its phases ran back to back: 18 us against 13 at M = 1024); a thread
-// holds at most four chunks of h (I <= 16384), longer rows recompute h in the second pass.
-constexpr int kFusedThreads = 512;
-constexpr int kFusedCache = 4;
+// would quantise it.  The fp16 intermediate never goes to memory.  A row is spread over 1024 threads so that a
+// thread holds at most two chunks of h (I <= 16384); longer rows recompute h in the second pass.  (Measured at
+// M = 1024, I = 13824, cold input: 512 threads with four chunks each, two workgroups per compute unit, are 4 % slower;
+// non-temporal loads change nothing.)
+constexpr int kFusedThreads = 1024;
+constexpr int kFusedCache = 2;
 
-__global__ __launch_bounds__(kFusedThreads, 4) void silu_mul_quantize_kernel(const uint16_t *__restrict__ gate_up,
+__global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const uint16_t *__restrict__ gate_up,
                                                                           int8_t *__restrict__ xq, float *__restrict__ s_a,
                                                                           int I) {
     __shared__ float scratch[kFusedThreads / 64];
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kFusedThreads, 4) void silu_mul_quantize_kernel(con
     for (int i = 0; i < kFusedCache; ++i) {
         const int c = threadIdx.x + i * kFusedThreads;
         cache[i] = v4u{0, 0, 0, 0};
-        if (c < chunks) cache[i] = silu_mul8(__builtin_nontemporal_load(gate + c), __builtin_nontemporal_load(up + c));
+        if (c < chunks) cache[i] = silu_mul8(gate[c], up[c]);
         amax = absmax8(cache[i], amax);
     }
     for (int c = threadIdx.x + kFusedCache * kFusedThreads; c < chunks; c += kFusedThreads)

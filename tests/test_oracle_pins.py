@@ -551,7 +551,7 @@ def test_fine_grained_hand_worked_example(oracle):
 
 def test_fine_grained_equals_dequantise_first_matmul(oracle):
     """Scaling each group's integer sum equals multiplying by weights dequantised group-wise beforehand
-    (the W4A16-shaped Eq. (1)): checked against a float64 library matmul."""
+    (the W4A16-shaped Eq. (4)): checked against a float64 library matmul."""
     M, N, K = 9, 37, 640
     xq, wq, s_a, _ = synth.uniform_codes(M, N, K, config_id=60)
     s_g = synth.group_scales(N, K, 128, config_id=60)
@@ -573,7 +573,7 @@ def test_fine_grained_equals_dequantise_first_matmul(oracle):
 
 
 def test_fine_grained_reduces_to_per_channel(oracle):
-    """With the same scale in every group of a channel, and with one group spanning all of K, Eq. (2) is Eq. (3)."""
+    """With the same scale in every group of a channel, and with one group spanning all of K, Eq. (5) is Eq. (6)."""
     M, N, K = 7, 21, 512
     xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=62)
     wp = oracle.pack_w4(wq)
