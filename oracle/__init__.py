@@ -28,6 +28,18 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_selftest(out_dir: str | None = None) -> str:
+    """Compile the oracle together with its sanitizer driver (`selftest.c`) under AddressSanitizer and
+    UndefinedBehaviorSanitizer, host only; returns the executable's path.  Running it exercises every exported
+    function on ragged shapes with exact-size heap buffers."""
+    exe = os.path.join(out_dir or _HERE, "oracle_selftest")
+    cmd = ["gcc", "-O1", "-g", "-fopenmp", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-ffp-contract=off", "-Wall", "-Wextra", "-o", exe,
+           os.path.join(_HERE, "selftest.c"), _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 def _load():
     global _lib
     if _lib is None:

@@ -102,33 +102,56 @@ def _torch():
 
 
 def _stream():
-    return ctypes.c_void_p(_torch().cuda.current_stream().cuda_stream)
+    """torch's current stream on the current device: the library launches on the device that is current when it is
+    called, and `_on_current_device` holds every tensor argument to that device."""
+    torch = _torch()
+    return ctypes.c_void_p(torch.cuda.current_stream(torch.cuda.current_device()).cuda_stream)
+
+
+def _on_current_device(t, what):
+    torch = _torch()
+    if not t.is_cuda:
+        raise TypeError(f"{what}: expected a device tensor")
+    if t.device.index != torch.cuda.current_device():
+        raise ValueError(f"{what} is on {t.device} but the current device is cuda:{torch.cuda.current_device()}: "
+                         "call under torch.cuda.device(...) of the tensors' device")
 
 
 def _dev(t, dtype, what):
     torch = _torch()
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError(f"{what}: expected a contiguous device tensor of {dtype}")
+    _on_current_device(t, what)
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _shaped(t, shape, what):
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{what}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t
 
 
 def bound_call(name: str, *args):
     """A launch with its arguments marshalled once, for loops that repeat the same call: `name` is an entry point of
     the C ABI, `args` its arguments in the C order without the trailing stream (device tensors, ints, or None for a
-    NULL pointer).  Returns a function of no arguments that launches on torch's current stream and raises on an error
-    code.  The tensors are kept alive by the returned function; shapes and dtypes are the caller's responsibility here
-    (the C side still validates pointers, sizes and alignment)."""
+    NULL pointer).  Returns a function of no arguments that launches on torch's current stream of the tensors' device
+    (which the caller keeps current) and raises on an error code.  The tensors are kept alive by the returned
+    function; shapes and dtypes are the caller's responsibility here (the C side still validates pointers, sizes and
+    alignment)."""
     torch = _torch()
     fn = getattr(lib(), name)
     keep = [a for a in args if isinstance(a, torch.Tensor)]
     for t in keep:
         if not (t.is_cuda and t.is_contiguous()):
             raise TypeError(f"{name}: expected contiguous device tensors")
+    if len({t.device for t in keep}) > 1:
+        raise ValueError(f"{name}: the tensors are on different devices")
+    device = keep[0].device if keep else torch.device("cuda", torch.cuda.current_device())
     cargs = [ctypes.c_void_p(a.data_ptr()) if isinstance(a, torch.Tensor) else a for a in args]
     current_stream = torch.cuda.current_stream
 
     def call(_keep=keep):
-        code = fn(*cargs, ctypes.c_void_p(current_stream().cuda_stream))
+        code = fn(*cargs, ctypes.c_void_p(current_stream(device).cuda_stream))
         if code != 0:
             _check(code)
     return call
@@ -187,8 +210,8 @@ def w4a8_quantize_act(x, xq=None, s_a=None):
     """fp16 [M][K] -> (int8 [M][K], fp32 [M])."""
     torch = _torch()
     M, K = x.shape
-    xq = torch.empty((M, K), dtype=torch.int8, device=x.device) if xq is None else xq
-    s_a = torch.empty((M,), dtype=torch.float32, device=x.device) if s_a is None else s_a
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device) if xq is None else _shaped(xq, (M, K), "xq")
+    s_a = torch.empty((M,), dtype=torch.float32, device=x.device) if s_a is None else _shaped(s_a, (M,), "s_a")
     _check(lib().w4a8_quantize_act(_dev(x, torch.float16, "x"), _dev(xq, torch.int8, "xq"),
                                    _dev(s_a, torch.float32, "s_a"), M, K, _stream()))
     return xq, s_a
@@ -200,8 +223,9 @@ def w4a8_quantize_act_strided(x, xq=None, s_a=None):
     M, K = x.shape
     if not (x.is_cuda and x.dtype == torch.float16 and x.stride(1) == 1):
         raise TypeError("x: expected a device fp16 view with unit column stride")
-    xq = torch.empty((M, K), dtype=torch.int8, device=x.device) if xq is None else xq
-    s_a = torch.empty((M,), dtype=torch.float32, device=x.device) if s_a is None else s_a
+    _on_current_device(x, "x")
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device) if xq is None else _shaped(xq, (M, K), "xq")
+    s_a = torch.empty((M,), dtype=torch.float32, device=x.device) if s_a is None else _shaped(s_a, (M,), "s_a")
     _check(lib().w4a8_quantize_act_strided(ctypes.c_void_p(x.data_ptr()), x.stride(0), _dev(xq, torch.int8, "xq"),
                                            _dev(s_a, torch.float32, "s_a"), M, K, _stream()))
     return xq, s_a
@@ -399,6 +423,7 @@ def w4a8_linear_tiled_fp16(x, wt, s_w, out=None, s_a_out=None):
     N = s_w.shape[0]
     if not (x.is_cuda and x.dtype == torch.float16 and x.stride(1) == 1):
         raise TypeError("x: expected a device fp16 view with unit column stride")
+    _on_current_device(x, "x")
     if wt.numel() != w4a8_tiled_weight_bytes(N, K):
         raise ValueError("tiled weight array does not match (N, K)")
     out = torch.empty((M, N), dtype=torch.float16, device=x.device) if out is None else out

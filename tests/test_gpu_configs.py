@@ -19,23 +19,40 @@ SHAPES_70B = {"qkv": (10240, 8192), "o": (8192, 8192), "gate_up": (57344, 8192),
 SWEEP_M = [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
 
 
-@pytest.fixture(scope="module")
-def weights_70b(gpu):
-    """Weights of one 70B linear at a time (the largest is 0.9 GB as fp16 on the host): quantised, packed and tiled on
-    the GPU once per shape and reused over the whole M sweep."""
+SHAPES_7B = synth.LLAMA_SHAPES["7b"]
+DECODE_M_7B = [1, 4, 16]
+
+
+def _one_linear_at_a_time(gpu, shapes, config_id):
+    """Weights of one linear at a time (the largest of the 70B ones is 0.9 GB as fp16 on the host): quantised, packed
+    and tiled on the GPU once per shape and reused over the whole M sweep."""
     cache = {}
 
     def get(name):
         if name not in cache:
             cache.clear()
             gpu.cuda.empty_cache()
-            N, K = SHAPES_70B[name]
-            w = synth.weights_fp16(N, K, config_id=4)
+            N, K = shapes[name]
+            w = synth.weights_fp16(N, K, config_id=config_id)
             dwp, dsw = w4a8.w4a8_quantize_weights(gpu.from_numpy(w).cuda())
             dwt = w4a8.w4a8_tile_weights(dwp)
             cache[name] = (w, dwp, dsw, dwt)
         return cache[name]
 
+    return cache, get
+
+
+@pytest.fixture(scope="module")
+def weights_70b(gpu):
+    cache, get = _one_linear_at_a_time(gpu, SHAPES_70B, config_id=4)
+    yield get
+    cache.clear()
+    gpu.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module")
+def weights_7b(gpu):
+    cache, get = _one_linear_at_a_time(gpu, SHAPES_7B, config_id=2)
     yield get
     cache.clear()
     gpu.cuda.empty_cache()
@@ -57,10 +74,21 @@ def _sample(M, N, tag):
 @pytest.mark.parametrize("M", SWEEP_M)
 @pytest.mark.parametrize("name", list(SHAPES_70B))
 def test_llama70b_sweep_sampled_parity(gpu, oracle, weights_70b, name, M):
-    t = gpu
-    N, K = SHAPES_70B[name]
-    w, dwp, dsw, dwt = weights_70b(name)
-    x = synth.activations_fp16(M, K, config_id=4, tag=5)
+    _sampled_parity(gpu, oracle, SHAPES_70B[name], weights_70b(name), M, config_id=4)
+
+
+@pytest.mark.parametrize("M", DECODE_M_7B)
+@pytest.mark.parametrize("name", list(SHAPES_7B))
+def test_llama7b_decode_sampled_parity(gpu, oracle, weights_7b, name, M):
+    """The four fused linears of a LLaMA-7B layer at token-generation batch sizes (the shapes the decode-throughput
+    figure is quoted on)."""
+    _sampled_parity(gpu, oracle, SHAPES_7B[name], weights_7b(name), M, config_id=2)
+
+
+def _sampled_parity(t, oracle, shape, weights, M, config_id):
+    N, K = shape
+    w, dwp, dsw, dwt = weights
+    x = synth.activations_fp16(M, K, config_id=config_id, tag=5)
     dxq, dsa = w4a8.w4a8_quantize_act(t.from_numpy(x).cuda())
     acc = w4a8.w4a8_gemm_acc_i32(dxq, dwp)
     out = w4a8.w4a8_gemm(dxq, dsa, dwp, dsw)
