@@ -122,9 +122,11 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
  * w4a8_tile_weights: wp [N][K/2] (device) in -> wt (device, 16-byte aligned, w4a8_tiled_weight_bytes(N, K)) out.
  * w4a8_gemm_tiled: w4a8_gemm over wt instead of wp (all other arguments as there).  Every M is accepted, and one
  *   copy of the weights, the tiled one, serves them all: up to M = 16 (token generation) the weight-streaming kernels
- *   read wt directly, above that the large-M kernel runs (through w4a8_gemm_tiled_splitk it also fills the chip at a
- *   few dozen to a few hundred rows).  w4a8_gemm serves every M from the row-major array, at up to twice the tiled
- *   time for M between 17 and 512.
+ *   read wt directly; so they do from 17 to 64 tokens where all of K fits the registers of a workgroup (K <= 5120 for
+ *   49 to 64 tokens, K <= 7168 or 8192 for 17 to 32); above that, and for a longer K, the large-M kernel runs
+ *   (w4a8_gemm_tiled_splitk, which has a workspace, serves 17 to 64 tokens with the weight-streaming kernel at any K
+ *   and fills the chip with the large-M kernel at a few hundred rows).  w4a8_gemm serves every M from the row-major
+ *   array, at up to twice the tiled time for M between 17 and 512.
  */
 size_t w4a8_tiled_weight_bytes(int N, int K);
 int w4a8_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, void *stream);
@@ -156,6 +158,9 @@ int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const 
  * 40 tiles for M = 32, N = 5120): K is cut into slices, every (tile, slice) pair is a workgroup of the same kernel that
  * writes its raw int32 sums to a slab of the workspace, and a second kernel adds the slabs and applies Eq. (6),(7).
  * Integer sums do not depend on the order of addition: the output has the bits w4a8_gemm_tiled gives.
+ * With 17 to 64 tokens and no tile forced the slices are slices of the weight-streaming kernel instead (each workgroup
+ * streams its channels' share of one K slice, with its slice of the activations in registers): as few slices as let a
+ * slice of K fit the registers, often one, and then no slab at all.
  *   variant : output tile as for W4A8_TILING_PREFILL_TILED, 0 = library's choice;
  *   splits  : number of K slices, 0 = library's choice (1 when the tiles fill the chip: then this is w4a8_gemm_tiled
  *             and the workspace is not touched), at most 64 and at most K / 128 rounded up;

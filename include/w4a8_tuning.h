@@ -23,7 +23,9 @@ extern "C" {
  *                    + 10000000 * chunks of weight loads a wave keeps in flight (1, 2, 3, 4 or 8; 0 = library's choice)
  *                    + 100000000 * flags (1 = chunks of 16 channels even where a workgroup's range does not divide
  *                      evenly, 2 = non-temporal weight loads, 8 = default cache policy (neither = library's choice),
- *                      4 = activations read straight from memory instead of staged in LDS);
+ *                      4 = activations read straight from memory instead of staged in LDS, 16 = every wave stages
+ *                      its own k steps through a window of LDS: tiled weights only, 17 to 64 tokens, 8 waves (or 16
+ *                      for up to 32 tokens and K <= 8192), one or two chunks in flight);
  *   DECODE_STREAM:   row_tiles * 100 + waves, row_tiles in {1, 2}, waves in {4, 8};
  *   PREFILL:         output tile (rows of X x channels): 1 = 128 x 256 as 1 x 4 waves, 2 = 128 x 128,
  *                    3 = 128 x 160, 4 = 128 x 256 as 2 x 2 waves (operands staged through registers);
@@ -40,14 +42,16 @@ extern "C" {
  */
 #define W4A8_TILING_AUTO 0
 #define W4A8_TILING_DECODE_RESIDENT 1 /* persistent weight-streaming kernel, activations kept in registers:
-                                         M <= 16 with K <= 16384, or M <= 32 with K <= 8192; at most 512
-                                         channels per workgroup                                          */
+                                         M <= 16 with K <= 16384, or M <= 32 with K <= 8192 (flag 16: M <= 32
+                                         with K <= 8192, M <= 64 with K <= 5120); at most 512 channels per
+                                         workgroup                                                         */
 #define W4A8_TILING_DECODE_STREAM 2   /* general weight-streaming kernel, M <= 64                         */
 #define W4A8_TILING_PREFILL 3         /* LDS-staged output tiles on 32x32x32 int8 MFMA, for large M       */
 #define W4A8_TILING_PREFILL_TILED 4   /* the same over the tiled weight layout (any M; meant for large M)  */
 #define W4A8_TILING_DECODE_RESIDENT_TILED 5 /* tilings 1 and 2 reading the TILED weight array (`wp` = wt);        */
 #define W4A8_TILING_DECODE_STREAM_TILED 6   /* same limits and variants as 1 and 2                                 */
-#define W4A8_TILING_AUTO_TILED 7      /* library's choice over the TILED array: 5 or 6 up to M = 16, 4 above   */
+#define W4A8_TILING_AUTO_TILED 7      /* library's choice over the TILED array: 5 or 6 up to M = 16, 5 with flag 16
+                                         up to M = 64 where K allows, 4 otherwise                            */
 int w4a8_gemm_tuned(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_w,
                     void *out_fp16, int32_t *acc_i32, int M, int N, int K,
                     int tiling, int variant,

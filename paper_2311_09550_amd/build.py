@@ -8,9 +8,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libw4a8.so")
-SOURCES = ["api.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_prefill_dma.hip", "gemm_prefill_tiled.hip", "probes.hip",
+SOURCES = ["api.hip", "gemm_decode.hip", "gemm_decode_wide.hip", "gemm_prefill.hip", "gemm_prefill_dma.hip", "gemm_prefill_tiled.hip", "probes.hip",
            "quantize.hip"]
-HEADERS = ["common.hpp", "kernels.hpp", os.path.join("..", "..", "include", "w4a8.h"),
+HEADERS = ["common.hpp", "kernels.hpp", "gemm_decode_resident.hpp", os.path.join("..", "..", "include", "w4a8.h"),
            os.path.join("..", "..", "include", "w4a8_tuning.h")]
 
 # -packed-fp32-ops: keep the compiler from forming packed fp32 VALU instructions.

@@ -70,6 +70,24 @@ struct Plan {
     int prefill_tile;
 };
 
+bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool whole16, int aux, bool tiled, DecodeShape *out,
+                    int k_slices = 1, bool x_window = false);
+
+// 17 to 64 tokens over tiled weights: shape of the persistent kernel with per-wave staging, cut into the fewest K
+// slices for which an instantiation exists (slices_forced > 0: exactly that many).  False when there is none.
+bool wide_plan(int M, int N, int K, int slices_forced, int max_slices, DecodeShape *out) {
+    if (M <= 16 || M > kResidentMaxM) return false;
+    const int first = slices_forced > 0 ? slices_forced : 1, last = slices_forced > 0 ? slices_forced : max_slices;
+    for (int s = first; s <= last; ++s) {
+        DecodeShape t{};
+        if (resident_shape(M, N, K, 0, 0, 0, false, -1, true, &t, s, true)) {
+            *out = t;
+            return true;
+        }
+    }
+    return false;
+}
+
 // Shape of the persistent weight-streaming kernel for (M, N, K).  Returns false when a wave's share of the
 // activations would not fit in registers (then the general streaming kernel takes over).
 //   waves    : 8 or 16, 0 = library's choice: 8 while K <= 8192 and M <= 16, else 16;
@@ -82,16 +100,27 @@ struct Plan {
 //              only some 40 to 50 outstanding wave-wide loads and one chunk per wave already is that many; two where a
 //              range is exactly two chunks and M <= 4 (everything is then requested at once: 4 % on 13B's O);
 //   whole16  : chunks of 16 channels even where the range does not divide evenly;
-//   aux      : cache policy of the weight loads, -1 = library's choice (non-temporal: 5 to 10 % faster).
-bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool whole16, int aux, bool tiled, DecodeShape *out) {
-    const int ks_total = (K + 127) / 128;
+//   aux      : cache policy of the weight loads, -1 = library's choice (non-temporal: 5 to 10 % faster);
+//   k_slices : workgroups along K (raw sums only when more than one);
+//   x_window : every wave stages its own k steps (tiled weights, 17 to 64 tokens).  Then waves = 0 means 16 waves for
+//              two column tiles when their k steps fit, else 8.
+bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool whole16, int aux, bool tiled, DecodeShape *out,
+                    int k_slices, bool x_window) {
     const int mt = (M + 15) / 16;
     DecodeShape s{};
     s.resident = true;
     s.tiled = tiled;
     s.fused_quant = out->fused_quant;  // set by the caller that wants the kernel to quantise its own activations
     s.aux = aux < 0 ? 2 : aux;
-    if (waves == 0) waves = (mt == 1 && ks_total <= 64) ? 8 : 16;
+    s.x_window = x_window;
+    s.k_slices = k_slices < 1 ? 1 : k_slices;
+    const int ks_total = ((K + 127) / 128 + s.k_slices - 1) / s.k_slices;  // k steps of a slice
+    if (waves == 0) {
+        if (x_window)  // 8 waves wherever their k steps fit the registers (measured 5 to 13 % faster than 16)
+            waves = ((mt == 1 && ks_total > 64) || (mt == 2 && ks_total > 56)) ? 16 : 8;
+        else
+            waves = (mt == 1 && ks_total <= 64) ? 8 : 16;
+    }
     s.waves = waves;
     s.x_steps = (ks_total + waves - 1) / waves;
     // In the tiled array a 128-byte line holds 16 bytes of each of 8 consecutive channels: ranges that start on
@@ -99,7 +128,8 @@ bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool
     const int unit = tiled ? 8 : 4;
     int rows;
     if (grid <= 0) {
-        rows = ((N + compute_units() - 1) / compute_units() + 15) / 16 * 16;
+        const long long per_wg = ((long long)N * s.k_slices + compute_units() - 1) / compute_units();
+        rows = per_wg > kResidentMaxRows ? kResidentMaxRows : (int)((per_wg + 15) / 16 * 16);
         if (rows > kResidentMaxRows) rows = kResidentMaxRows;
     } else {
         rows = ((N + grid - 1) / grid + unit - 1) / unit * unit;
@@ -224,12 +254,15 @@ int choose_tiled_tile8(int M, int N) {
 int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
     pl->tiling = tiling;
     if (tiling == W4A8_TILING_AUTO_TILED) {
-        // one weight array for every M: the weight-streaming kernels up to M = 16, the large-M kernel above
+        // one weight array for every M: the weight-streaming kernels up to M = 16 and, where all of K fits a wave's
+        // registers, up to M = 64; the large-M kernel above
         if (M > 16)
-            pl->tiling = W4A8_TILING_PREFILL_TILED;
+            pl->tiling = wide_plan(M, N, K, 1, 1, &pl->decode) ? W4A8_TILING_DECODE_RESIDENT_TILED : W4A8_TILING_PREFILL_TILED;
         else
-            pl->tiling = resident_shape(M, N, K, 0, 0, 0, false, -1, true, &pl->decode) ? W4A8_TILING_DECODE_RESIDENT_TILED
-                                                                                         : W4A8_TILING_DECODE_STREAM_TILED;
+            pl->tiling = (resident_shape(M, N, K, 0, 0, 0, false, -1, true, &pl->decode, 1, true) ||
+                          resident_shape(M, N, K, 0, 0, 0, false, -1, true, &pl->decode))
+                             ? W4A8_TILING_DECODE_RESIDENT_TILED
+                             : W4A8_TILING_DECODE_STREAM_TILED;
     }
     const bool decode_tiled = pl->tiling == W4A8_TILING_DECODE_RESIDENT_TILED || pl->tiling == W4A8_TILING_DECODE_STREAM_TILED;
     if (pl->tiling == W4A8_TILING_DECODE_RESIDENT_TILED) pl->tiling = W4A8_TILING_DECODE_RESIDENT;
@@ -242,11 +275,17 @@ int choose_plan(int M, int N, int K, int tiling, int variant, Plan *pl) {
                                                                                           : W4A8_TILING_DECODE_STREAM;
     }
     if (pl->tiling == W4A8_TILING_DECODE_RESIDENT) {
-        if (M > 32) return W4A8_ERR_ARG;
+        if (M > kResidentMaxM) return W4A8_ERR_ARG;
         const int flags = variant / 100000000, prefetch = variant / 10000000 % 10, waves = variant / 100000 % 100;
-        if (!resident_shape(M, N, K, waves, variant % 100000, prefetch, (flags & 1) != 0, (flags & 2) ? 2 : (flags & 8) ? 0 : -1,
-                            decode_tiled, &pl->decode))
-            return W4A8_ERR_ARG;
+        // The library's own choice over the tiled array: per-wave staging from five tokens on (measured on LLaMA-13B
+        // shapes: level with the whole-row staging at 5 or 6 tokens, 6 to 20 % faster at 16, where the whole rows crowd
+        // or overflow LDS; below five tokens its extra round trip per window costs up to 8 % on a long K).
+        const bool want_window = (flags & 16) != 0 || (tiling == W4A8_TILING_AUTO_TILED && M >= 5);
+        auto shape = [&](bool window) {
+            return resident_shape(M, N, K, waves, variant % 100000, prefetch, (flags & 1) != 0,
+                                  (flags & 2) ? 2 : (flags & 8) ? 0 : -1, decode_tiled, &pl->decode, 1, window);
+        };
+        if (!(want_window && shape(true)) && !((flags & 16) == 0 && shape(false))) return W4A8_ERR_ARG;
         pl->decode.x_direct = (flags & 4) != 0;
     } else if (pl->tiling == W4A8_TILING_DECODE_STREAM) {
         if (M > kDecodeMaxM) return W4A8_ERR_ARG;
@@ -464,13 +503,39 @@ SplitPlan plan_split(int M, int N, int K, int variant, int splits) {
     return pl;
 }
 
+// What w4a8_gemm_tiled_splitk does with a shape.  Up to 16 tokens (no tile or slice count forced): the weight-streaming
+// kernels, no slabs.  17 to 64 tokens (no tile forced): the persistent kernel with per-wave staging, in as few K slices
+// as a wave's registers allow (or the forced count, if an instantiation exists for it).  Otherwise the LDS-staged
+// kernel with the slices of plan_split.
+struct SplitRoute {
+    enum Kind { kStream, kWide, kRing } kind;
+    DecodeShape wide;
+    SplitPlan ring;
+    size_t slab_bytes;  // workspace the route needs
+};
+
+SplitRoute split_route(int M, int N, int K, int variant, int splits) {
+    SplitRoute r{};
+    const size_t slab = (size_t)M * (size_t)N * sizeof(int32_t);
+    if (M <= 16 && variant == 0 && splits == 0) {
+        r.kind = SplitRoute::kStream;
+    } else if (variant == 0 && wide_plan(M, N, K, splits, 8, &r.wide)) {
+        r.kind = SplitRoute::kWide;
+        r.slab_bytes = r.wide.k_slices > 1 ? (size_t)r.wide.k_slices * slab : 0;
+    } else {
+        r.kind = SplitRoute::kRing;
+        r.ring = plan_split(M, N, K, variant, splits);
+        r.slab_bytes = r.ring.splits > 1 ? (size_t)r.ring.splits * slab : 0;
+    }
+    return r;
+}
+
 }  // namespace
 
 size_t w4a8_gemm_tiled_workspace_bytes(int M, int N, int K) {
     if (check_gemm_shape(M, N, K)) return 0;
-    // the library's own choice never exceeds 6 slices; a forced count is checked against the buffer at the call
-    const SplitPlan pl = plan_split(M, N, K, 0, 0);
-    return pl.splits > 1 ? (size_t)pl.splits * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+    // the library's own choice never exceeds 8 slices; a forced count is checked against the buffer at the call
+    return split_route(M, N, K, 0, 0).slab_bytes;
 }
 
 int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16, int M,
@@ -480,10 +545,29 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
     if (variant < 0 || variant > kTiledTileMax4 || splits < 0 || splits > 64) return W4A8_ERR_ARG;
     if (misaligned(xq) || misaligned(wt) || misaligned(out_fp16) || misaligned(s_w) || misaligned(workspace))
         return W4A8_ERR_ALIGN;
-    if (M <= 16 && variant == 0 && splits == 0)  // token generation: the weight-streaming kernels over the same array
+    const SplitRoute route = split_route(M, N, K, variant, splits);
+    if (route.kind == SplitRoute::kStream)  // token generation: the weight-streaming kernels over the same array
         return run_gemm(xq, s_a, wt, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_AUTO_TILED, 0, stream);
-    const SplitPlan pl = plan_split(M, N, K, variant, splits);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (route.kind == SplitRoute::kWide) {
+        const DecodeShape &ds = route.wide;
+        DecodeArgs d{};
+        d.xq = xq; d.s_a = s_a; d.wp = wt; d.s_w = s_w;
+        d.M = M; d.N = N; d.K = K;
+        d.rows_per_wg = ds.rows_per_wg;
+        d.chunk_rows = ds.chunk_rows;
+        if (ds.k_slices <= 1) {
+            d.out = out_fp16;
+            return launch_gemm_decode(d, false, ds, st) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+        }
+        if (!workspace) return W4A8_ERR_NULL;
+        if (workspace_bytes < route.slab_bytes) return W4A8_ERR_WORKSPACE;
+        d.acc_out = static_cast<int32_t *>(workspace);
+        if (launch_gemm_decode(d, true, ds, st) != hipSuccess) return W4A8_ERR_LAUNCH;
+        return launch_splitk_epilogue(d.acc_out, ds.k_slices, s_a, s_w, out_fp16, M, N, st) == hipSuccess ? W4A8_OK
+                                                                                                        : W4A8_ERR_LAUNCH;
+    }
+    const SplitPlan pl = route.ring;
     PrefillArgs a{};
     a.xq = xq; a.s_a = s_a; a.wp = wt; a.s_w = s_w;
     a.M = M; a.N = N; a.K = K; a.ldc = N;
@@ -536,10 +620,7 @@ int w4a8_gemm_tiled_splitk_static(const int8_t *xq, const float *s_a, const uint
     if (!xq || !s_a || !wt || !s_w || !out_fp16) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, N, K)) return e;
     if (variant < 0 || variant > kTiledTileMax4 || splits < 0 || splits > 64) return W4A8_ERR_ARG;
-    const bool streams_weights = M <= 16 && variant == 0 && splits == 0;  // then no slabs are used at all
-    const SplitPlan pl = plan_split(M, N, K, variant, splits);
-    const size_t need = (streams_weights || pl.splits <= 1) ? 0 : (size_t)pl.splits * (size_t)M * (size_t)N * sizeof(int32_t);
-    if (need > kStaticScratchBytes) return W4A8_ERR_WORKSPACE;
+    if (split_route(M, N, K, variant, splits).slab_bytes > kStaticScratchBytes) return W4A8_ERR_WORKSPACE;
     void *ws = nullptr;
     if (int e = static_scratch(&ws)) return e;
     return w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, out_fp16, M, N, K, variant, splits, ws, kStaticScratchBytes, stream);

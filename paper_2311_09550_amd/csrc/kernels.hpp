@@ -49,6 +49,8 @@ struct DecodeArgs {
     int x_lds_offset;    //   ... starting at this byte of the kernel's dynamic LDS
     int x16_lds_pitch;   // fused-quantiser form: the fp16 rows are staged too, rows this many bytes apart
     int x16_lds_offset;  //   ... starting here
+    int ks_per_slice;    // persistent kernel: k steps (of 128) per K slice; <= 0 = all of K in one slice.  With more than
+                         // one slice acc_out holds one [M][N] slab of raw sums per slice
 };
 
 constexpr int kResidentMaxRows = 512;  // channels per workgroup of the persistent kernel (their scales are staged in LDS,
@@ -67,12 +69,24 @@ struct DecodeShape {
     int rows_per_wg;  // resident: output channels per persistent workgroup, a multiple of 4, at most kResidentMaxRows
     int row_tiles;  // streaming: 16-row weight tiles per wave, 1 or 2
     bool tiled;     // DecodeArgs::wp is the tiled weight array (2 KB blocks) instead of the row-major one
+    bool x_window;  // resident: every wave stages its own k steps through a window of LDS (tiled weights; the only
+                    // form beyond 32 tokens)
+    int k_slices;   // resident: workgroups along K (0 or 1 = none); more than one only with raw sums, one slab each
 };
+
+// Token counts the persistent kernel serves: 32 with the activations staged whole or read directly, 64 with per-wave
+// staging.
+constexpr int kResidentMaxM = 64;
 
 bool decode_resident_supported(int M, int N, int K, const DecodeShape &s);
 // Per-device preparations (LDS allowance) of every instantiation of the persistent kernel, for the current device.
 hipError_t prepare_decode_kernels();
 hipError_t launch_gemm_decode(const DecodeArgs &p, bool acc_out, const DecodeShape &s, hipStream_t stream);
+// The instantiations with per-wave staging (mt = column tiles of 16 tokens, 2 to 4): whether one exists for the shape,
+// and its launch (prepare_only: the per-device preparations of all of them).
+bool decode_wide_supported(int mt, const DecodeShape &s);
+hipError_t launch_gemm_decode_wide(const DecodeArgs &p, bool acc_out, const DecodeShape &s, int mt, bool prepare_only,
+                                   hipStream_t stream);
 
 struct PrefillArgs {
     const int8_t *xq;

@@ -171,9 +171,11 @@ def test_split_workspace_is_a_pure_function_of_shape(L):
     f = w4a8.w4a8_gemm_tiled_workspace_bytes
     assert f(1024, 15360, 5120) == 0                      # 240 tiles of 256 x 256: no split
     assert f(16, 48, 40) == 0 and f(0, 16, 32) == 0       # outside the contract
-    for shape in [(32, 5120, 5120), (128, 5120, 13824), (64, 4096, 4096)]:
+    for shape in [(32, 5120, 13824), (128, 5120, 13824), (64, 4096, 11008), (100, 5120, 5120)]:
         n = f(*shape)
         assert n == f(*shape) and n % (shape[0] * shape[1] * 4) == 0 and 2 <= n // (shape[0] * shape[1] * 4) <= 8
+    # 17 to 64 tokens with a K that fits a wave's registers: the weight-streaming kernel in one slice, no slabs
+    assert f(32, 5120, 5120) == 0 and f(64, 4096, 4096) == 0 and f(64, 15360, 5120) == 0
 
 
 def test_probe_arguments(L):

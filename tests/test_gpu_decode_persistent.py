@@ -15,8 +15,8 @@ pytestmark = pytest.mark.gpu
 EPOCH, EPOCH_T = w4a8.TILING_DECODE_RESIDENT, w4a8.TILING_DECODE_RESIDENT_TILED
 
 
-def variant(grid=0, waves=0, prefetch=0, whole16=False, nt=None, x_direct=False):
-    flags = (1 if whole16 else 0) + (0 if nt is None else 2 if nt else 8) + (4 if x_direct else 0)
+def variant(grid=0, waves=0, prefetch=0, whole16=False, nt=None, x_direct=False, window=False):
+    flags = (1 if whole16 else 0) + (0 if nt is None else 2 if nt else 8) + (4 if x_direct else 0) + (16 if window else 0)
     return grid + 100000 * waves + 10000000 * prefetch + 100000000 * flags
 
 
@@ -92,3 +92,67 @@ def test_persistent_kernel_extreme_codes_at_the_longest_k(gpu, oracle):
     acc = w4a8.w4a8_gemm_tuned(t.from_numpy(xq).cuda(), None, wt, None, EPOCH_T, 0, want_acc=True, N=N)
     t.cuda.synchronize()
     assert np.all(acc.cpu().numpy() == 128 * 8 * K)
+
+
+# ---- every wave stages its own k steps through a window of LDS (tiled weights; the only form beyond 32 tokens and the
+# library's choice from five tokens on)
+
+WINDOW_SHAPES = [(16, 32), (17, 64), (1001, 160), (300, 1024), (520, 4096), (520, 5120), (130, 7168), (700, 8192)]
+
+
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 31, 32, 33, 47, 48, 49, 64])
+@pytest.mark.parametrize("N,K", WINDOW_SHAPES + [(520, 13824), (40, 16384)])
+def test_window_form_librarys_choice(gpu, oracle, M, N, K):
+    """Two to four column tiles, one and several windows per wave, ranges of one chunk and of many, ragged N and a K
+    that ends inside a k step; shapes whose K does not fit a wave's registers are refused (and skipped here: they are
+    served in K slices, below)."""
+    _run(gpu, oracle, M, N, K, True, variant(window=True), 64, f"window M={M} N={N} K={K}")
+
+
+@pytest.mark.parametrize("prefetch", [1, 2])
+@pytest.mark.parametrize("grid", [1, 7, 64, 256, 1000])
+@pytest.mark.parametrize("M,N,K", [(20, 5120, 512), (33, 1000, 2080), (64, 1300, 5120), (40, 516, 4128)])
+def test_window_form_grid_and_prefetch_variants(gpu, oracle, M, N, K, grid, prefetch):
+    if -(-N // grid) > 512:
+        pytest.skip("more than 512 channels per workgroup: outside this kernel's reach")
+    _run(gpu, oracle, M, N, K, True, variant(grid, 0, prefetch, window=True), 65,
+         f"window grid={grid} P={prefetch} M={M} N={N} K={K}")
+
+
+@pytest.mark.parametrize("M", [4, 5, 9, 16, 17, 32, 48, 64])
+@pytest.mark.parametrize("N,K", [(520, 5120), (1001, 160), (200, 13824)])
+def test_one_weight_array_serves_medium_m_too(gpu, oracle, M, N, K):
+    """w4a8_gemm_tiled routes 5 to 64 tokens to the window form when all of K fits a wave's registers (and to the
+    large-M kernel when it does not)."""
+    t = gpu
+    xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=66)
+    wp = oracle.pack_w4(wq)
+    acc_o, y32, _ = oracle.gemm(xq, s_a, wp, s_w)
+    wt = w4a8.w4a8_tile_weights(t.from_numpy(wp).cuda())
+    out = w4a8.w4a8_gemm_tiled(t.from_numpy(xq).cuda(), t.from_numpy(s_a).cuda(), wt, t.from_numpy(s_w).cuda())
+    t.cuda.synchronize()
+    assert_fp16_close(out.cpu().numpy(), y32, acc_o, f"gemm_tiled M={M} N={N} K={K}")
+
+
+@pytest.mark.parametrize("M,N,K,splits", [(64, 520, 13824, 3), (64, 520, 13824, 0), (32, 300, 13824, 2), (48, 1001, 8192, 2),
+                                          (33, 130, 28672, 0), (64, 200, 5120, 4), (17, 40, 4096, 8)])
+def test_window_form_in_k_slices(gpu, oracle, M, N, K, splits):
+    """A K too long for a wave's registers (or a forced slice count) is cut over workgroups: one slab of raw sums per
+    slice, added up and dequantised by the slab epilogue.  Integer sums: the bits of the unsliced result."""
+    t = gpu
+    xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=67)
+    wp = oracle.pack_w4(wq)
+    acc_o, y32, _ = oracle.gemm(xq, s_a, wp, s_w)
+    wt = w4a8.w4a8_tile_weights(t.from_numpy(wp).cuda())
+    dxq, dsa, dsw = t.from_numpy(xq).cuda(), t.from_numpy(s_a).cuda(), t.from_numpy(s_w).cuda()
+    if splits == 0:
+        need = w4a8.w4a8_gemm_tiled_workspace_bytes(M, N, K)
+        assert need > 0 and need % (M * N * 4) == 0
+        ws = t.empty((need,), dtype=t.uint8, device="cuda")
+        out = w4a8.w4a8_gemm_tiled_splitk(dxq, dsa, wt, dsw, ws=ws)
+    else:
+        out = w4a8.w4a8_gemm_tiled_splitk(dxq, dsa, wt, dsw, splits=splits)
+    ref = w4a8.w4a8_gemm_tiled(dxq, dsa, wt, dsw)
+    t.cuda.synchronize()
+    assert_fp16_close(out.cpu().numpy(), y32, acc_o, f"sliced M={M} N={N} K={K} splits={splits}")
+    assert_equal_bits(out.cpu().numpy().view(np.uint16), ref.cpu().numpy().view(np.uint16), "sliced vs w4a8_gemm_tiled")
