@@ -36,7 +36,8 @@ extern "C" {
  *                    9, 10 = the tiles of 4, 5 run by two sets of waves that split every 128-k stage between
  *                    them and add their integer sums before the epilogue (same bits; never the library's choice);
  *                    11 = 256 x 192 as 4 x 2 waves (the library pairs it with 1 where whole rounds of 256 x 256 tiles
- *                    leave columns over).
+ *                    leave columns over); 12 = 128 x 256 as 2 x 4 waves with a three-stage ring, one workgroup per
+ *                    compute unit (the library's choice where such tiles number no more than the compute units).
  * Exactly one of out_fp16 / acc_i32 must be non-NULL (s_a and s_w may be NULL
  * when acc_i32 is requested).
  */

@@ -171,15 +171,24 @@ int choose_prefill_tile(int M, int N) {
     return best;
 }
 
-// Output tile of the kernel over the tiled weight layout, by the same estimate.  Measured on LLaMA-13B shapes at
-// M = 1024 and 4096: one 256 x 256 workgroup per compute unit wins when its tiles fill the chip in whole rounds,
-// two 128 x 256 workgroups otherwise, the narrower tiles when N is too small for either.
+// Output tile of the kernel over the tiled weight layout.  A launch runs in rounds of as many workgroups as the chip
+// holds at once; the estimate is rounds x tile area x workgroups per compute unit / efficiency of the tile shape.
+// Efficiencies and the cost of a round in which a compute unit holds one workgroup instead of two ("alone") are
+// measured on LLaMA-13B shapes, M = 128 .. 4096 (warm weights, tiles timed in turn within one process):
+//   256 x 256         one per compute unit, the most work per operand byte staged;
+//   256 x 192         its narrower partner: fills one round where 256 x 256 would need two, or leave columns over;
+//   128 x 256 8 waves one per compute unit (three-stage ring): half the tile in 59 % of the time of 256 x 256;
+//   128 x 256 4 waves two per compute unit (two-stage ring); alone on a compute unit it takes 73 % of a shared round;
+//   128 x 160, 128 x 128, 64 x 128   two per compute unit, for N or M too small for the above;
+//   128 x 128 with the k halves of a stage on two wave sets, one per compute unit.
+// For 256 x 256 the estimate also covers the launch in two phases (whole rounds of 256 x 256, the columns left over as
+// one round of 256 x 192, see launch_tiled_in_phases).
 int choose_tiled_tile(int M, int N) {
-    struct Option { int id, bm, bn, per_cu; double eff; };
-    const Option options[] = {{kTiled256x256, 256, 256, 1, 1.00},
-                              {kTiled128x256, 128, 256, 2, 0.93},
-                              {kTiled128x160, 128, 160, 2, 0.75},
-                              {kTiled128x128, 128, 128, 2, 0.75}};
+    struct Option { int id, bm, bn, per_cu; double eff, alone; };
+    const Option options[] = {{kTiled256x256, 256, 256, 1, 1.00, 1.0},    {kTiled256x192, 256, 192, 1, 0.97, 1.0},
+                              {kTiled128x256, 128, 256, 2, 0.93, 0.73},   {kTiled128x256W8, 128, 256, 1, 0.85, 1.0},
+                              {kTiled128x160, 128, 160, 2, 0.66, 0.63},   {kTiled128x128, 128, 128, 2, 0.75, 0.67},
+                              {kTiled64x128, 64, 128, 2, 0.60, 0.75},     {kTiled128x128K2, 128, 128, 1, 0.60, 1.0}};
     const int cus = compute_units();
     // Medium M: when not even 128 x 128 tiles occupy three quarters of the compute units, run time is the length of
     // one workgroup's walk over K, and smaller tiles (more workgroups, each with a shorter stage) shorten it.
@@ -190,11 +199,19 @@ int choose_tiled_tile(int M, int N) {
     int best = kTiled256x256;
     double best_cost = 0;
     for (const Option &o : options) {
-        const long long tiles = (long long)((M + o.bm - 1) / o.bm) * ((N + o.bn - 1) / o.bn);
+        const long long tiles = count(o.bm, o.bn);
         const long long slots = (long long)cus * o.per_cu;
         const long long full = tiles / slots, rest = tiles % slots;
-        const double last = rest == 0 ? 0.0 : (o.per_cu == 1 || rest * 2 > slots ? 1.0 : 0.5);
-        const double cost = ((double)full + last) * o.bm * o.bn * o.per_cu / o.eff;
+        const double last = rest == 0 ? 0.0 : ((o.per_cu > 1 && rest <= cus) ? o.alone : 1.0);
+        double cost = ((double)full + last) * o.bm * o.bn * o.per_cu / o.eff;
+        if (o.id == kTiled256x256) {
+            const long long tiles_m = (M + 255) / 256, cols = (N + 255) / 256, per_round = cus / tiles_m;
+            if (per_round > 0 && cols > per_round && cols % per_round != 0) {
+                const long long rest_cols = N - (cols / per_round) * per_round * 256;
+                const double phased = (double)(cols / per_round) * 256 * 256 + 256 * 192 / 0.97;
+                if ((rest_cols + 191) / 192 <= per_round && phased < cost) cost = phased;
+            }
+        }
         if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = o.id; }
     }
     return best;
@@ -485,8 +502,8 @@ SplitPlan plan_split(int M, int N, int K, int variant, int splits) {
     }
     int s = splits;
     if (s == 0) {
-        static const int bm[] = {0, 256, 256, 128, 128, 128, 64, 64, 32, 128, 128, 256};
-        static const int bn[] = {0, 256, 256, 256, 160, 128, 128, 64, 128, 160, 128, 192};
+        static const int bm[] = {0, 256, 256, 128, 128, 128, 64, 64, 32, 128, 128, 256, 128};
+        static const int bn[] = {0, 256, 256, 256, 160, 128, 128, 64, 128, 160, 128, 192, 256};
         const long long tiles = count(bm[pl.tile], bn[pl.tile]);
         s = 1;
         if (M <= 512 && tiles <= (long_k ? cus : cus / 2)) {

@@ -99,7 +99,7 @@ def test_argument_validation_happens_before_any_launch(L):
     assert L.w4a8_silu_mul(p, p, 1, 12, null) == -2
     assert L.w4a8_silu_mul_quantize(p, null, p, 1, 32, null) == -1
     assert L.w4a8_silu_mul_quantize(p, p, p, 1, 24, null) == -2
-    assert t(p, p, p, p, p, null, 1, 16, 1024, 4, 12, p, big, null) == -7      # tiled layout: unknown tile id
+    assert t(p, p, p, p, p, null, 1, 16, 1024, 4, 13, p, big, null) == -7      # tiled layout: unknown tile id
     f = L.w4a8_linear_tiled_fp16
     assert f(null, 1024, p, p, p, null, 1, 16, 1024, null) == -1
     assert f(p, 1024, p, p, null, null, 1, 16, 1024, null) == -1
@@ -123,7 +123,7 @@ def test_argument_validation_happens_before_any_launch(L):
     sk = L.w4a8_gemm_tiled_splitk
     assert sk(p, p, p, p, null, 1, 16, 256, 0, 0, p, big, null) == -1
     assert sk(p, p, p, p, p, 1, 16, 48, 0, 0, p, big, null) == -2
-    assert sk(p, p, p, p, p, 1, 16, 256, 12, 0, p, big, null) == -7          # unknown tile
+    assert sk(p, p, p, p, p, 1, 16, 256, 13, 0, p, big, null) == -7          # unknown tile
     assert sk(p, p, p, p, p, 1, 16, 256, 0, 65, p, big, null) == -7          # too many slices
     assert sk(p, p, p, p, p, 1, 16, 256, 0, 2, null, big, null) == -1        # two slices need a workspace
     assert sk(p, p, p, p, p, 1, 16, 256, 0, 2, p, ctypes.c_size_t(127), null) == -4

@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 
 TILED = w4a8.TILING_PREFILL_TILED
 BASE_TILES = [1, 2, 3, 4, 5, 6, 7, 8]   # 256x256 (2x4 waves), 256x256 (4x2), 128x256, 128x160, 128x128, 64x128, 64x64, 32x128
-TILES = BASE_TILES + [9, 10, 11]        # signed int4 only: 128x160 and 128x128 with two wave sets splitting each stage's k; 256x192
+TILES = BASE_TILES + [9, 10, 11, 12]    # signed int4 only: 128x160 and 128x128 with two wave sets splitting each stage's k; 256x192;
+                                        # 128x256 on 8 waves
 
 
 def tiled_layout(wq):
