@@ -183,7 +183,8 @@ int choose_prefill_tile(int M, int N) {
 //   128 x 128 with the k halves of a stage on two wave sets, one per compute unit.
 // For 256 x 256 the estimate also covers the launch in two phases (whole rounds of 256 x 256, the columns left over as
 // one round of 256 x 192, see launch_tiled_in_phases).
-int choose_tiled_tile(int M, int N) {
+// max_id: the highest tile id the weight format has (the unsigned storage lacks the tiles above kTiledTileMax).
+int choose_tiled_tile(int M, int N, int max_id = kTiledTileMax4) {
     struct Option { int id, bm, bn, per_cu; double eff, alone; };
     const Option options[] = {{kTiled256x256, 256, 256, 1, 1.00, 1.0},    {kTiled256x192, 256, 192, 1, 0.97, 1.0},
                               {kTiled128x256, 128, 256, 2, 0.93, 0.73},   {kTiled128x256W8, 128, 256, 1, 0.85, 1.0},
@@ -199,12 +200,13 @@ int choose_tiled_tile(int M, int N) {
     int best = kTiled256x256;
     double best_cost = 0;
     for (const Option &o : options) {
+        if (o.id > max_id) continue;
         const long long tiles = count(o.bm, o.bn);
         const long long slots = (long long)cus * o.per_cu;
         const long long full = tiles / slots, rest = tiles % slots;
         const double last = rest == 0 ? 0.0 : ((o.per_cu > 1 && rest <= cus) ? o.alone : 1.0);
         double cost = ((double)full + last) * o.bm * o.bn * o.per_cu / o.eff;
-        if (o.id == kTiled256x256) {
+        if (o.id == kTiled256x256 && max_id >= kTiled256x192) {
             const long long tiles_m = (M + 255) / 256, cols = (N + 255) / 256, per_round = cus / tiles_m;
             if (per_round > 0 && cols > per_round && cols % per_round != 0) {
                 const long long rest_cols = N - (cols / per_round) * per_round * 256;
@@ -718,7 +720,9 @@ static int gemm_tiled_variant(const int8_t *xq, const float *s_a, const uint8_t 
     a.xq = xq; a.s_a = s_a; a.wp = wt; a.s_w = s_w;
     a.out = out_fp16; a.acc_out = acc_i32;
     a.M = M; a.N = N; a.K = K; a.ldc = N;
-    const int tile = variant ? variant : (wfmt == 8 ? choose_tiled_tile8(M, N) : choose_tiled_tile(M, N));
+    const int tile = variant ? variant
+                             : wfmt == 8 ? choose_tiled_tile8(M, N)
+                                         : choose_tiled_tile(M, N, wfmt == 4 ? kTiledTileMax4 : kTiledTileMax);
     return launch_gemm_prefill_tiled(a, want_acc, tile, static_cast<hipStream_t>(stream), wfmt) == hipSuccess
                ? W4A8_OK
                : W4A8_ERR_LAUNCH;

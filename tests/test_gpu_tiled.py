@@ -125,6 +125,27 @@ def test_unsigned_storage_variant(gpu, oracle, M, N, K, tile):
     assert_equal_bits(out.cpu().numpy().view(np.uint16), ref.cpu().numpy().view(np.uint16), "unsigned vs signed storage")
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 27648, 160), (512, 15360, 160), (2048, 5120, 160), (1024, 27648, 128)])
+def test_library_tile_choice_exists_for_every_weight_format(gpu, oracle, M, N, K):
+    """Shapes for which the signed int4 format is given one of its own tiles (128 x 256 on 8 waves, 256 x 192, the
+    two-phase launch): the unsigned storage and the int8 weights, which lack those tiles, must be given one they have.
+    Same codes, so all three outputs have the same bits; sampled rows against the oracle."""
+    t = gpu
+    xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=57)
+    dxq, dsa, dsw = t.from_numpy(xq).cuda(), t.from_numpy(s_a).cuda(), t.from_numpy(s_w).cuda()
+    wp = oracle.pack_w4(wq)
+    signed = w4a8.w4a8_gemm_tiled(dxq, dsa, w4a8.w4a8_tile_weights(t.from_numpy(wp).cuda()), dsw)
+    ut = w4a8.w4a8_tile_weights(t.from_numpy(oracle.pack_u4(wq.astype(np.int16) + 8)).cuda())
+    unsigned = w4a8.w4a8_gemm_tiled_unsigned(dxq, dsa, ut, dsw)
+    w8 = w4a8.w8a8_gemm_tiled(dxq, dsa, w4a8.w8a8_tile_weights(t.from_numpy(wq).cuda()), dsw)
+    t.cuda.synchronize()
+    assert_equal_bits(unsigned.cpu().numpy().view(np.uint16), signed.cpu().numpy().view(np.uint16), "unsigned vs signed")
+    assert_equal_bits(w8.cpu().numpy().view(np.uint16), signed.cpu().numpy().view(np.uint16), "int8 weights vs signed int4")
+    rows = [0, M // 3, M - 1]
+    acc_o, y32, _ = oracle.gemm(xq[rows], s_a[rows], wp, s_w)
+    assert_fp16_close(signed.cpu().numpy()[rows], y32, acc_o, f"library tile M={M} N={N} K={K}")
+
+
 def test_tiled_llama13b_prefill_sampled(gpu, oracle):
     """Full-size LLaMA-13B gate/up shape at M = 1024 in the default tile: rows of the output sampled and checked
     against the oracle one by one (raw sums bit-exact)."""
