@@ -53,6 +53,10 @@ int w4a8_version(void);
 /* Static, never-NULL description of an error code. */
 const char *w4a8_strerror(int err);
 
+/* Name of the HIP error behind the last W4A8_ERR_LAUNCH that an entry point returned on the calling thread
+ * ("hipSuccess" if none did): static, never NULL. */
+const char *w4a8_last_hip_error(void);
+
 /*
  * Per-token activation quantisation (Sec. 3 "Per tensor vs. Per token";
  * Eq. (2) with zero point 0; Table 1 row RTN_pt).

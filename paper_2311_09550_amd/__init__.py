@@ -35,6 +35,10 @@ def lib():
             raise ImportError(
                 f"{LIB_PATH} is missing: build the HIP library first "
                 "(python -m paper_2311_09550_amd.build); there is no fallback path")
+        # torch first: it ships its own HIP runtime, and the one loaded first serves the whole process.  Loaded the
+        # other way round, this library's kernels are registered with a runtime that torch's streams and memory do
+        # not belong to, and every launch is rejected.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         L.w4a8_version.restype = i
@@ -87,13 +91,15 @@ def lib():
                      "w4a8_quantize_weights", "w4a8_quantize_weights_clipped", "w4a8_silu_mul", "w4a8_silu_mul_quantize", "w4a8_pack_weights_host",
                      "w4a8_tile_weights", "w4a8_gemm_tiled"):
             getattr(L, name).restype = i
+        L.w4a8_last_hip_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
 
 
 def _check(code: int):
     if code != 0:
-        raise W4A8Error(code, lib().w4a8_strerror(code).decode())
+        detail = f" ({lib().w4a8_last_hip_error().decode()})" if code == -5 else ""
+        raise W4A8Error(code, lib().w4a8_strerror(code).decode() + detail)
 
 
 def _torch():

@@ -16,6 +16,16 @@ using namespace w4a8;
 
 constexpr int kDecodeMaxM = 64;
 
+// What HIP said when an entry point last returned W4A8_ERR_LAUNCH on this thread (hipSuccess if it never did).
+thread_local hipError_t last_hip_error = hipSuccess;
+
+inline int launched(hipError_t e) {
+    if (e == hipSuccess) return W4A8_OK;
+    last_hip_error = e;
+    (void)hipGetLastError();  // a rejected launch leaves its error in the runtime's per-thread slot: take it out
+    return W4A8_ERR_LAUNCH;
+}
+
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 inline int check_gemm_shape(int M, int N, int K) {
@@ -50,12 +60,14 @@ int static_scratch(void **ptr) {
     static std::mutex lookup_lock;
     int dev = 0;
     *ptr = nullptr;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return W4A8_ERR_LAUNCH;
+    if (int e = launched(hipGetDevice(&dev))) return e;
+    if (dev < 0 || dev >= kMaxDevices) return launched(hipErrorInvalidDevice);
     if (!known[dev].load(std::memory_order_acquire)) {
         std::lock_guard<std::mutex> hold(lookup_lock);
         if (!known[dev].load(std::memory_order_relaxed)) {
             void *p = nullptr;
-            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return W4A8_ERR_LAUNCH;
+            if (int e = launched(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)))) return e;
+            if (p == nullptr) return launched(hipErrorInvalidSymbol);
             addr[dev] = p;
             known[dev].store(true, std::memory_order_release);
         }
@@ -394,7 +406,7 @@ int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float 
         a.M = M; a.N = N; a.K = K; a.ldc = N;
         err = launch_gemm_prefill(a, want_acc, pl.prefill_tile, st);
     }
-    return err == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+    return launched(err);
 }
 
 }  // namespace
@@ -402,6 +414,8 @@ int run_gemm(const int8_t *xq, const float *s_a, const uint8_t *wp, const float 
 extern "C" {
 
 int w4a8_version(void) { return 100; }
+
+const char *w4a8_last_hip_error(void) { return hipGetErrorName(last_hip_error); }
 
 const char *w4a8_strerror(int err) {
     switch (err) {
@@ -421,8 +435,7 @@ int w4a8_quantize_act(const void *x_fp16, int8_t *xq, float *s_a, int M, int K, 
     if (!x_fp16 || !xq || !s_a) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, 1, K)) return e;
     if (misaligned(x_fp16) || misaligned(xq)) return W4A8_ERR_ALIGN;
-    return launch_quantize_act(x_fp16, K, xq, s_a, M, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK
-                                                                                                            : W4A8_ERR_LAUNCH;
+    return launched(launch_quantize_act(x_fp16, K, xq, s_a, M, K, static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_quantize_act_strided(const void *x_fp16, long long ldx, int8_t *xq, float *s_a, int M, int K, void *stream) {
@@ -430,8 +443,7 @@ int w4a8_quantize_act_strided(const void *x_fp16, long long ldx, int8_t *xq, flo
     if (int e = check_gemm_shape(M, 1, K)) return e;
     if (ldx < K || (ldx & 7) != 0) return W4A8_ERR_SHAPE;  // rows must not overlap and must start 16-byte aligned
     if (misaligned(x_fp16) || misaligned(xq)) return W4A8_ERR_ALIGN;
-    return launch_quantize_act(x_fp16, ldx, xq, s_a, M, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK
-                                                                                                              : W4A8_ERR_LAUNCH;
+    return launched(launch_quantize_act(x_fp16, ldx, xq, s_a, M, K, static_cast<hipStream_t>(stream)));
 }
 
 size_t w4a8_gemm_workspace_bytes(int M, int N, int K) {
@@ -469,7 +481,7 @@ int w4a8_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, void *stream
     if (!wp || !wt) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(1, N, K)) return e;
     if (misaligned(wp) || misaligned(wt)) return W4A8_ERR_ALIGN;
-    return launch_tile_weights(wp, wt, N, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+    return launched(launch_tile_weights(wp, wt, N, K, static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16, int M, int N,
@@ -577,14 +589,13 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
         d.chunk_rows = ds.chunk_rows;
         if (ds.k_slices <= 1) {
             d.out = out_fp16;
-            return launch_gemm_decode(d, false, ds, st) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+            return launched(launch_gemm_decode(d, false, ds, st));
         }
         if (!workspace) return W4A8_ERR_NULL;
         if (workspace_bytes < route.slab_bytes) return W4A8_ERR_WORKSPACE;
         d.acc_out = static_cast<int32_t *>(workspace);
-        if (launch_gemm_decode(d, true, ds, st) != hipSuccess) return W4A8_ERR_LAUNCH;
-        return launch_splitk_epilogue(d.acc_out, ds.k_slices, s_a, s_w, out_fp16, M, N, st) == hipSuccess ? W4A8_OK
-                                                                                                        : W4A8_ERR_LAUNCH;
+        if (int e = launched(launch_gemm_decode(d, true, ds, st))) return e;
+        return launched(launch_splitk_epilogue(d.acc_out, ds.k_slices, s_a, s_w, out_fp16, M, N, st));
     }
     const SplitPlan pl = route.ring;
     PrefillArgs a{};
@@ -594,7 +605,7 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
         a.out = out_fp16;
         const hipError_t e = variant == 0 ? launch_tiled_in_phases(a, false, pl.tile, st)
                                           : launch_gemm_prefill_tiled(a, false, pl.tile, st);
-        return e == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+        return launched(e);
     }
     // one launch must cover the problem (slabs are whole M x N matrices)
     if ((long long)M * K > 0xF0000000ll || (long long)tiled_weight_bytes(N, K, 4) > 0xF0000000ll) return W4A8_ERR_SHAPE;
@@ -603,9 +614,8 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
     a.acc_out = static_cast<int32_t *>(workspace);
     a.splits = pl.splits;
     a.stages_per_split = pl.stages_per_split;
-    if (launch_gemm_prefill_tiled(a, true, pl.tile, st) != hipSuccess) return W4A8_ERR_LAUNCH;
-    return launch_splitk_epilogue(a.acc_out, pl.splits, s_a, s_w, out_fp16, M, N, st) == hipSuccess ? W4A8_OK
-                                                                                                    : W4A8_ERR_LAUNCH;
+    if (int e = launched(launch_gemm_prefill_tiled(a, true, pl.tile, st))) return e;
+    return launched(launch_splitk_epilogue(a.acc_out, pl.splits, s_a, s_w, out_fp16, M, N, st));
 }
 
 int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16,
@@ -631,7 +641,7 @@ int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt,
     a.M = M; a.N = N; a.K = K;
     a.rows_per_wg = shape.rows_per_wg;
     a.chunk_rows = shape.chunk_rows;
-    return launch_gemm_decode(a, false, shape, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+    return launched(launch_gemm_decode(a, false, shape, static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_gemm_tiled_splitk_static(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
@@ -649,8 +659,8 @@ int w4a8_init(void) {
     void *ws = nullptr;
     if (int e = static_scratch(&ws)) return e;
     (void)compute_units();
-    if (prepare_tiled_kernels() != hipSuccess || prepare_decode_kernels() != hipSuccess) return W4A8_ERR_LAUNCH;
-    return W4A8_OK;
+    if (int e = launched(prepare_tiled_kernels())) return e;
+    return launched(prepare_decode_kernels());
 }
 
 // ---- W8A8 comparison variant: int8 weight codes in the tiled layout, the same kernels without the int4 conversion
@@ -664,7 +674,7 @@ int w8a8_tile_weights(const int8_t *w8, uint8_t *wt, int N, int K, void *stream)
     if (!w8 || !wt) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(1, N, K)) return e;
     if (misaligned(w8) || misaligned(wt)) return W4A8_ERR_ALIGN;
-    return launch_tile_weights8(w8, wt, N, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+    return launched(launch_tile_weights8(w8, wt, N, K, static_cast<hipStream_t>(stream)));
 }
 
 static int gemm_tiled_variant(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
@@ -701,9 +711,7 @@ int w4a8_gemm_fine_grained(const int8_t *xq, const float *s_a, const uint8_t *wt
     a.out = out_fp16;
     a.M = M; a.N = N; a.K = K; a.ldc = N; a.ldg = ldg;
     const int tile = variant ? variant : choose_fine_tile(M, N);
-    return launch_gemm_prefill_tiled(a, false, tile, static_cast<hipStream_t>(stream), kWeightsFineGrained4) == hipSuccess
-               ? W4A8_OK
-               : W4A8_ERR_LAUNCH;
+    return launched(launch_gemm_prefill_tiled(a, false, tile, static_cast<hipStream_t>(stream), kWeightsFineGrained4));
 }
 
 static int gemm_tiled_variant(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,
@@ -723,17 +731,14 @@ static int gemm_tiled_variant(const int8_t *xq, const float *s_a, const uint8_t 
     const int tile = variant ? variant
                              : wfmt == 8 ? choose_tiled_tile8(M, N)
                                          : choose_tiled_tile(M, N, wfmt == 4 ? kTiledTileMax4 : kTiledTileMax);
-    return launch_gemm_prefill_tiled(a, want_acc, tile, static_cast<hipStream_t>(stream), wfmt) == hipSuccess
-               ? W4A8_OK
-               : W4A8_ERR_LAUNCH;
+    return launched(launch_gemm_prefill_tiled(a, want_acc, tile, static_cast<hipStream_t>(stream), wfmt));
 }
 
 int w4a8_quantize_weights(const void *w_fp16, uint8_t *wp, float *s_w, int N, int K, void *stream) {
     if (!w_fp16 || !wp || !s_w) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(1, N, K)) return e;
     if (misaligned(w_fp16) || misaligned(wp)) return W4A8_ERR_ALIGN;
-    return launch_quantize_weights(w_fp16, wp, s_w, N, K, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK
-                                                                                                             : W4A8_ERR_LAUNCH;
+    return launched(launch_quantize_weights(w_fp16, wp, s_w, N, K, static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const float *beta, uint8_t *wp, float *s_w, int N,
@@ -741,26 +746,21 @@ int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const 
     if (!w_fp16 || !wp || !s_w) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(1, N, K)) return e;
     if (misaligned(w_fp16) || misaligned(wp)) return W4A8_ERR_ALIGN;
-    return launch_quantize_weights_clip(w_fp16, gamma, beta, wp, s_w, N, K, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? W4A8_OK
-               : W4A8_ERR_LAUNCH;
+    return launched(launch_quantize_weights_clip(w_fp16, gamma, beta, wp, s_w, N, K, static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_silu_mul(const void *gate_up_fp16, void *h_fp16, int M, int I, void *stream) {
     if (!gate_up_fp16 || !h_fp16) return W4A8_ERR_NULL;
     if (M < 1 || I < 8 || (I % 8) != 0 || M > 65535) return W4A8_ERR_SHAPE;
     if (misaligned(gate_up_fp16) || misaligned(h_fp16)) return W4A8_ERR_ALIGN;
-    return launch_silu_mul(gate_up_fp16, h_fp16, M, I, static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK
-                                                                                                          : W4A8_ERR_LAUNCH;
+    return launched(launch_silu_mul(gate_up_fp16, h_fp16, M, I, static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_silu_mul_quantize(const void *gate_up_fp16, int8_t *xq, float *s_a, int M, int I, void *stream) {
     if (!gate_up_fp16 || !xq || !s_a) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, 1, I)) return e;  // I is the K of the GEMM that consumes xq
     if (misaligned(gate_up_fp16) || misaligned(xq)) return W4A8_ERR_ALIGN;
-    return launch_silu_mul_quantize(gate_up_fp16, xq, s_a, M, I, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? W4A8_OK
-               : W4A8_ERR_LAUNCH;
+    return launched(launch_silu_mul_quantize(gate_up_fp16, xq, s_a, M, I, static_cast<hipStream_t>(stream)));
 }
 
 // ---- probes of what the chip sustains (context for the measurements, no part of the path)
@@ -769,8 +769,7 @@ int w4a8_probe_stream_read(const void *buf, size_t bytes, void *sink, void *stre
     if (!buf || !sink) return W4A8_ERR_NULL;
     if (bytes < 16) return W4A8_ERR_SHAPE;
     if (misaligned(buf)) return W4A8_ERR_ALIGN;
-    return launch_probe_stream_read(buf, bytes, static_cast<unsigned *>(sink), 8 * compute_units(),
-                                    static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+    return launched(launch_probe_stream_read(buf, bytes, static_cast<unsigned *>(sink), 8 * compute_units(), static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_probe_read_pattern(const void *buf, size_t bytes, void *sink, int pattern, int loads, int workgroups_per_cu,
@@ -780,17 +779,13 @@ int w4a8_probe_read_pattern(const void *buf, size_t bytes, void *sink, int patte
     if (misaligned(buf)) return W4A8_ERR_ALIGN;
     if (pattern < 0 || pattern > 5 || (loads != 4 && loads != 8 && loads != 16) || workgroups_per_cu < 1 || workgroups_per_cu > 64)
         return W4A8_ERR_ARG;
-    return launch_probe_read_pattern(buf, bytes, static_cast<unsigned *>(sink), pattern, loads,
-                                     workgroups_per_cu * compute_units(), static_cast<hipStream_t>(stream)) == hipSuccess
-               ? W4A8_OK
-               : W4A8_ERR_LAUNCH;
+    return launched(launch_probe_read_pattern(buf, bytes, static_cast<unsigned *>(sink), pattern, loads, workgroups_per_cu * compute_units(), static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_probe_mfma_int8(void *sink, int iters, int pattern, void *stream) {
     if (!sink) return W4A8_ERR_NULL;
     if (iters < 1 || iters > (1 << 24) || pattern < 0 || pattern > 1) return W4A8_ERR_ARG;
-    return launch_probe_mfma_i8(static_cast<int *>(sink), 2 * compute_units(), iters, pattern,
-                                static_cast<hipStream_t>(stream)) == hipSuccess ? W4A8_OK : W4A8_ERR_LAUNCH;
+    return launched(launch_probe_mfma_i8(static_cast<int *>(sink), 2 * compute_units(), iters, pattern, static_cast<hipStream_t>(stream)));
 }
 
 int w4a8_pack_weights_host(const int8_t *wq_host, uint8_t *wp_host, int N, int K) {

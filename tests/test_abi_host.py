@@ -45,6 +45,8 @@ def test_version_and_strerror(L):
         assert msg and msg not in seen
         seen.add(msg)
     assert "unknown" in w4a8.w4a8_strerror(-99)
+    # no entry point has returned W4A8_ERR_LAUNCH on this thread: validation errors never reach HIP
+    assert L.w4a8_last_hip_error() == b"hipSuccess"
 
 
 def test_workspace_bytes_is_a_pure_function_of_shape(L):
