@@ -150,26 +150,36 @@ def weights_13b(gpu):
     gpu.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("M", [1, 16, 128, 1024, 2048])
+@pytest.mark.parametrize("M", [1, 2, 16, 64, 128, 1024, 2048])
 def test_llama13b_layer_stack_stage_wise(gpu, oracle, weights_13b, M):
     """Hidden states -> quantiser -> QKV -> (the Q slice stands in for the attention output) -> quantiser -> O ->
-    quantiser -> gate+up -> SiLU(gate)*up -> quantiser -> down, as the benchmark's step runs it: tiled weights above
-    M = 64, row-major below; the fused SiLU*up + quantiser, checked against the two separate kernels."""
+    quantiser -> gate+up -> SiLU(gate)*up -> quantiser -> down, in the launch configuration the benchmark times at these
+    M: the one tiled weight copy through w4a8_gemm_tiled_splitk (weight-streaming kernel up to 64 tokens, in K slices
+    for the down projection; large-M kernel above); the fused SiLU*up + quantiser, checked against the two separate
+    kernels.  Up to 64 tokens the row-major entry must give the same bits, and up to 2 tokens so must the linear that
+    quantises its own activations."""
     t = gpu
     H = synth.LLAMA_SHAPES["13b"]["qkv"][1]
 
-    def gemm(name, dxq, dsa):
+    def gemm(name, dxq, dsa, x_fp16=None):
         w, dwp, dsw, dwt = weights_13b[name]
-        return w4a8.w4a8_gemm_tiled(dxq, dsa, dwt, dsw) if M > 64 else w4a8.w4a8_gemm(dxq, dsa, dwp, dsw)
+        out = w4a8.w4a8_gemm_tiled_splitk(dxq, dsa, dwt, dsw)
+        if M <= 64:
+            same = w4a8.w4a8_gemm(dxq, dsa, dwp, dsw)
+            assert bool((out.view(t.int16) == same.view(t.int16)).all()), name + ": row-major entry differs from the tiled one"
+        if M <= 2 and x_fp16 is not None:
+            fused = w4a8.w4a8_linear_tiled_fp16(x_fp16, dwt, dsw)
+            assert bool((out.view(t.int16) == fused.view(t.int16)).all()), name + ": self-quantising linear differs"
+        return out
 
     h = t.from_numpy(synth.activations_fp16(M, H, config_id=5, tag=1)).cuda()
     xq1, sa1 = w4a8.w4a8_quantize_act(h)
-    qkv = gemm("qkv", xq1, sa1)
+    qkv = gemm("qkv", xq1, sa1, h)
     attn = qkv[:, :H].contiguous()
     xq2, sa2 = w4a8.w4a8_quantize_act(attn)
-    o = gemm("o", xq2, sa2)
+    o = gemm("o", xq2, sa2, qkv[:, :H])   # the strided view the benchmark hands over
     xq3, sa3 = w4a8.w4a8_quantize_act(o)
-    gu = gemm("gate_up", xq3, sa3)
+    gu = gemm("gate_up", xq3, sa3, o)
     xq4, sa4 = w4a8.w4a8_silu_mul_quantize(gu)
     down = gemm("down", xq4, sa4)
     act = w4a8.w4a8_silu_mul(gu)
