@@ -516,8 +516,8 @@ SplitPlan plan_split(int M, int N, int K, int variant, int splits) {
     }
     int s = splits;
     if (s == 0) {
-        static const int bm[] = {0, 256, 256, 128, 128, 128, 64, 64, 32, 128, 128, 256, 128, 128};
-        static const int bn[] = {0, 256, 256, 256, 160, 128, 128, 64, 128, 160, 128, 192, 256, 256};
+        static const int bm[] = {0, 256, 256, 128, 128, 128, 64, 64, 32, 128, 128, 256, 128};
+        static const int bn[] = {0, 256, 256, 256, 160, 128, 128, 64, 128, 160, 128, 192, 256};
         const long long tiles = count(bm[pl.tile], bn[pl.tile]);
         s = 1;
         if (M <= 512 && tiles <= (long_k ? cus : cus / 2)) {

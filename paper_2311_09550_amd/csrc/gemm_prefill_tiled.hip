@@ -740,7 +740,6 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
                     case kTiled128x128K2: e = launch_tile<2, 2, 2, 2, 3, 4, false, false, 2>(q, acc_out, stream); break;
                     case kTiled256x192: e = launch_tile<2, 3, 4, 2, 3>(q, acc_out, stream); break;
                     case kTiled128x256W8: e = launch_tile<2, 2, 2, 4, 3>(q, acc_out, stream); break;
-                    case kTiled128x256W8R4: e = launch_tile<2, 2, 2, 4, 4>(q, acc_out, stream); break;
                     default: e = hipErrorInvalidConfiguration;
                 }
             } else if (wbits == 8) {

@@ -137,8 +137,7 @@ constexpr int kTiled256x192 = 11;       // 8 waves of 64 x 96 (int4 weights only
 constexpr int kTiledTileMax = 8;        // tiles every weight format has
 constexpr int kTiled128x256W8 = 12;     // 128 x 256 as 8 waves of 64 x 64, three-stage ring, one workgroup per compute unit
                                         // (int4 weights only): where 128 x 256 tiles number no more than the compute units
-constexpr int kTiled128x256W8R4 = 13;   // the same with a four-stage ring
-constexpr int kTiledTileMax4 = 13;      // tiles of the signed int4 format
+constexpr int kTiledTileMax4 = 12;      // tiles of the signed int4 format
 
 // wbits = 4: packed int4 codes (blocks of 2 KB); wbits = 8: int8 codes of the W8A8 comparison variant (blocks of 4 KB);
 // wbits = kWeightsUnsigned4: the 2 KB blocks with unsigned nibbles u = w + 8 (the paper's vanilla storage, GEMM only)
