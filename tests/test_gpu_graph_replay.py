@@ -1,0 +1,75 @@
+"""The entry points under HIP graph capture: captured once after w4a8_init (which makes every per-device preparation up
+front, so that no launch has to make one while a capture is open), replayed several times with new input contents and
+with eager work and synchronisations between the replays; every replay must reproduce the eager result bit for bit."""
+import numpy as np
+import pytest
+
+import paper_2311_09550_amd as w4a8
+from paper_2311_09550_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _linear(t, M, wt, s_w, x, xq, s_a, out, how, ws):
+    if how == "fused":
+        w4a8.w4a8_linear_tiled_fp16(x, wt, s_w, out=out)
+        return
+    w4a8.w4a8_quantize_act(x, xq, s_a)
+    if how == "tiled":
+        w4a8.w4a8_gemm_tiled(xq, s_a, wt, s_w, out=out)
+    elif how == "splitk":
+        w4a8.w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, ws=ws, out=out)
+    else:
+        w4a8.w4a8_gemm_tiled_splitk_static(xq, s_a, wt, s_w, out)
+
+
+# (M, N, K, entry): whole-row staging, fused quantiser, per-wave windows, K slices of the weight-streaming kernel (slabs in a
+# workspace and in the static array), K slices of the large-M kernel, the two-phase large-M launch
+CASES = [(3, 520, 2080, "tiled"), (2, 520, 2080, "fused"), (16, 1000, 5120, "tiled"), (48, 300, 13824, "splitk"),
+         (48, 300, 13824, "static"), (130, 520, 8192, "splitk"), (130, 520, 8192, "static"), (300, 17000, 160, "tiled")]
+
+
+@pytest.mark.parametrize("M,N,K,how", CASES)
+def test_graph_replays_match_eager(gpu, oracle, M, N, K, how):
+    t = gpu
+    w4a8.w4a8_init()
+    w = t.from_numpy(synth.weights_fp16(N, K, config_id=90)).cuda()
+    wp, s_w = w4a8.w4a8_quantize_weights(w)
+    wt = w4a8.w4a8_tile_weights(wp)
+    xs = [t.from_numpy(synth.activations_fp16(M, K, config_id=90, tag=10 + i)).cuda() for i in range(4)]
+    x = xs[0].clone()
+    xq = t.empty((M, K), dtype=t.int8, device="cuda")
+    s_a = t.empty((M,), dtype=t.float32, device="cuda")
+    out = t.empty((M, N), dtype=t.float16, device="cuda")
+    ws = t.empty((max(16, 8 * M * N * 4),), dtype=t.uint8, device="cuda")
+
+    eager = []
+    for xi in xs:
+        x.copy_(xi)
+        _linear(t, M, wt, s_w, x, xq, s_a, out, how, ws)
+        eager.append(out.clone())
+    t.cuda.synchronize()
+
+    x.copy_(xs[0])
+    side = t.cuda.Stream()
+    side.wait_stream(t.cuda.current_stream())
+    graph = t.cuda.CUDAGraph()
+    with t.cuda.stream(side):
+        with t.cuda.graph(graph):
+            _linear(t, M, wt, s_w, x, xq, s_a, out, how, ws)
+    t.cuda.current_stream().wait_stream(side)
+    for rnd in range(2):
+        for i, xi in enumerate(xs):
+            x.copy_(xi)                      # eager work between the replays
+            out.fill_(7.0)
+            ws[: min(ws.numel(), 1 << 16)].fill_(0x5A)
+            graph.replay()
+            t.cuda.synchronize()
+            assert bool((out.view(t.int16) == eager[i].view(t.int16)).all()), f"replay {rnd}.{i} of {how} M={M} differs from eager"
+    # and the eager result is the oracle's
+    xq_o, s_a_o = oracle.quantize_act(xs[3].cpu().numpy())
+    wq_o, s_w_o = oracle.quantize_weights_rtn(w.cpu().numpy())
+    acc_o, y32, _ = oracle.gemm(xq_o, s_a_o, oracle.pack_w4(wq_o), s_w_o)
+    got = eager[3].cpu().numpy().astype(np.float64)
+    y = y32.astype(np.float64)
+    assert np.all(np.abs(got - y) <= np.maximum(2.0 ** -10 * np.abs(y), 2.0 ** -24))
