@@ -12,15 +12,15 @@
 //     order gives the same bits);
 //   * the dequantisation of Eq. (6),(7) is applied once, to the complete sum.
 //
-// gemm_decode_resident_kernel (M <= 16 and friends): a persistent workgroup
-// walks over many 16-channel row blocks.  A wave's k steps are the same for
-// every row block, so its activation operands are loaded and permuted ONCE
-// and stay in registers; per row block only weights are loaded, and the loads
-// of the next block are issued as soon as a register is consumed, so a wave
-// always has its full set of 16-byte loads in flight.
+// gemm_decode_resident_kernel (gemm_decode_resident.hpp; instantiated here for up to 32 tokens with the activations
+// staged whole or read directly, and in gemm_decode_wide.hip for up to 64 tokens with per-wave staging): a persistent
+// workgroup walks over many 16-channel row blocks.  A wave's k steps are the same for every row block, so its
+// activation operands are brought in ONCE and stay in registers; per row block only weights are loaded, and the loads
+// of the next block are issued as soon as a register is consumed, so a wave always has its full set of 16-byte loads
+// in flight.
 //
-// gemm_decode_stream_kernel: the general form (any M <= 64, any K), one row
-// block per workgroup, activations re-read from cache for every block.
+// gemm_decode_stream_kernel (this file): the general form (any M <= 64, any K), one row block per workgroup,
+// activations re-read from cache for every block.
 #include "gemm_decode_resident.hpp"
 
 namespace w4a8 {
