@@ -3,11 +3,13 @@
 rocprofv3 writes one CSV per run (`*_counter_collection.csv` for `--pmc`, `*_kernel_stats.csv` / `*_kernel_trace.csv`
 for `--kernel-trace --stats`).  This script reads them, never the GPU:
 
-    python -m paper_2311_09550_amd.counters traffic --fetch DIR --write DIR --kernel NAME --key KEY --gemms N
+    python -m paper_2311_09550_amd.counters traffic --fetch DIR --write DIR --kernel NAME --key KEY --calls-per-dispatch F
         HBM-side bytes per GEMM call of the kernel whose name contains NAME: FETCH_SIZE and WRITE_SIZE (KiB-like units
         per dispatch), each scaled by what the same counter reads for the 256 MiB `__amd_rocclr_copyBuffer` dispatches
         of `bench.py --copy-calibration` in the same run, summed over all dispatches of the kernel and divided by the
-        N GEMM calls of the run (a GEMM call may be more than one dispatch; N = 0: one call per dispatch).  Merges the result under KEY into
+        GEMM calls of the run = dispatches x F (a GEMM call may be more than one dispatch: the timed step makes 4 calls
+        in 5 dispatches, F = 0.8; default F = 1); with --by-grid instead the mean over the kernel's grid sizes of the
+        mean per dispatch (the decode section: one GEMM shape per grid size, equal weights).  Merges the result under KEY into
         profiles/traffic_counters.json together with the hash of the kernel sources, which `bench.py` checks before it
         reports the figure.  Prints a markdown table per (kernel, grid size).
 
@@ -96,10 +98,21 @@ def cmd_traffic(a):
     n_w = sum(len(g["write"]) for g in groups.values())
     if n_f != n_w:
         print(f"\n(the two runs saw {n_f} and {n_w} dispatches: each total is divided by its own run's GEMM calls)")
-    gemms = a.gemms if a.gemms > 0 else n_f   # 0: every dispatch is one GEMM call
-    per_f, per_w = total_f / gemms, total_w * (n_f / n_w if n_w else 1.0) / gemms
-    print(f"\nPer GEMM call ({gemms} calls in the run): {per_f / 1e6:.2f} MB fetched + {per_w / 1e6:.2f} MB written = "
-          f"{(per_f + per_w) / 1e6:.2f} MB.")
+    gemms = n_f * a.calls_per_dispatch
+    if a.by_grid:
+        # one GEMM shape per grid size, every shape with the same weight, however many launches each had
+        by_grid = collections.defaultdict(lambda: {"fetch": [], "write": []})
+        for (name, grid), g in groups.items():
+            by_grid[grid]["fetch"] += g["fetch"]
+            by_grid[grid]["write"] += g["write"]
+        per_f = statistics.mean(statistics.mean(g["fetch"]) for g in by_grid.values())
+        per_w = statistics.mean(statistics.mean(g["write"]) for g in by_grid.values())
+        print(f"\nPer GEMM call, mean over the {len(by_grid)} grid sizes (one GEMM shape each) of the mean per dispatch: "
+              f"{per_f / 1e6:.2f} MB fetched + {per_w / 1e6:.2f} MB written = {(per_f + per_w) / 1e6:.2f} MB.")
+    else:
+        per_f, per_w = total_f / gemms, total_w * (n_f / n_w if n_w else 1.0) / gemms
+        print(f"\nPer GEMM call ({gemms:.0f} calls in {n_f} dispatches): {per_f / 1e6:.2f} MB fetched + {per_w / 1e6:.2f} MB written = "
+              f"{(per_f + per_w) / 1e6:.2f} MB.")
     try:
         prof = json.load(open(TRAFFIC_FILE))
     except (OSError, ValueError):
@@ -109,7 +122,7 @@ def cmd_traffic(a):
         prof = {"source_hash": h, "kernels": {}}
     prof["summary"] = a.summary
     prof["kernels"][a.key] = {"traffic_bytes_per_launch": round(per_f + per_w), "fetch_bytes_per_launch": round(per_f),
-                              "write_bytes_per_launch": round(per_w), "gemm_calls": gemms,
+                              "write_bytes_per_launch": round(per_w), "gemm_calls": round(gemms),
                               "fetch_scale": round(fscale, 4), "write_scale": round(wscale, 4)}
     with open(TRAFFIC_FILE, "w") as f:
         json.dump(prof, f, indent=1, sort_keys=True)
@@ -159,7 +172,9 @@ def main():
     t.add_argument("--write", required=True)
     t.add_argument("--kernel", required=True)
     t.add_argument("--key", required=True)
-    t.add_argument("--gemms", type=int, default=0, help="GEMM calls in the run; 0 = one per dispatch")
+    t.add_argument("--calls-per-dispatch", type=float, default=1.0, help="GEMM calls per dispatch of the kernel")
+    t.add_argument("--by-grid", action="store_true",
+                   help="mean over grid sizes of the mean per dispatch (one GEMM shape per grid size, equal weights)")
     t.add_argument("--summary", default="profiles/")
     s = sub.add_parser("sq")
     s.add_argument("--dir", required=True)
