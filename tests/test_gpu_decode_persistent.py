@@ -156,3 +156,32 @@ def test_window_form_in_k_slices(gpu, oracle, M, N, K, splits):
     t.cuda.synchronize()
     assert_fp16_close(out.cpu().numpy(), y32, acc_o, f"sliced M={M} N={N} K={K} splits={splits}")
     assert_equal_bits(out.cpu().numpy().view(np.uint16), ref.cpu().numpy().view(np.uint16), "sliced vs w4a8_gemm_tiled")
+
+
+def _random_shapes(count, seed):
+    g = synth.rng(4242, seed)
+    shapes = []
+    for _ in range(count):
+        M = int(g.integers(1, 65))
+        N = int(g.integers(1, 2500))
+        K = 32 * int(g.integers(1, 257))          # 32 .. 8192, any multiple of 32 (ragged against the 128-wide k steps)
+        shapes.append((M, N, K))
+    return shapes
+
+
+@pytest.mark.parametrize("M,N,K", _random_shapes(48, 1))
+def test_one_copy_entries_on_seeded_random_shapes(gpu, oracle, M, N, K):
+    """Seeded random (M <= 64, N, K) through both one-copy entries: whichever kernel the library picks (whole-row
+    staging, per-wave windows, K slices, or the large-M kernel where K does not fit), the raw sums behind the fp16
+    output are the oracle's."""
+    t = gpu
+    xq, wq, s_a, s_w = synth.uniform_codes(M, N, K, config_id=68)
+    wp = oracle.pack_w4(wq)
+    acc_o, y32, _ = oracle.gemm(xq, s_a, wp, s_w)
+    wt = w4a8.w4a8_tile_weights(t.from_numpy(wp).cuda())
+    dxq, dsa, dsw = t.from_numpy(xq).cuda(), t.from_numpy(s_a).cuda(), t.from_numpy(s_w).cuda()
+    a = w4a8.w4a8_gemm_tiled(dxq, dsa, wt, dsw)
+    b = w4a8.w4a8_gemm_tiled_splitk(dxq, dsa, wt, dsw)
+    t.cuda.synchronize()
+    assert_fp16_close(a.cpu().numpy(), y32, acc_o, f"gemm_tiled M={M} N={N} K={K}")
+    assert_equal_bits(b.cpu().numpy().view(np.uint16), a.cpu().numpy().view(np.uint16), "splitk entry vs gemm_tiled")
