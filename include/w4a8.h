@@ -125,7 +125,7 @@ int w4a8_gemm_acc_i32(const int8_t *xq, const uint8_t *wp, int32_t *acc, int M, 
  * w4a8_tiled_weight_bytes: size of wt in bytes (0 for a shape outside the contract).
  * w4a8_tile_weights: wp [N][K/2] (device) in -> wt (device, 16-byte aligned, w4a8_tiled_weight_bytes(N, K)) out.
  * w4a8_gemm_tiled: w4a8_gemm over wt instead of wp (all other arguments as there).  Every M is accepted, and one
- *   copy of the weights, the tiled one, serves them all: up to M = 16 (token generation) the weight-streaming kernels
+ *   copy of the weights, the tiled one, serves them all: up to 16 tokens (token generation) the weight-streaming kernels
  *   read wt directly; so they do from 17 to 64 tokens where all of K fits the registers of a workgroup (K <= 5120 for
  *   49 to 64 tokens, K <= 7168 or 8192 for 17 to 32); above that, and for a longer K, the large-M kernel runs
  *   (w4a8_gemm_tiled_splitk, which has a workspace, serves 17 to 64 tokens with the weight-streaming kernel at any K
