@@ -21,16 +21,21 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 
 
 def source_hash() -> str:
-    """Hash of the kernel sources and public headers: ties a profile of hardware counters to the build it was taken
-    from (bench.py reports a counter figure only when the hashes agree)."""
+    """Hash of the code of the kernel sources and public headers (comments and white space left out, so that an edit
+    of the documentation does not count as another build): ties a profile of hardware counters to the build it was
+    taken from (bench.py reports a counter figure only when the hashes agree)."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for d in (CSRC, os.path.join(HERE, "..", "include")):
         for name in sorted(os.listdir(d)):
             if name.endswith((".hip", ".hpp", ".h")):
+                with open(os.path.join(d, name), "r", encoding="utf-8") as f:
+                    text = f.read()
+                text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)   # block comments
+                text = re.sub(r"//[^\n]*", " ", text)                 # line comments (no string here holds "//")
                 h.update(name.encode())
-                with open(os.path.join(d, name), "rb") as f:
-                    h.update(f.read())
+                h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 
