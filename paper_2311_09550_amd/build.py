@@ -73,5 +73,42 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(verbose: bool = False) -> str:
+    """The library with its HOST code under AddressSanitizer and UndefinedBehaviorSanitizer (device code as usual), and
+    the C driver tests/abi_selftest.c linked against it.  Returns the driver's path; running it needs no GPU."""
+    root = os.path.dirname(HERE)
+    objdir = os.path.join(HERE, "_build", "hostsan")
+    os.makedirs(objdir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    procs, objs = [], []
+    for src in SOURCES:
+        o = os.path.join(objdir, src + ".o")
+        objs.append(o)
+        cmd = [hipcc(), *FLAGS, *san, "-c", os.path.join(CSRC, src), "-o", o]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for cmd, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            sys.stderr.write(out)
+            raise RuntimeError("hipcc failed: " + " ".join(cmd))
+    lib = os.path.join(objdir, "libw4a8_hostsan.so")
+    subprocess.run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                    "-shared-libsan", "-o", lib, *objs], check=True)
+    exe = os.path.join(objdir, "abi_selftest")
+    # the sanitizer runtime of hipcc's clang lives outside the loader's default path
+    rt = subprocess.run([hipcc(), "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True).stdout.strip()
+    rpaths = ["-Wl,-rpath," + objdir] + (["-Wl,-rpath," + os.path.dirname(rt)] if os.path.isabs(rt) else [])
+    subprocess.run([hipcc(), "-x", "c", os.path.join(root, "tests", "abi_selftest.c"), "-x", "none", "-fsanitize=address",
+                    "-fsanitize=undefined", "-fno-sanitize-recover=all", "-shared-libsan", "-g", "-o", exe, lib, *rpaths],
+                   check=True)
+    return exe
+
+
 if __name__ == "__main__":
-    print(build_library(force=True, verbose=True))
+    if "--host-sanitize" in sys.argv[1:]:
+        print(build_host_sanitized(verbose=True))
+    else:
+        print(build_library(force=True, verbose=True))
