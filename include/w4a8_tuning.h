@@ -19,7 +19,7 @@ extern "C" {
  * every shape.  `tiling` is one of W4A8_TILING_*.  `variant` refines it
  * (0 = library default, W4A8_ERR_ARG if not available for the shape):
  *   DECODE_RESIDENT: workgroups (size of the persistent grid, 0 = library's choice)
- *                    + 100000 * waves (8 or 16, 0 = library's choice)
+ *                    + 100000 * waves (8 or 16, 0 = library's choice: 8 wherever a wave's k steps fit its registers)
  *                    + 10000000 * chunks of weight loads a wave keeps in flight (1, 2, 3, 4 or 8; 0 = library's choice)
  *                    + 100000000 * flags (1 = chunks of 16 channels even where a workgroup's range does not divide
  *                      evenly, 2 = non-temporal weight loads, 8 = default cache policy (neither = library's choice),

@@ -102,7 +102,7 @@ bool wide_plan(int M, int N, int K, int slices_forced, int max_slices, DecodeSha
 
 // Shape of the persistent weight-streaming kernel for (M, N, K).  Returns false when a wave's share of the
 // activations would not fit in registers (then the general streaming kernel takes over).
-//   waves    : 8 or 16, 0 = library's choice: 8 while K <= 8192 and M <= 16, else 16;
+//   waves    : 8 or 16, 0 = library's choice (8 wherever a wave's k steps fit its registers, see below);
 //   grid     : workgroups wanted, 0 = library's choice.  A workgroup's range is N / grid rounded up to whole cache
 //              lines of the weight array (8 channels in the tiled array, 4 in the row-major one).  The library's own
 //              choice is one workgroup per compute unit with the range rounded up to whole 16-channel chunks
@@ -127,14 +127,20 @@ bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool
     s.x_window = x_window;
     s.k_slices = k_slices < 1 ? 1 : k_slices;
     const int ks_total = ((K + 127) / 128 + s.k_slices - 1) / s.k_slices;  // k steps of a slice
+    // 8 waves wherever their k steps fit the registers (measured 4 to 13 % faster than 16): up to 14 steps per wave
+    // for one column tile (K <= 14336), 7 for two with per-wave staging, 5 for three and four
     if (waves == 0) {
-        if (x_window)  // 8 waves wherever their k steps fit the registers (measured 5 to 13 % faster than 16)
-            waves = ((mt == 1 && ks_total > 64) || (mt == 2 && ks_total > 56)) ? 16 : 8;
+        if (mt == 1)
+            waves = ks_total <= 112 ? 8 : 16;
+        else if (x_window)
+            waves = (mt == 2 && ks_total > 56) ? 16 : 8;
         else
-            waves = (mt == 1 && ks_total <= 64) ? 8 : 16;
+            waves = 16;
     }
     s.waves = waves;
     s.x_steps = (ks_total + waves - 1) / waves;
+    // beyond 8 steps per wave only 11 and 14 are instantiated; a wave's surplus steps load nothing and multiply zeros
+    if (mt == 1 && waves == 8 && s.x_steps > 8) s.x_steps = s.x_steps <= 11 ? 11 : 14;
     // In the tiled array a 128-byte line holds 16 bytes of each of 8 consecutive channels: ranges that start on
     // multiples of 8 channels never share a line with a neighbour (which would fetch it a second time).
     const int unit = tiled ? 8 : 4;

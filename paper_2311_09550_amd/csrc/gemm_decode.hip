@@ -222,7 +222,7 @@ static hipError_t launch_epoch(const DecodeArgs &p, bool acc_out, const DecodeSh
         return launch_epoch_xs<MT_, XS_, WV_>(p, acc_out, s, grid, sets, false, stream);                 \
     }
     W4A8_EPOCH(1, 1, 8) W4A8_EPOCH(1, 2, 8) W4A8_EPOCH(1, 3, 8) W4A8_EPOCH(1, 4, 8) W4A8_EPOCH(1, 5, 8) W4A8_EPOCH(1, 6, 8)
-    W4A8_EPOCH(1, 7, 8) W4A8_EPOCH(1, 8, 8)
+    W4A8_EPOCH(1, 7, 8) W4A8_EPOCH(1, 8, 8) W4A8_EPOCH(1, 11, 8) W4A8_EPOCH(1, 14, 8)
     W4A8_EPOCH(1, 1, 16) W4A8_EPOCH(1, 2, 16) W4A8_EPOCH(1, 3, 16) W4A8_EPOCH(1, 4, 16) W4A8_EPOCH(1, 5, 16)
     W4A8_EPOCH(1, 6, 16) W4A8_EPOCH(1, 7, 16) W4A8_EPOCH(1, 8, 16)
     W4A8_EPOCH(2, 1, 16) W4A8_EPOCH(2, 2, 16) W4A8_EPOCH(2, 3, 16) W4A8_EPOCH(2, 4, 16)
@@ -245,7 +245,7 @@ static bool epoch_supported(int mt, const DecodeShape &s) {
     if (s.chunk_rows < 4 || s.chunk_rows > 16 || (s.chunk_rows & 3)) return false;
     if (s.aux != 0 && s.aux != 2) return false;
     if (s.rows_per_wg > kResidentMaxRows) return false;
-    if (s.x_steps < 1 || s.x_steps > 8) return false;
+    if (s.x_steps < 1 || (s.x_steps > 8 && !(mt == 1 && s.waves == 8 && (s.x_steps == 11 || s.x_steps == 14)))) return false;
     if (mt == 2 && (s.waves != 16 || s.x_steps > 4)) return false;
     if (s.fused_quant && !(s.tiled && fused_quant_fits(mt, s.x_steps, s.prefetch, s.waves))) return false;
     return epoch_fits(mt, s.x_steps, s.prefetch, s.waves);
@@ -261,7 +261,9 @@ bool decode_resident_supported(int M, int N, int K, const DecodeShape &s) {
     const int mt = (M + 15) / 16;
     if (s.k_slices > (K + 127) / 128) return false;
     const int steps = (slice_steps(K, s) + s.waves - 1) / s.waves;
-    if (steps != s.x_steps || (s.waves != 8 && s.waves != 16)) return false;
+    // more steps per wave than K needs are allowed (the surplus loads nothing), fewer are not
+    if (s.waves != 8 && s.waves != 16) return false;
+    if (s.x_steps < steps || (s.x_steps > steps && !(s.x_steps == 11 || s.x_steps == 14))) return false;
     // 32-bit buffer offsets (the tiled array rounds N up to 32 and K up to 128)
     const unsigned long long w_bytes = s.tiled ? (unsigned long long)tiled_weight_bytes(N, K)
                                                : (unsigned long long)N * (unsigned long long)(K >> 1);

@@ -26,7 +26,7 @@ hipError_t launch_wide_p(const DecodeArgs &p, bool acc_out, int grid, int sets, 
 }
 
 constexpr bool wide_shape_exists(int mt, int xs, int waves) {
-    if (mt == 1) return (waves == 8 && xs >= 1 && xs <= 8) || (waves == 16 && xs >= 5 && xs <= 8);
+    if (mt == 1) return (waves == 8 && ((xs >= 1 && xs <= 8) || xs == 11 || xs == 14)) || (waves == 16 && xs >= 5 && xs <= 8);
     if (mt == 2) return (waves == 16 && xs >= 1 && xs <= 4) || (waves == 8 && xs >= 1 && xs <= 7);
     if (mt == 3 || mt == 4) return waves == 8 && xs >= 1 && xs <= 5;
     return false;
@@ -58,7 +58,7 @@ hipError_t launch_gemm_decode_wide(const DecodeArgs &p, bool acc_out, const Deco
                                : launch_wide_p<MT_, XS_, 1, WV_>(p, acc_out, grid, sets, false, stream);      \
     }
     W4A8_WIDE(1, 1, 8) W4A8_WIDE(1, 2, 8) W4A8_WIDE(1, 3, 8) W4A8_WIDE(1, 4, 8) W4A8_WIDE(1, 5, 8) W4A8_WIDE(1, 6, 8)
-    W4A8_WIDE(1, 7, 8) W4A8_WIDE(1, 8, 8)
+    W4A8_WIDE(1, 7, 8) W4A8_WIDE(1, 8, 8) W4A8_WIDE(1, 11, 8) W4A8_WIDE(1, 14, 8)
     W4A8_WIDE(1, 5, 16) W4A8_WIDE(1, 6, 16) W4A8_WIDE(1, 7, 16) W4A8_WIDE(1, 8, 16)
     W4A8_WIDE(2, 1, 16) W4A8_WIDE(2, 2, 16) W4A8_WIDE(2, 3, 16) W4A8_WIDE(2, 4, 16)
     W4A8_WIDE(2, 1, 8) W4A8_WIDE(2, 2, 8) W4A8_WIDE(2, 3, 8) W4A8_WIDE(2, 4, 8) W4A8_WIDE(2, 5, 8) W4A8_WIDE(2, 6, 8)
