@@ -8,8 +8,8 @@ for `--kernel-trace --stats`).  This script reads them, never the GPU:
         per dispatch), each scaled by what the same counter reads for the 256 MiB `__amd_rocclr_copyBuffer` dispatches
         of `bench.py --copy-calibration` in the same run, summed over all dispatches of the kernel and divided by the
         GEMM calls of the run = dispatches x F (a GEMM call may be more than one dispatch: the timed step makes 4 calls
-        in 5 dispatches, F = 0.8; default F = 1); with --by-grid instead the mean over the kernel's grid sizes of the
-        mean per dispatch (the decode section: one GEMM shape per grid size, equal weights).  Merges the result under KEY into
+        in 5 dispatches, F = 0.8; default F = 1); with --by-grid instead the mean over the GEMM shapes of the mean per
+        dispatch (the decode section: a shape is told by grid size and k steps per wave; equal weights).  Merges the result under KEY into
         profiles/traffic_counters.json together with the hash of the kernel sources, which `bench.py` checks before it
         reports the figure.  Prints a markdown table per (kernel, grid size).
 
@@ -100,14 +100,17 @@ def cmd_traffic(a):
         print(f"\n(the two runs saw {n_f} and {n_w} dispatches: each total is divided by its own run's GEMM calls)")
     gemms = n_f * a.calls_per_dispatch
     if a.by_grid:
-        # one GEMM shape per grid size, every shape with the same weight, however many launches each had
+        # one GEMM shape per (grid size, k steps per wave = second template argument of the kernel): every shape with
+        # the same weight, however many launches each had and whichever instantiations served its token counts
         by_grid = collections.defaultdict(lambda: {"fetch": [], "write": []})
         for (name, grid), g in groups.items():
-            by_grid[grid]["fetch"] += g["fetch"]
-            by_grid[grid]["write"] += g["write"]
+            args = name[name.find("<") + 1:].split(",") if "<" in name else []
+            key = (grid, args[1].strip() if len(args) > 1 else "")
+            by_grid[key]["fetch"] += g["fetch"]
+            by_grid[key]["write"] += g["write"]
         per_f = statistics.mean(statistics.mean(g["fetch"]) for g in by_grid.values())
         per_w = statistics.mean(statistics.mean(g["write"]) for g in by_grid.values())
-        print(f"\nPer GEMM call, mean over the {len(by_grid)} grid sizes (one GEMM shape each) of the mean per dispatch: "
+        print(f"\nPer GEMM call, mean over the {len(by_grid)} GEMM shapes (grid size, k steps per wave) of the mean per dispatch: "
               f"{per_f / 1e6:.2f} MB fetched + {per_w / 1e6:.2f} MB written = {(per_f + per_w) / 1e6:.2f} MB.")
     else:
         per_f, per_w = total_f / gemms, total_w * (n_f / n_w if n_w else 1.0) / gemms
