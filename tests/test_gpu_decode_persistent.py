@@ -135,7 +135,8 @@ def test_one_weight_array_serves_medium_m_too(gpu, oracle, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K,splits", [(64, 520, 13824, 3), (64, 520, 13824, 0), (32, 300, 13824, 2), (48, 1001, 8192, 2),
-                                          (33, 130, 28672, 0), (64, 200, 5120, 4), (17, 40, 4096, 8)])
+                                          (33, 130, 28672, 0), (64, 200, 5120, 4), (17, 40, 4096, 8), (33, 77, 4128, 3),
+                                          (50, 1001, 2080, 5), (20, 24, 65536, 0)])
 def test_window_form_in_k_slices(gpu, oracle, M, N, K, splits):
     """A K too long for a wave's registers (or a forced slice count) is cut over workgroups: one slab of raw sums per
     slice, added up and dequantised by the slab epilogue.  Integer sums: the bits of the unsliced result."""
