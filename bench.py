@@ -97,6 +97,9 @@ def parse_args():
                     "(decode, layer_stack, 7b, 70b, large_m, row_major, achievable, medium_m, table5, w8a8, cpu); empty = all")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-swiglu-epilogue", action="store_true",
+                    help="keep SiLU*up in the quantiser in front of the down projection at every M (default: from 768 "
+                         "tokens on it moves into the gate+up GEMM's epilogue, w4a8_gemm_tiled_swiglu)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy three times: the dispatch of known size against which "
                          "hardware traffic counters are scaled")
@@ -109,12 +112,17 @@ def parse_args():
 
 def prepare_weights(torch, w4a8, synth, model="13b"):
     """Offline weight preparation, on the GPU: quantise and pack, then reorder into the tiled array (the only copy that
-    is kept).  Returns name -> (wt, s_w)."""
+    is kept).  Returns name -> (wt, s_w); "gate_up_interleaved" holds the gate and up channels of the same matrix
+    interleaved, the order the GEMM with the SiLU*up epilogue takes them in (a deployment keeps one of the two orders;
+    the benchmark keeps both because it also times the unfused launches)."""
     out = {}
     for name, (N, K) in synth.LLAMA_SHAPES[model].items():
         w = torch.from_numpy(synth.weights_fp16(N, K, config_id=3)).to("cuda")
         wp, s_w = w4a8.w4a8_quantize_weights(w)
         out[name] = (w4a8.w4a8_tile_weights(wp), s_w)
+        if name == "gate_up":
+            wp, s_w = w4a8.w4a8_quantize_weights(w4a8.interleave_gate_up(w))
+            out["gate_up_interleaved"] = (w4a8.w4a8_tile_weights(wp), s_w)
         del w, wp
     return out
 
@@ -122,10 +130,18 @@ def prepare_weights(torch, w4a8, synth, model="13b"):
 class LayerStack:
     """Device buffers of one 13B-shaped decoder layer's linears and the launches of a step.
 
-    Eight launches (three per-token quantisers, the fused SiLU*up + quantiser, four GEMMs).  M <= 2 with fuse=True:
+    Eight launches (three per-token quantisers, the fused SiLU*up + quantiser, four GEMMs).  From SWIGLU_FROM_M tokens
+    on the gate+up GEMM applies SiLU*up in its epilogue (w4a8_gemm_tiled_swiglu) and a plain per-token quantiser
+    follows: still eight launches, but the M x 2I intermediate is neither written nor read.  M <= 2 with fuse=True:
     five launches -- the linears fed by fp16 hidden states (QKV, O, gate+up) quantise their own activations inside the
     weight-streaming GEMM (w4a8_linear_tiled_fp16); only the SiLU*up + quantiser in front of the down projection stays
     a launch of its own (its input is twice as wide as its output)."""
+
+    # Token count from which the gate+up GEMM takes SiLU*up into its epilogue (None = never; `--no-swiglu-epilogue`).
+    # Measured on the 13B layer, both forms in turn on one box: 1.5 to 1.7 % off the step at M = 1024 and 2048 (the GEMM
+    # gains 2.7 us of exposed exp2 / reciprocal work at the end of its tiles, the quantiser behind it reads half the
+    # bytes and loses 8 us); level at 256 and 512; 1 % slower at 128.
+    SWIGLU_FROM_M = 768
 
     def __init__(self, torch, w4a8, synth, M, weights, model="13b", fuse=False):
         self.torch, self.w4a8, self.M = torch, w4a8, M
@@ -134,6 +150,7 @@ class LayerStack:
         dev = "cuda"
         self.wp = {k: v[0] for k, v in weights.items()}
         self.s_w = {k: v[1] for k, v in weights.items()}
+        self.swiglu = (self.SWIGLU_FROM_M is not None and M >= self.SWIGLU_FROM_M and "gate_up_interleaved" in weights)
         H = self.shapes["qkv"][1]
         I = self.shapes["down"][1]
         # fp16 hidden states enter the stack; attention itself is not modelled: the Q slice of the QKV output stands in
@@ -159,6 +176,12 @@ class LayerStack:
             xq, sa = (self.xq_i, self.sa_i) if name == "down" else (self.xq_h, self.sa_h)
             self.gemm[name] = b("w4a8_gemm_tiled_splitk", xq, sa, self.wp[name], self.s_w[name], self.out[name], M, N, K,
                                 0, 0, self.ws[name], self.ws[name].numel())
+        if self.swiglu:
+            # gate+up with SiLU*up in its epilogue -> h [M][I]; the quantiser in front of the down projection reads h
+            self.hmid = e(M, I, dt=torch.float16)
+            self.gemm["gate_up"] = b("w4a8_gemm_tiled_swiglu", self.xq_h, self.sa_h, self.wp["gate_up_interleaved"],
+                                     self.s_w["gate_up_interleaved"], self.hmid, M, I, self.shapes["gate_up"][1])
+            self.quant["down"] = b("w4a8_quantize_act", self.hmid, self.xq_i, self.sa_i, M, I)
         if self.fused:
             src = {"qkv": (self.h, H), "o": (self.out["qkv"], self.shapes["qkv"][0]), "gate_up": (self.out["o"], H)}
             self.linear = {name: b("w4a8_linear_tiled_fp16", x, ldx, self.wp[name], self.s_w[name], self.out[name], None,
@@ -692,6 +715,8 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.no_swiglu_epilogue:
+        LayerStack.SWIGLU_FROM_M = None
     weights = prepare_weights(torch, w4a8, synth)
     stack = LayerStack(torch, w4a8, synth, M, weights)
     # set-up ends with the device out of its idle power state (see SETTLE_MS); then the warm-up steps asked for
@@ -723,10 +748,15 @@ def main():
     ops_per_launch = sum(gemm_ops(M, *stack.shapes[k]) for k in gemm_us) / len(gemm_us)
     achieved = ops_per_launch / avg_us / 1e6   # TOPS
     traffic, traffic_note = measured_traffic(f"gemm_prefill_tiled_kernel@13b,M={M}")
+
+    def launch_bytes(k):   # the gate+up GEMM with the SiLU*up epilogue writes M x I values instead of M x 2I
+        by = gemm_bytes(M, *stack.shapes[k])
+        return by - M * stack.shapes[k][0] if (k == "gate_up" and stack.swiglu) else by
+
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": traffic,
                 "traffic_unit": "bytes per launch (L2 fills + write-backs)", "traffic_source": traffic_note,
-                "algorithmic_bytes_per_launch": round(sum(gemm_bytes(M, *stack.shapes[k]) for k in gemm_us) / len(gemm_us)),
+                "algorithmic_bytes_per_launch": round(sum(launch_bytes(k) for k in gemm_us) / len(gemm_us)),
                 "kernel": "gemm_prefill_tiled_kernel", "avg_launch_us": round(avg_us, 2),
                 "per_linear_us": {k: round(v, 2) for k, v in gemm_us.items()},
                 "per_linear_tops": {k: round(gemm_ops(M, *stack.shapes[k]) / v / 1e6, 1) for k, v in gemm_us.items()},
@@ -739,8 +769,10 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"LLaMA-13B-shaped decoder-layer linear stack (QKV, O, gate+up, down), M={M} tokens: "
-                               "4 per-token int8 quantisations (one fused with SiLU*up) + 4 W4A8 GEMMs with fused dequant; "
-                               "weights quantised, packed and reordered into the tiled layout offline",
+                               "4 per-token int8 quantisations + 4 W4A8 GEMMs with fused dequant, SiLU*up "
+                               + ("in the gate+up GEMM's epilogue; " if stack.swiglu else "fused with the quantiser behind it; ")
+                               + "weights quantised, packed and reordered into the tiled layout offline",
+                   "silu_mul": "gemm epilogue" if stack.swiglu else "quantiser",
                    "M": M, "linears": {k: list(v) for k, v in stack.shapes.items()}, "launches_per_step": 8},
         "settle_ms_before_warmup": 2 * SETTLE_MS,
         "gemm_share_of_step": round(sum(gemm_us.values()) / (ms_per_step * 1e3), 4),

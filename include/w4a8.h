@@ -158,6 +158,22 @@ int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const 
                                   uint8_t *wp, float *s_w, int N, int K, void *stream);
 
 /*
+ * The gate and up projections of a gated MLP and the glue behind them in one launch (fusion across operators,
+ * Sec. 6.1): w4a8_gemm_tiled over the 2 I channels of both projections, stored INTERLEAVED (channel 2 i = gate_i,
+ * channel 2 i + 1 = up_i: the caller interleaves the rows of the two weight matrices before w4a8_quantize_weights and
+ * w4a8_tile_weights; s_w_gu follows the same order), with w4a8_silu_mul applied in the epilogue:
+ *   h[m][i] = fp16( silu(fp16 gate[m][i]) * fp16 up[m][i] ),  gate / up = the W4A8 linear of Eq. (6),(7)
+ * i.e. exactly what w4a8_gemm_tiled followed by w4a8_silu_mul gives on the same weights in the usual order, bit for
+ * bit, without the M x 2 I intermediate going to memory.
+ *   xq [M][K], s_a [M], wt_gu (tiled array of 2 I channels x K), s_w_gu [2 I]   in;   h_fp16 [M][I]   out.
+ *   I follows the K contract (I % 32 == 0, I <= 65536).  Runs the large-M kernel whatever M is: meant for some hundred
+ *   tokens and more (below that the weight-streaming kernels and w4a8_silu_mul_quantize are faster).
+ *   M * K and the tiled weight bytes must each be below 0xF0000000 (W4A8_ERR_SHAPE).
+ */
+int w4a8_gemm_tiled_swiglu(const int8_t *xq, const float *s_a, const uint8_t *wt_gu, const float *s_w_gu, void *h_fp16,
+                           int M, int I, int K, void *stream);
+
+/*
  * w4a8_gemm_tiled for shapes whose output tiles alone would leave most of the chip idle (medium M, small N: e.g.
  * 40 tiles for M = 32, N = 5120): K is cut into slices, every (tile, slice) pair is a workgroup of the same kernel that
  * writes its raw int32 sums to a slab of the workspace, and a second kernel adds the slabs and applies Eq. (6),(7).

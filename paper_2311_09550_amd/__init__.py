@@ -74,6 +74,8 @@ def lib():
         L.w4a8_gemm_tiled_splitk.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
         L.w4a8_gemm_tiled_splitk_static.restype = i
         L.w4a8_gemm_tiled_splitk_static.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp]
+        L.w4a8_gemm_tiled_swiglu.restype = i
+        L.w4a8_gemm_tiled_swiglu.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp]
         L.w4a8_linear_tiled_fp16.restype = i
         L.w4a8_linear_tiled_fp16.argtypes = [vp, ctypes.c_longlong, vp, vp, vp, vp, i, i, i, vp]
         L.w4a8_init.restype = i
@@ -419,6 +421,28 @@ def w4a8_gemm_tiled_splitk(xq, s_a, wt, s_w, variant: int = 0, splits: int = 0, 
                                         _dev(s_w, torch.float32, "s_w"), _dev(out, torch.float16, "out"), M, N, K, variant,
                                         splits, _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()))
     return out
+
+
+def w4a8_gemm_tiled_swiglu(xq, s_a, wt_gu, s_w_gu, h=None):
+    """int8 [M][K], fp32 [M], tiled weights of the 2 I interleaved gate / up channels, fp32 [2 I] -> h = fp16 [M][I],
+    silu(gate) * up applied in the GEMM's epilogue."""
+    torch = _torch()
+    M, K = xq.shape
+    N = s_w_gu.shape[0]
+    if N % 2 or wt_gu.numel() != w4a8_tiled_weight_bytes(N, K) or tuple(s_a.shape) != (M,):
+        raise ValueError("shape mismatch")
+    I = N // 2
+    h = torch.empty((M, I), dtype=torch.float16, device=xq.device) if h is None else _shaped(h, (M, I), "h")
+    _check(lib().w4a8_gemm_tiled_swiglu(_dev(xq, torch.int8, "xq"), _dev(s_a, torch.float32, "s_a"), _dev(wt_gu, torch.uint8, "wt_gu"),
+                                        _dev(s_w_gu, torch.float32, "s_w_gu"), _dev(h, torch.float16, "h"), M, I, K, _stream()))
+    return h
+
+
+def interleave_gate_up(w_gate_up):
+    """[2 I][...] rows (gate rows, then up rows) -> rows interleaved gate_0, up_0, gate_1, up_1, ...: the order
+    w4a8_gemm_tiled_swiglu expects its channels in (a view operation on the caller's weights, before quantisation)."""
+    I = w_gate_up.shape[0] // 2
+    return w_gate_up.reshape(2, I, *w_gate_up.shape[1:]).transpose(0, 1).reshape(w_gate_up.shape).contiguous()
 
 
 def w4a8_linear_tiled_fp16(x, wt, s_w, out=None, s_a_out=None):

@@ -496,6 +496,40 @@ int w4a8_gemm_tiled(const int8_t *xq, const float *s_a, const uint8_t *wt, const
     return run_gemm(xq, s_a, wt, s_w, out_fp16, nullptr, M, N, K, W4A8_TILING_AUTO_TILED, 0, stream);
 }
 
+int w4a8_gemm_tiled_swiglu(const int8_t *xq, const float *s_a, const uint8_t *wt_gu, const float *s_w_gu, void *h_fp16, int M,
+                           int I, int K, void *stream) {
+    if (!xq || !s_a || !wt_gu || !s_w_gu || !h_fp16) return W4A8_ERR_NULL;
+    if (I < 32 || (I % 32) != 0 || I > W4A8_MAX_K) return W4A8_ERR_SHAPE;  // I follows the K contract, as in w4a8_silu_mul
+    const int N = 2 * I;
+    if (int e = check_gemm_shape(M, N, K)) return e;
+    if (misaligned(xq) || misaligned(wt_gu) || misaligned(h_fp16) || misaligned(s_w_gu)) return W4A8_ERR_ALIGN;
+    if ((long long)M * K > 0xF0000000ll || (long long)tiled_weight_bytes(N, K, 4) > 0xF0000000ll) return W4A8_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int tile = choose_tiled_tile(M, N);
+    if (tile != kTiled256x256 && tile != kTiled256x192 && tile != kTiled128x256 && tile != kTiled128x256W8)
+        tile = kTiled128x128;  // the fused form exists for the large-M tiles; fewer tokens are not what it is for
+    PrefillArgs a{};
+    a.xq = xq; a.s_a = s_a; a.wp = wt_gu; a.s_w = s_w_gu; a.out = h_fp16;
+    a.M = M; a.N = N; a.K = K; a.ldc = I;
+    // the two-phase launch of launch_tiled_in_phases, with the output offset counted in values of h
+    const int cus = compute_units();
+    const long long tiles_m = (M + 255) / 256, cols = (N + 255) / 256, per_round = cus / tiles_m;
+    if (tile == kTiled256x256 && per_round > 0 && cols > per_round && cols % per_round != 0) {
+        const long long n_first = (cols / per_round) * per_round * 256, rest = N - n_first;
+        if ((rest + 191) / 192 <= per_round) {
+            PrefillArgs first = a, second = a;
+            first.N = (int)n_first;
+            second.N = (int)rest;
+            second.wp = wt_gu + (size_t)(n_first / 32) * (size_t)((K + kTiledBlockK - 1) / kTiledBlockK) * (size_t)kTiledBlockBytes;
+            second.s_w = s_w_gu + n_first;
+            second.out = (unsigned short *)h_fp16 + n_first / 2;
+            if (int e = launched(launch_gemm_prefill_tiled_swiglu(first, kTiled256x256, st))) return e;
+            return launched(launch_gemm_prefill_tiled_swiglu(second, kTiled256x192, st));
+        }
+    }
+    return launched(launch_gemm_prefill_tiled_swiglu(a, tile, st));
+}
+
 // ---- K split over workgroups for shapes whose tiles alone leave most of the chip idle (medium M, small N)
 
 namespace {

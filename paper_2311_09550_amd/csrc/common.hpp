@@ -139,6 +139,22 @@ struct RowQuantizer {
     }
 };
 
+// silu(gate) * up in fp32 from two fp16 values: g / (1 + e^-g) with the hardware's exp2 and reciprocal (about 1 ulp of
+// fp32 each), three orders of magnitude below the fp16 rounding that follows.  exp2 overflows to +inf for very negative
+// g, the reciprocal of that is 0: silu(-65504) = -0.  One definition for the row-wise kernels and for the GEMM epilogue
+// that applies it, so that both give the same fp16 bits.
+__device__ __forceinline__ float silu_mul_f32(float gt, float up) {
+    return gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(gt * -1.4426950408889634f)) * up;
+}
+
+// Four (gate, up) pairs held as fp16 pairs in four words (low half = gate, high half = up) -> four fp16 products.
+__device__ __forceinline__ v2u silu_mul_pairs4(v4u v) {
+    v2u o;
+    o.x = pack_f16x2(silu_mul_f32(lo_half(v.x), hi_half(v.x)), silu_mul_f32(lo_half(v.y), hi_half(v.y)));
+    o.y = pack_f16x2(silu_mul_f32(lo_half(v.z), hi_half(v.z)), silu_mul_f32(lo_half(v.w), hi_half(v.w)));
+    return o;
+}
+
 __device__ __forceinline__ void halves8(v4u v, float (&x)[8]) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

@@ -109,9 +109,15 @@ __global__ __launch_bounds__(256) void tile_weights_kernel(const uint8_t *__rest
 // stage's k between them (set ks takes k = 64 ks .. 64 ks + 63 of the stage, i.e. MFMA steps 2 ks and 2 ks + 1); their
 // integer sums meet in LDS before the epilogue.  For tiles that a compute unit holds only once (N too small for
 // more workgroups) this doubles the waves per SIMD without shrinking the tile.
+// SWIGLU (signed int4, per-channel scales, fp16 output): the channels are gate and up projections interleaved
+// (channel 2 i = gate_i, 2 i + 1 = up_i) and the epilogue stores h_i = fp16(silu(fp16 gate_i) * fp16 up_i) instead of the
+// two values: the glue between the gate+up and the down projection done where its inputs are produced (the fusion
+// across operators of Sec. 6.1).  p.out is then h [M][p.ldc], p.ldc = channels / 2; same bits as silu_mul_kernel
+// gives on the unfused output.
 template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS = 4, bool UNS = false, bool FG = false,
-          int KS = 1>
+          int KS = 1, bool SWIGLU = false>
 __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kernel(PrefillArgs p) {
+    static_assert(!SWIGLU || (WBITS == 4 && !UNS && !FG && !ACC_OUT), "fused SiLU * up: the plain W4A8 kernel, fp16 output");
     static_assert(KS == 1 || (KS == 2 && WBITS == 4 && !UNS && !FG && STAGES == 3), "k split: the plain W4A8 kernel only");
     static_assert(WBITS == 4 || WBITS == 8, "int4 or int8 weight codes");
     static_assert(!UNS || WBITS == 4, "the unsigned storage is a 4-bit format");
@@ -515,7 +521,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
         else
             return deq(acc[mt][t][v], s_a, s_w);
     };
-    if (!ACC_OUT && (p.ldc & 7) == 0) {
+    if (!ACC_OUT && (SWIGLU || (p.ldc & 7) == 0)) {  // the fused form is only launched with a pitch that allows this path
         constexpr int kRowBytes = 64 * NTW;        // fp16 bytes of a slab row (32 NTW channels)
         constexpr int kPitch = kRowBytes + 16;     // padded: rows 16 apart, not 1 apart, share banks
         constexpr int kChunksPerRow = 4 * NTW;     // 16-byte chunks
@@ -548,6 +554,20 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
                 const v4u v = *(const v4u *)(slab + row * kPitch + col * 16);
                 const int mm = m_slab + row, n = n_wave + col * 8;
                 if (mm >= p.M || n >= p.N) continue;
+                if constexpr (SWIGLU) {
+                    // eight channels = four (gate, up) pairs -> four values of h
+                    const v2u hv = silu_mul_pairs4(v);
+                    unsigned short *dst = (unsigned short *)p.out + (size_t)mm * p.ldc + (n >> 1);
+                    if (n + 8 <= p.N) {
+                        *(v2u *)dst = hv;
+                    } else {
+                        const unsigned w[2] = {hv.x, hv.y};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n + 2 * e + 1 < p.N) dst[e] = (unsigned short)(w[e >> 1] >> (16 * (e & 1)));
+                    }
+                    continue;
+                }
                 unsigned short *dst = (unsigned short *)p.out + (size_t)mm * p.ldc + n;
                 if (n + 8 <= p.N) {
                     *(v4u *)dst = v;
@@ -610,7 +630,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void gemm_prefill_tiled_kerne
 
 namespace {
 
-template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS, bool UNS, bool FG, int KS>
+template <int MTW, int NTW, int WM, int WN, int STAGES, bool ACC_OUT, int WBITS, bool UNS, bool FG, int KS, bool SWIGLU = false>
 hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
     // ring + spare KB; group scales: 128 NTW bytes per wave and ring slot, and a KB of slack behind them
@@ -619,7 +639,7 @@ hipError_t launch_one(const PrefillArgs &p, dim3 grid, hipStream_t stream) {
     constexpr int kMeet = KS == 2 ? WM * WN * (32 * (64 * NTW + 16) + MTW * NTW * 16 * 256) : 0;
     constexpr int kLdsBytes = (kRing > kMeet ? kRing : kMeet) + (BM + BN) * 4;  // + the epilogue's s_a and s_w
     static_assert(kLdsBytes <= 160 * 1024, "a workgroup's ring must fit the compute unit's LDS");
-    constexpr auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS, FG, KS>;
+    constexpr auto kernel = gemm_prefill_tiled_kernel<MTW, NTW, WM, WN, STAGES, ACC_OUT, WBITS, UNS, FG, KS, SWIGLU>;
     if (const hipError_t e = allow_lds<kernel>(kLdsBytes); e != hipSuccess) return e;
     if (p.prepare_only) return hipSuccess;
     hipLaunchKernelGGL(kernel, grid, dim3(64 * WM * WN * KS), kLdsBytes, stream, p);
@@ -641,6 +661,16 @@ hipError_t launch_tile(PrefillArgs p, bool acc_out, hipStream_t stream) {
         return acc_out ? launch_one<MTW, NTW, WM, WN, STAGES, true, WBITS, UNS, false, KS>(p, grid, stream)
                        : launch_one<MTW, NTW, WM, WN, STAGES, false, WBITS, UNS, false, KS>(p, grid, stream);
     }
+}
+
+// The fused SiLU * up form of a tile: one launch covers the problem (byte offsets below 2^32 are the caller's check).
+template <int MTW, int NTW, int WM, int WN, int STAGES>
+hipError_t launch_tile_swiglu(PrefillArgs p, hipStream_t stream) {
+    constexpr int BM = 32 * MTW * WM, BN = 32 * NTW * WN;
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    const int total = p.tiles_m * p.tiles_n;
+    return launch_one<MTW, NTW, WM, WN, STAGES, false, 4, false, false, 1, true>(p, dim3(8 * ((total + 7) / 8)), stream);
 }
 
 // One thread per 16-byte chunk of the tiled int8 array (W8A8 variant): a plain gather, no reordering inside a chunk.
@@ -788,10 +818,30 @@ hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int til
     return hipSuccess;
 }
 
+hipError_t launch_gemm_prefill_tiled_swiglu(const PrefillArgs &p, int tile, hipStream_t stream) {
+    // p.N interleaved channels (even), p.out = h with pitch p.ldc (a multiple of 4 elements: the 8-byte stores of four
+    // values are aligned)
+    const long long kMaxBytes = 0xF0000000ll;
+    const long long kb_total = (p.K + kTiledBlockK - 1) / kTiledBlockK;
+    if ((p.N & 1) || (p.ldc & 3) || (long long)p.M * p.K > kMaxBytes ||
+        (long long)((p.N + 31) / 32) * kb_total * kTiledBlockBytes > kMaxBytes)
+        return hipErrorInvalidValue;
+    switch (tile) {
+        case kTiled256x256: return launch_tile_swiglu<4, 2, 2, 4, 3>(p, stream);
+        case kTiled256x192: return launch_tile_swiglu<2, 3, 4, 2, 3>(p, stream);
+        case kTiled128x256: return launch_tile_swiglu<4, 2, 1, 4, 2>(p, stream);
+        case kTiled128x256W8: return launch_tile_swiglu<2, 2, 2, 4, 3>(p, stream);
+        case kTiled128x128: return launch_tile_swiglu<2, 2, 2, 2, 3>(p, stream);
+        default: return hipErrorInvalidConfiguration;
+    }
+}
+
 hipError_t prepare_tiled_kernels() {
     PrefillArgs a{};
     a.M = 32; a.N = 32; a.K = kTiledBlockK; a.ldc = 32; a.ldg = 32;
     a.prepare_only = true;
+    for (int tile : {kTiled256x256, kTiled256x192, kTiled128x256, kTiled128x256W8, kTiled128x128})
+        if (const hipError_t e = launch_gemm_prefill_tiled_swiglu(a, tile, nullptr); e != hipSuccess) return e;
     struct Format { int wbits, tiles; bool acc; };
     const Format formats[] = {{4, kTiledTileMax4, true}, {8, kTiledTileMax, true}, {kWeightsUnsigned4, kTiledTileMax, true},
                               {kWeightsFineGrained4, kFineTileMax, false}};

@@ -156,6 +156,9 @@ size_t tiled_weight_bytes(int N, int K, int wbits = 4);
 hipError_t launch_tile_weights(const uint8_t *wp, uint8_t *wt, int N, int K, hipStream_t stream);
 hipError_t launch_tile_weights8(const int8_t *w8, uint8_t *wt, int N, int K, hipStream_t stream);
 hipError_t launch_gemm_prefill_tiled(const PrefillArgs &p, bool acc_out, int tile, hipStream_t stream, int wbits = 4);
+// The same over gate and up channels interleaved, storing h = fp16(silu(gate) * up) (p.out = h, p.ldc = its pitch);
+// tiles 256 x 256, 256 x 192, 128 x 256 (both forms) and 128 x 128.
+hipError_t launch_gemm_prefill_tiled_swiglu(const PrefillArgs &p, int tile, hipStream_t stream);
 // Per-device preparations (LDS allowance) of every instantiation of the tiled kernel, for the current device.
 hipError_t prepare_tiled_kernels();
 // fp16 output from `splits` slabs [M][N] of raw int32 sums (what the tiled kernel writes when PrefillArgs::splits > 1)

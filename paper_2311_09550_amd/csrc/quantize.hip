@@ -40,7 +40,7 @@ __device__ __forceinline__ v4u silu_mul8(v4u gv, v4u uv) {
         for (int e = 0; e < 2; ++e) {
             const float gt = e ? hi_half(gv[j]) : lo_half(gv[j]);
             const float up = e ? hi_half(uv[j]) : lo_half(uv[j]);
-            y[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(gt * -1.4426950408889634f)) * up;
+            y[e] = silu_mul_f32(gt, up);
         }
         o[j] = pack_f16x2(y[0], y[1]);
     }

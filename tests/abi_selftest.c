@@ -98,6 +98,8 @@ int main(void)
     EXPECT(w4a8_gemm_tiled_splitk(p, p, p, p, p, 1, 16, 256, 0, 2, p, 127, NULL), W4A8_ERR_WORKSPACE);
     EXPECT(w4a8_gemm_tiled_splitk(p, p, p, p, p, 64, 512, 13824, 0, 0, NULL, 0, NULL), W4A8_ERR_NULL);
     EXPECT(w4a8_gemm_tiled_splitk_static(p, p, p, p, p, 512, 4096, 1024, 6, 8, NULL), W4A8_ERR_WORKSPACE);
+    EXPECT(w4a8_gemm_tiled_swiglu(p, p, p, p, p, 4, 40, 64, NULL), W4A8_ERR_SHAPE);
+    EXPECT(w4a8_gemm_tiled_swiglu(p, p, p, p, odd, 4, 64, 64, NULL), W4A8_ERR_ALIGN);
     EXPECT(w4a8_linear_tiled_fp16(p, 1000, p, p, p, NULL, 1, 16, 1024, NULL), W4A8_ERR_SHAPE);
     EXPECT(w4a8_linear_tiled_fp16(p, 1024, p, p, p, NULL, 17, 16, 1024, NULL), W4A8_ERR_ARG);
     EXPECT(w4a8_gemm_fine_grained(p, p, p, p, 12, p, 1, 16, 128, 0, NULL), W4A8_ERR_SHAPE);

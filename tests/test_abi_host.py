@@ -110,6 +110,11 @@ def test_argument_validation_happens_before_any_launch(L):
     assert f(odd, 1024, p, p, p, null, 1, 16, 1024, null) == -3
     assert f(p, 1024, p, p, p, null, 17, 16, 1024, null) == -7                  # M beyond token generation
     assert f(p, 16384, p, p, p, null, 4, 16, 16384, null) == -7                 # K beyond what a wave can hold
+    sg = L.w4a8_gemm_tiled_swiglu
+    assert sg(p, p, p, null, p, 4, 64, 64, null) == -1
+    assert sg(p, p, p, p, p, 4, 40, 64, null) == -2                            # I follows the K contract
+    assert sg(p, p, p, p, p, 4, 64, 48, null) == -2
+    assert sg(p, p, p, p, odd, 4, 64, 64, null) == -3
     g2 = L.w4a8_gemm_tiled_splitk_static
     assert g2(null, p, p, p, p, 64, 512, 1024, 0, 0, null) == -1
     assert g2(p, p, p, p, p, 64, 512, 1000, 0, 0, null) == -2

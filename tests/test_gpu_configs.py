@@ -184,6 +184,16 @@ def test_llama13b_layer_stack_stage_wise(gpu, oracle, weights_13b, M):
     down = gemm("down", xq4, sa4)
     act = w4a8.w4a8_silu_mul(gu)
     xq4b, sa4b = w4a8.w4a8_quantize_act(act)
+    if M >= 768:
+        # what the benchmark launches from 768 tokens on: SiLU*up in the gate+up GEMM's epilogue (interleaved channels),
+        # a plain quantiser behind it -- the same h, the same codes and scales
+        w_gu = weights_13b["gate_up"][0]
+        wp_i, sw_i = w4a8.w4a8_quantize_weights(w4a8.interleave_gate_up(t.from_numpy(w_gu).cuda()))
+        h_fused = w4a8.w4a8_gemm_tiled_swiglu(xq3, sa3, w4a8.w4a8_tile_weights(wp_i), sw_i)
+        xq4c, sa4c = w4a8.w4a8_quantize_act(h_fused)
+        assert bool((h_fused.view(t.int16) == act.view(t.int16)).all()), "SiLU*up in the GEMM epilogue vs the glue kernel"
+        assert bool((xq4c == xq4).all()) and bool((sa4c.view(t.int32) == sa4.view(t.int32)).all())
+        del wp_i, sw_i, h_fused
     t.cuda.synchronize()
 
     _check_quant_stage(t, oracle, "quant(h)", h, xq1, sa1)

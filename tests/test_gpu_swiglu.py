@@ -1,0 +1,70 @@
+"""GPU parity of the gate+up GEMM that applies SiLU(gate) * up in its epilogue (w4a8_gemm_tiled_swiglu): against the
+CPU oracle (GEMM, Eq. (6),(7), then the fp64 glue) and, bit for bit, against the library's own two calls (w4a8_gemm_tiled
+over the weights in the usual order, then w4a8_silu_mul), through the C ABI."""
+import numpy as np
+import pytest
+
+import paper_2311_09550_amd as w4a8
+from paper_2311_09550_amd import synth
+
+from parity import assert_equal_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(t, oracle, M, I, K, tag):
+    x = synth.activations_fp16(M, K, config_id=2, tag=tag)
+    w = synth.weights_fp16(2 * I, K, config_id=tag)          # rows 0 .. I-1 gate, I .. 2I-1 up
+    dx = t.from_numpy(x).cuda()
+    xq, s_a = w4a8.w4a8_quantize_act(dx)
+    dw = t.from_numpy(w).cuda()
+    wp, s_w = w4a8.w4a8_quantize_weights(dw)
+    gate_up = w4a8.w4a8_gemm_tiled(xq, s_a, w4a8.w4a8_tile_weights(wp), s_w)
+    h_two = w4a8.w4a8_silu_mul(gate_up)
+    wp_i, s_w_i = w4a8.w4a8_quantize_weights(w4a8.interleave_gate_up(dw))
+    h = w4a8.w4a8_gemm_tiled_swiglu(xq, s_a, w4a8.w4a8_tile_weights(wp_i), s_w_i)
+    t.cuda.synchronize()
+    return x, w, gate_up, h_two, h
+
+
+@pytest.mark.parametrize("M", [1, 33, 130, 300, 1024])
+@pytest.mark.parametrize("I,K", [(32, 32), (96, 160), (544, 1056), (4128, 256)])
+def test_swiglu_epilogue_matches_two_calls_and_oracle(gpu, oracle, M, I, K):
+    t = gpu
+    x, w, gate_up, h_two, h = _case(t, oracle, M, I, K, 91)
+    assert_equal_bits(h.cpu().numpy().view(np.uint16), h_two.cpu().numpy().view(np.uint16), f"fused vs two calls M={M} I={I} K={K}")
+    # against the oracle: its GEMM gives the fp16 gate / up values (checked to 2^-10 elsewhere; here the GPU's own fp16
+    # intermediate is the input of the glue, so the glue is checked on exactly what it was fed)
+    rows = sorted({0, M // 2, M - 1})
+    y64, _ = oracle.silu_mul(gate_up.cpu().numpy()[rows])
+    got = h.cpu().numpy()[rows].astype(np.float64)
+    big = np.abs(y64) >= 2.0 ** -14
+    assert np.all(np.abs(got - y64)[big] <= 2.0 ** -10 * np.abs(y64)[big])
+    assert np.all(np.abs(got - y64)[~big] <= 2.0 ** -24)
+    xq_o, s_a_o = oracle.quantize_act(x[rows])
+    wq_o, s_w_o = oracle.quantize_weights_rtn(w)
+    acc_o, y32, _ = oracle.gemm(xq_o, s_a_o, oracle.pack_w4(wq_o), s_w_o)
+    gu = gate_up.cpu().numpy()[rows].astype(np.float64)
+    y = y32.astype(np.float64)
+    assert np.all(np.abs(gu - y) <= np.maximum(2.0 ** -10 * np.abs(y), 2.0 ** -24))
+
+
+def test_swiglu_two_phase_launch_at_the_13b_shape(gpu, oracle):
+    """M = 1024, I = 13824: 256 x 256 tiles in whole rounds plus 256 x 192 tiles for the columns left over, the second
+    launch writing behind the first one's values of h."""
+    t = gpu
+    M, I, K = 1024, 13824, 256
+    x, w, gate_up, h_two, h = _case(t, oracle, M, I, K, 92)
+    assert_equal_bits(h.cpu().numpy().view(np.uint16), h_two.cpu().numpy().view(np.uint16), "fused vs two calls, two phases")
+
+
+def test_swiglu_refuses_what_it_does_not_serve(gpu):
+    t = gpu
+    xq = t.zeros((4, 64), dtype=t.int8, device="cuda")
+    s_a = t.ones((4,), dtype=t.float32, device="cuda")
+    for I in (16, 40):       # I follows the K contract
+        wt = t.zeros((w4a8.w4a8_tiled_weight_bytes(2 * I, 64),), dtype=t.uint8, device="cuda")
+        s_w = t.ones((2 * I,), dtype=t.float32, device="cuda")
+        with pytest.raises(w4a8.W4A8Error) as e:
+            w4a8.w4a8_gemm_tiled_swiglu(xq, s_a, wt, s_w)
+        assert e.value.code == -2
