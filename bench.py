@@ -130,27 +130,33 @@ def prepare_weights(torch, w4a8, synth, model="13b"):
 class LayerStack:
     """Device buffers of one 13B-shaped decoder layer's linears and the launches of a step.
 
-    Eight launches (three per-token quantisers, the fused SiLU*up + quantiser, four GEMMs).  From SWIGLU_FROM_M tokens
-    on the gate+up GEMM applies SiLU*up in its epilogue (w4a8_gemm_tiled_swiglu) and a plain per-token quantiser
-    follows: still eight launches, but the M x 2I intermediate is neither written nor read.  M <= 2 with fuse=True:
-    five launches -- the linears fed by fp16 hidden states (QKV, O, gate+up) quantise their own activations inside the
-    weight-streaming GEMM (w4a8_linear_tiled_fp16); only the SiLU*up + quantiser in front of the down projection stays
-    a launch of its own (its input is twice as wide as its output)."""
+    Eight launches (three per-token quantisers, the fused SiLU*up + quantiser, four GEMMs).  Up to SWIGLU_UP_TO_M and
+    from SWIGLU_FROM_M tokens on the gate+up GEMM applies SiLU*up in its epilogue (w4a8_gemm_tiled_swiglu) and a plain
+    per-token quantiser follows: still eight launches, but the M x 2I intermediate is neither written nor read.
+    M <= 2 with fuse=True: four launches -- every linear quantises its own activations inside the weight-streaming
+    GEMM (w4a8_linear_tiled_fp16), and the gate+up one also applies SiLU*up (w4a8_linear_tiled_swiglu_fp16), so that
+    the down projection is fed fp16 like the others."""
 
     # Token count from which the gate+up GEMM takes SiLU*up into its epilogue (None = never; `--no-swiglu-epilogue`).
     # Measured on the 13B layer, both forms in turn on one box: 1.5 to 1.7 % off the step at M = 1024 and 2048 (the GEMM
     # gains 2.7 us of exposed exp2 / reciprocal work at the end of its tiles, the quantiser behind it reads half the
     # bytes and loses 8 us); level at 256 and 512; 1 % slower at 128.
     SWIGLU_FROM_M = 768
+    # ... and the token count up to which the weight-streaming kernel does (its epilogue is a few lanes' work)
+    SWIGLU_UP_TO_M = 32
 
     def __init__(self, torch, w4a8, synth, M, weights, model="13b", fuse=False):
         self.torch, self.w4a8, self.M = torch, w4a8, M
         self.shapes = synth.LLAMA_SHAPES[model]
-        self.fused = bool(fuse and M <= 2)   # measured: 41 against 47 us per layer at M = 1, 45 against 49.5 at M = 2, slower from M = 3
+        # measured, the forms timed in turn: 37.8 against 46.9 us per layer at M = 1 (40.1 with SiLU*up and the down
+        # projection's quantiser as a launch of their own), 44.1 against 47.1 at M = 2, slower from M = 3
+        self.fused = bool(fuse and M <= 2)
         dev = "cuda"
         self.wp = {k: v[0] for k, v in weights.items()}
         self.s_w = {k: v[1] for k, v in weights.items()}
-        self.swiglu = (self.SWIGLU_FROM_M is not None and M >= self.SWIGLU_FROM_M and "gate_up_interleaved" in weights)
+        self.swiglu = (self.SWIGLU_FROM_M is not None and (M >= self.SWIGLU_FROM_M or M <= self.SWIGLU_UP_TO_M)
+                       and "gate_up_interleaved" in weights)
+        self.fused = self.fused and self.swiglu
         H = self.shapes["qkv"][1]
         I = self.shapes["down"][1]
         # fp16 hidden states enter the stack; attention itself is not modelled: the Q slice of the QKV output stands in
@@ -183,10 +189,12 @@ class LayerStack:
                                      self.s_w["gate_up_interleaved"], self.hmid, M, I, self.shapes["gate_up"][1])
             self.quant["down"] = b("w4a8_quantize_act", self.hmid, self.xq_i, self.sa_i, M, I)
         if self.fused:
-            src = {"qkv": (self.h, H), "o": (self.out["qkv"], self.shapes["qkv"][0]), "gate_up": (self.out["o"], H)}
+            src = {"qkv": (self.h, H), "o": (self.out["qkv"], self.shapes["qkv"][0]), "down": (self.hmid, I)}
             self.linear = {name: b("w4a8_linear_tiled_fp16", x, ldx, self.wp[name], self.s_w[name], self.out[name], None,
                                    M, self.shapes[name][0], self.shapes[name][1]) for name, (x, ldx) in src.items()}
-        self.launches_per_step = 5 if self.fused else 8
+            self.linear["gate_up"] = b("w4a8_linear_tiled_swiglu_fp16", self.out["o"], H, self.wp["gate_up_interleaved"],
+                                       self.s_w["gate_up_interleaved"], self.hmid, None, M, I, self.shapes["gate_up"][1])
+        self.launches_per_step = 4 if self.fused else 8
 
     def _gemm(self, name, record=False):
         if record:
@@ -201,10 +209,10 @@ class LayerStack:
     def step(self, record=None):
         """One pass over the launches; `record` names the GEMM to bracket with timing events (None: none)."""
         for name in ("qkv", "o", "gate_up", "down"):
-            if self.fused and name != "down":
+            if self.fused:
                 self.linear[name]()      # per-token quantiser inside the weight-streaming GEMM
                 continue
-            self.quant[name]()           # "down": SiLU*up and its quantiser in one pass
+            self.quant[name]()           # "down": SiLU*up and its quantiser in one pass, or the quantiser of h
             self._gemm(name, record == name)
 
     def gemms_only(self):
@@ -277,7 +285,7 @@ def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 2, 16, 64, 128, 1024, 2
     """The decoder layer's linear stack at several M, replayed from a HIP graph (what a serving loop does; at small M
     the launches would otherwise be timed by the interpreter).  Layer time = graph time / steps; the GEMM share is the
     time of a second graph that holds only the four plain GEMMs (pre-quantised inputs), over the layer time.  At
-    M <= 2 the layer runs with the quantisers folded into the GEMMs (5 launches), and the unfused form (8 launches)
+    M <= 2 the layer runs with the quantisers folded into the GEMMs (4 launches), and the unfused form (8 launches)
     is timed beside it.  One layer's weights (158 MB) stay resident in the last-level cache across replays: the small-M
     rows are a warm-cache figure, the HBM-bound figure is the `decode` list."""
     rows = []

@@ -166,8 +166,10 @@ int w4a8_quantize_weights_clipped(const void *w_fp16, const float *gamma, const 
  * i.e. exactly what w4a8_gemm_tiled followed by w4a8_silu_mul gives on the same weights in the usual order, bit for
  * bit, without the M x 2 I intermediate going to memory.
  *   xq [M][K], s_a [M], wt_gu (tiled array of 2 I channels x K), s_w_gu [2 I]   in;   h_fp16 [M][I]   out.
- *   I follows the K contract (I % 32 == 0, I <= 65536).  Runs the large-M kernel whatever M is: meant for some hundred
- *   tokens and more (below that the weight-streaming kernels and w4a8_silu_mul_quantize are faster).
+ *   I follows the K contract (I % 32 == 0, I <= 65536).  Up to 64 tokens the weight-streaming kernel runs (where all
+ *   of K fits its waves' registers, as for w4a8_gemm_tiled), otherwise the large-M kernel, which has the fused form
+ *   for its 256- and 128-row tiles: from 65 to some hundred tokens w4a8_gemm_tiled and w4a8_silu_mul_quantize are
+ *   faster.
  *   M * K and the tiled weight bytes must each be below 0xF0000000 (W4A8_ERR_SHAPE).
  */
 int w4a8_gemm_tiled_swiglu(const int8_t *xq, const float *s_a, const uint8_t *wt_gu, const float *s_w_gu, void *h_fp16,
@@ -213,6 +215,16 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
  */
 int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16,
                            float *s_a_out, int M, int N, int K, void *stream);
+
+/*
+ * w4a8_linear_tiled_fp16 over the interleaved gate / up weights of w4a8_gemm_tiled_swiglu, with SiLU * up in the
+ * epilogue: from the fp16 input of a gated MLP to h = silu(gate) * up in one launch (Sec. 6.1), bit for bit
+ *   w4a8_quantize_act_strided(x_fp16, ldx, xq, s_a, M, K);  w4a8_gemm_tiled_swiglu(xq, s_a, wt_gu, s_w_gu, h_fp16, M, I, K).
+ *   x_fp16, ldx, s_a_out as above;  wt_gu, s_w_gu: 2 I interleaved channels;  h_fp16 [M][I] out;  I % 32 == 0.
+ * Same limits as w4a8_linear_tiled_fp16 (M <= 4, rows must fit in LDS twice over; W4A8_ERR_ARG otherwise).
+ */
+int w4a8_linear_tiled_swiglu_fp16(const void *x_fp16, long long ldx, const uint8_t *wt_gu, const float *s_w_gu, void *h_fp16,
+                                  float *s_a_out, int M, int I, int K, void *stream);
 
 /*
  * w4a8_gemm_tiled_splitk for callers that cannot allocate device memory and have no workspace to pass: code under

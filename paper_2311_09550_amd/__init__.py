@@ -78,6 +78,8 @@ def lib():
         L.w4a8_gemm_tiled_swiglu.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp]
         L.w4a8_linear_tiled_fp16.restype = i
         L.w4a8_linear_tiled_fp16.argtypes = [vp, ctypes.c_longlong, vp, vp, vp, vp, i, i, i, vp]
+        L.w4a8_linear_tiled_swiglu_fp16.restype = i
+        L.w4a8_linear_tiled_swiglu_fp16.argtypes = [vp, ctypes.c_longlong, vp, vp, vp, vp, i, i, i, vp]
         L.w4a8_init.restype = i
         L.w4a8_init.argtypes = []
         L.w4a8_probe_stream_read.restype = i
@@ -466,6 +468,31 @@ def w4a8_linear_tiled_fp16(x, wt, s_w, out=None, s_a_out=None):
                                         None if s_a_out is None else _dev(s_a_out, torch.float32, "s_a_out"), M, N, K,
                                         _stream()))
     return out
+
+
+def w4a8_linear_tiled_swiglu_fp16(x, wt_gu, s_w_gu, h=None, s_a_out=None):
+    """fp16 [M][K] view, tiled weights of the 2 I interleaved gate / up channels, fp32 [2 I] -> h = fp16 [M][I]:
+    per-token quantisation, W4A8 GEMM and SiLU(gate) * up in one launch (M <= 4, rows small enough for LDS)."""
+    torch = _torch()
+    M, K = x.shape
+    N = s_w_gu.shape[0]
+    if N % 2:
+        raise ValueError("s_w_gu holds the scales of 2 I interleaved channels")
+    if not (x.is_cuda and x.dtype == torch.float16 and x.stride(1) == 1):
+        raise TypeError("x: expected a device fp16 view with unit column stride")
+    _on_current_device(x, "x")
+    if wt_gu.numel() != w4a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (2 I, K)")
+    h = torch.empty((M, N // 2), dtype=torch.float16, device=x.device) if h is None else h
+    if h.shape != (M, N // 2):
+        raise ValueError("h shape mismatch")
+    if s_a_out is not None and tuple(s_a_out.shape) != (M,):
+        raise ValueError("s_a_out shape mismatch")
+    _check(lib().w4a8_linear_tiled_swiglu_fp16(ctypes.c_void_p(x.data_ptr()), x.stride(0), _dev(wt_gu, torch.uint8, "wt_gu"),
+                                               _dev(s_w_gu, torch.float32, "s_w_gu"), _dev(h, torch.float16, "h"),
+                                               None if s_a_out is None else _dev(s_a_out, torch.float32, "s_a_out"), M,
+                                               N // 2, K, _stream()))
+    return h
 
 
 STATIC_SCRATCH_BYTES = 16 << 20

@@ -123,6 +123,7 @@ bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool
     s.resident = true;
     s.tiled = tiled;
     s.fused_quant = out->fused_quant;  // set by the caller that wants the kernel to quantise its own activations
+    s.swiglu = out->swiglu;            // ... or to apply SiLU * up to interleaved gate / up channels
     s.aux = aux < 0 ? 2 : aux;
     s.x_window = x_window;
     s.k_slices = k_slices < 1 ? 1 : k_slices;
@@ -505,9 +506,22 @@ int w4a8_gemm_tiled_swiglu(const int8_t *xq, const float *s_a, const uint8_t *wt
     if (misaligned(xq) || misaligned(wt_gu) || misaligned(h_fp16) || misaligned(s_w_gu)) return W4A8_ERR_ALIGN;
     if ((long long)M * K > 0xF0000000ll || (long long)tiled_weight_bytes(N, K, 4) > 0xF0000000ll) return W4A8_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // up to 64 tokens: the weight-streaming kernel with per-wave staging, where it has a shape for (M, N, K)
+    if (M <= kResidentMaxM) {
+        DecodeShape shape{};
+        shape.swiglu = true;
+        if (resident_shape(M, N, K, 0, 0, 0, false, -1, true, &shape, 1, true)) {
+            DecodeArgs d{};
+            d.xq = xq; d.s_a = s_a; d.wp = wt_gu; d.s_w = s_w_gu; d.out = h_fp16;
+            d.M = M; d.N = N; d.K = K;
+            d.rows_per_wg = shape.rows_per_wg;
+            d.chunk_rows = shape.chunk_rows;
+            return launched(launch_gemm_decode(d, false, shape, st));
+        }
+    }
     int tile = choose_tiled_tile(M, N);
     if (tile != kTiled256x256 && tile != kTiled256x192 && tile != kTiled128x256 && tile != kTiled128x256W8)
-        tile = kTiled128x128;  // the fused form exists for the large-M tiles; fewer tokens are not what it is for
+        tile = kTiled128x128;  // the large-M kernel has the fused form for these tiles
     PrefillArgs a{};
     a.xq = xq; a.s_a = s_a; a.wp = wt_gu; a.s_w = s_w_gu; a.out = h_fp16;
     a.M = M; a.N = N; a.K = K; a.ldc = I;
@@ -658,8 +672,9 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
     return launched(launch_splitk_epilogue(a.acc_out, pl.splits, s_a, s_w, out_fp16, M, N, st));
 }
 
-int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16,
-                           float *s_a_out, int M, int N, int K, void *stream) {
+// quantiser + GEMM in one launch; swiglu: N = 2 I interleaved gate / up channels, out = h
+static int linear_tiled(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16, float *s_a_out,
+                        int M, int N, int K, bool swiglu, void *stream) {
     if (!x_fp16 || !wt || !s_w || !out_fp16) return W4A8_ERR_NULL;
     if (int e = check_gemm_shape(M, N, K)) return e;
     if (ldx < K || (ldx & 7) != 0) return W4A8_ERR_SHAPE;  // rows must not overlap and must start 16-byte aligned
@@ -668,6 +683,7 @@ int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt,
     if (((unsigned long long)(M - 1) * (unsigned long long)ldx + (unsigned long long)K) * 2ull > 0xFFFF0000ull) return W4A8_ERR_SHAPE;
     DecodeShape shape{};
     shape.fused_quant = true;
+    shape.swiglu = swiglu;
     if (!resident_shape(M, N, K, 0, 0, 0, false, -1, true, &shape)) return W4A8_ERR_ARG;
     // both copies of the rows (fp16 and int8, padded to the 1 KB pieces of the copy) must fit in LDS beside the slots
     // of the partial sums
@@ -682,6 +698,17 @@ int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt,
     a.rows_per_wg = shape.rows_per_wg;
     a.chunk_rows = shape.chunk_rows;
     return launched(launch_gemm_decode(a, false, shape, static_cast<hipStream_t>(stream)));
+}
+
+int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16,
+                           float *s_a_out, int M, int N, int K, void *stream) {
+    return linear_tiled(x_fp16, ldx, wt, s_w, out_fp16, s_a_out, M, N, K, false, stream);
+}
+
+int w4a8_linear_tiled_swiglu_fp16(const void *x_fp16, long long ldx, const uint8_t *wt_gu, const float *s_w_gu, void *h_fp16,
+                                  float *s_a_out, int M, int I, int K, void *stream) {
+    if (I < 32 || (I % 32) != 0 || I > W4A8_MAX_K) return W4A8_ERR_SHAPE;
+    return linear_tiled(x_fp16, ldx, wt_gu, s_w_gu, h_fp16, s_a_out, M, 2 * I, K, true, stream);
 }
 
 int w4a8_gemm_tiled_splitk_static(const int8_t *xq, const float *s_a, const uint8_t *wt, const float *s_w, void *out_fp16,

@@ -39,6 +39,16 @@ __device__ __forceinline__ void store4_f16(const DecodeArgs &p, int m, int n, in
     }
 }
 
+// The four channels are two (gate, up) pairs of interleaved gate / up weights: dequantise and round to fp16 as
+// store4_f16 would, then store h = fp16(silu(gate) * up) of both pairs (row m of h, N / 2 values long).  Same bits as
+// the fp16 GEMM output run through the row-wise SiLU * up kernel.
+__device__ __forceinline__ void store4_h(const DecodeArgs &p, int m, int n, v4i s, float sa, float4 sw) {
+    const unsigned gu0 = pack_f16x2(dequant(s.x, sa, sw.x), dequant(s.y, sa, sw.y));
+    const unsigned gu1 = pack_f16x2(dequant(s.z, sa, sw.z), dequant(s.w, sa, sw.w));
+    unsigned short *dst = (unsigned short *)p.out + (size_t)m * (size_t)(p.N >> 1) + (n >> 1);
+    *(unsigned *)dst = pack_f16x2(silu_mul_f32(lo_half(gu0), hi_half(gu0)), silu_mul_f32(lo_half(gu1), hi_half(gu1)));
+}
+
 template <bool ACC_OUT>
 __device__ __forceinline__ void store4(const DecodeArgs &p, int m, int n, v4i s) {
     if (ACC_OUT) {
@@ -128,9 +138,16 @@ __device__ __forceinline__ void wait_vmcnt_at_most() {
 // [y * ks_per_slice, (y + 1) * ks_per_slice) of its channels and writes slab y of p.acc_out ([slices][M][N]); a second
 // kernel adds the slabs and dequantises.  That is how a K too long for a wave's registers is served, and it divides the
 // activations a workgroup has to bring in by the number of slices.
-template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false, bool XW = false>
+//
+// SWIGLU (fp16 output only): the weights are those of the gate and up projections with their channels interleaved
+// (channel 2 i = gate_i, 2 i + 1 = up_i, N = 2 I), and the epilogue stores h = silu(gate) * up, I values per token,
+// instead of the 2 I outputs (Sec. 6.1: glue operators folded into their neighbours).  The four channels an epilogue
+// item holds are two such pairs; ranges and chunks are multiples of 4 channels, so no pair is ever split.
+template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false, bool XW = false,
+          bool SWIGLU = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(DecodeArgs p) {
     static_assert(!FQ || (MT == 1 && !ACC_OUT), "the fused quantiser serves up to four tokens and the fp16 output");
+    static_assert(!SWIGLU || (TILED && !ACC_OUT), "SiLU * up in the epilogue: tiled weights, fp16 output");
     static_assert(!XW || (TILED && !FQ), "per-wave staging: tiled weights, quantised activations");
     extern __shared__ __attribute__((aligned(16))) uint8_t epoch_lds[];
     float *sw_lds = (float *)epoch_lds;
@@ -509,7 +526,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
                 float sa_m = sa[0];
 #pragma unroll
                 for (int t = 1; t < MT; ++t) sa_m = mt == t ? sa[t] : sa_m;
-                store4_f16(p, m, n, row_end, s, sa_m, sw);
+                if constexpr (SWIGLU)
+                    store4_h(p, m, n, s, sa_m, sw);
+                else
+                    store4_f16(p, m, n, row_end, s, sa_m, sw);
             }
         }
         set ^= 1;
@@ -528,9 +548,22 @@ constexpr int epoch_lds_bytes(int mt, int prefetch, int waves, int sets) {
     return kEpochScaleBytes + kEpochAmaxBytes + sets * prefetch * mt * waves * 1024;
 }
 
-template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false, bool XW = false>
+// (column tiles, k steps per wave, waves) for which the form with per-wave staging is instantiated
+constexpr bool wide_shape_exists(int mt, int xs, int waves) {
+    if (mt == 1) return (waves == 8 && ((xs >= 1 && xs <= 8) || xs == 11 || xs == 14)) || (waves == 16 && xs >= 5 && xs <= 8);
+    if (mt == 2) return (waves == 16 && xs >= 1 && xs <= 4) || (waves == 8 && xs >= 1 && xs <= 7);
+    if (mt == 3 || mt == 4) return waves == 8 && xs >= 1 && xs <= 5;
+    return false;
+}
+// ... and those of one column tile for which the form with the fused quantiser is
+constexpr bool fused_shape_exists(int xs, int waves) {
+    return (xs >= 1 && xs <= 8 && (waves == 8 || waves == 16)) || (waves == 8 && (xs == 11 || xs == 14));
+}
+
+template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false, bool XW = false,
+          bool SWIGLU = false>
 static hipError_t launch_epoch_one(const DecodeArgs &p, int grid, int sets, bool prepare_only, hipStream_t stream) {
-    constexpr auto kernel = gemm_decode_resident_kernel<MT, XS, P, WAVES, ACC_OUT, TILED, AUX, FQ, XW>;
+    constexpr auto kernel = gemm_decode_resident_kernel<MT, XS, P, WAVES, ACC_OUT, TILED, AUX, FQ, XW, SWIGLU>;
     static_assert(epoch_lds_bytes(MT, P, WAVES, 2) <= kCuLdsBytes, "both sets of slots must fit the compute unit's LDS");
     if (const hipError_t e = allow_lds<kernel>(kCuLdsBytes); e != hipSuccess) return e;
     if (prepare_only) return hipSuccess;

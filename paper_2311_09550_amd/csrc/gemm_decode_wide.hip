@@ -25,13 +25,6 @@ hipError_t launch_wide_p(const DecodeArgs &p, bool acc_out, int grid, int sets, 
     }
 }
 
-constexpr bool wide_shape_exists(int mt, int xs, int waves) {
-    if (mt == 1) return (waves == 8 && ((xs >= 1 && xs <= 8) || xs == 11 || xs == 14)) || (waves == 16 && xs >= 5 && xs <= 8);
-    if (mt == 2) return (waves == 16 && xs >= 1 && xs <= 4) || (waves == 8 && xs >= 1 && xs <= 7);
-    if (mt == 3 || mt == 4) return waves == 8 && xs >= 1 && xs <= 5;
-    return false;
-}
-
 }  // namespace
 
 bool decode_wide_supported(int mt, const DecodeShape &s) {

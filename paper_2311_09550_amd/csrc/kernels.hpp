@@ -72,6 +72,8 @@ struct DecodeShape {
     bool x_window;  // resident: every wave stages its own k steps through a window of LDS (tiled weights; the only
                     // form beyond 32 tokens)
     int k_slices;   // resident: workgroups along K (0 or 1 = none); more than one only with raw sums, one slab each
+    bool swiglu;    // resident: interleaved gate / up channels, the epilogue stores h = silu(gate) * up (tiled weights,
+                    // fp16 output, with the fused quantiser or with per-wave staging)
 };
 
 // Token counts the persistent kernel serves: 32 with the activations staged whole or read directly, 64 with per-wave
@@ -87,6 +89,9 @@ hipError_t launch_gemm_decode(const DecodeArgs &p, bool acc_out, const DecodeSha
 bool decode_wide_supported(int mt, const DecodeShape &s);
 hipError_t launch_gemm_decode_wide(const DecodeArgs &p, bool acc_out, const DecodeShape &s, int mt, bool prepare_only,
                                    hipStream_t stream);
+// The instantiations whose epilogue applies SiLU * up (DecodeShape::swiglu): the same pair.
+bool decode_swiglu_supported(int mt, const DecodeShape &s);
+hipError_t launch_gemm_decode_swiglu(const DecodeArgs &p, const DecodeShape &s, int mt, bool prepare_only, hipStream_t stream);
 
 struct PrefillArgs {
     const int8_t *xq;

@@ -110,6 +110,12 @@ def test_argument_validation_happens_before_any_launch(L):
     assert f(odd, 1024, p, p, p, null, 1, 16, 1024, null) == -3
     assert f(p, 1024, p, p, p, null, 17, 16, 1024, null) == -7                  # M beyond token generation
     assert f(p, 16384, p, p, p, null, 4, 16, 16384, null) == -7                 # K beyond what a wave can hold
+    fs = L.w4a8_linear_tiled_swiglu_fp16
+    assert fs(p, 1024, p, p, null, null, 1, 32, 1024, null) == -1
+    assert fs(p, 1024, p, p, p, null, 1, 40, 1024, null) == -2                  # I follows the K contract
+    assert fs(p, 1000, p, p, p, null, 1, 32, 1024, null) == -2
+    assert fs(odd, 1024, p, p, p, null, 1, 32, 1024, null) == -3
+    assert fs(p, 1024, p, p, p, null, 5, 32, 1024, null) == -7
     sg = L.w4a8_gemm_tiled_swiglu
     assert sg(p, p, p, null, p, 4, 64, 64, null) == -1
     assert sg(p, p, p, p, p, 4, 40, 64, null) == -2                            # I follows the K contract

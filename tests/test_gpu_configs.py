@@ -156,8 +156,9 @@ def test_llama13b_layer_stack_stage_wise(gpu, oracle, weights_13b, M):
     quantiser -> gate+up -> SiLU(gate)*up -> quantiser -> down, in the launch configuration the benchmark times at these
     M: the one tiled weight copy through w4a8_gemm_tiled_splitk (weight-streaming kernel up to 64 tokens, in K slices
     for the down projection; large-M kernel above); the fused SiLU*up + quantiser, checked against the two separate
-    kernels.  Up to 64 tokens the row-major entry must give the same bits, and up to 2 tokens so must the linear that
-    quantises its own activations."""
+    kernels.  Up to 64 tokens the row-major entry must give the same bits, and up to 2 tokens so must the linears that
+    quantise their own activations (the four launches the benchmark makes there, the gate+up one with SiLU*up in its
+    epilogue); up to 32 and from 768 tokens the gate+up GEMM with SiLU*up in its epilogue must give the glue kernel's h."""
     t = gpu
     H = synth.LLAMA_SHAPES["13b"]["qkv"][1]
 
@@ -184,16 +185,24 @@ def test_llama13b_layer_stack_stage_wise(gpu, oracle, weights_13b, M):
     down = gemm("down", xq4, sa4)
     act = w4a8.w4a8_silu_mul(gu)
     xq4b, sa4b = w4a8.w4a8_quantize_act(act)
-    if M >= 768:
-        # what the benchmark launches from 768 tokens on: SiLU*up in the gate+up GEMM's epilogue (interleaved channels),
-        # a plain quantiser behind it -- the same h, the same codes and scales
+    if M >= 768 or M <= 32:
+        # what the benchmark launches at these token counts: SiLU*up in the gate+up GEMM's epilogue (interleaved
+        # channels), a plain quantiser behind it -- the same h, the same codes and scales
         w_gu = weights_13b["gate_up"][0]
         wp_i, sw_i = w4a8.w4a8_quantize_weights(w4a8.interleave_gate_up(t.from_numpy(w_gu).cuda()))
-        h_fused = w4a8.w4a8_gemm_tiled_swiglu(xq3, sa3, w4a8.w4a8_tile_weights(wp_i), sw_i)
+        wt_i = w4a8.w4a8_tile_weights(wp_i)
+        h_fused = w4a8.w4a8_gemm_tiled_swiglu(xq3, sa3, wt_i, sw_i)
         xq4c, sa4c = w4a8.w4a8_quantize_act(h_fused)
         assert bool((h_fused.view(t.int16) == act.view(t.int16)).all()), "SiLU*up in the GEMM epilogue vs the glue kernel"
         assert bool((xq4c == xq4).all()) and bool((sa4c.view(t.int32) == sa4.view(t.int32)).all())
-        del wp_i, sw_i, h_fused
+        if M <= 2:
+            # ... and at one or two tokens from fp16 to h in one launch, then the down projection fed fp16
+            h_one = w4a8.w4a8_linear_tiled_swiglu_fp16(o, wt_i, sw_i)
+            assert bool((h_one.view(t.int16) == act.view(t.int16)).all()), "self-quantising gate+up linear with SiLU*up"
+            w, dwp, dsw, dwt = weights_13b["down"]
+            down_one = w4a8.w4a8_linear_tiled_fp16(h_one, dwt, dsw)
+            assert bool((down_one.view(t.int16) == down.view(t.int16)).all()), "self-quantising down projection"
+        del wp_i, sw_i, wt_i, h_fused
     t.cuda.synchronize()
 
     _check_quant_stage(t, oracle, "quant(h)", h, xq1, sa1)

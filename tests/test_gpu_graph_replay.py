@@ -73,3 +73,54 @@ def test_graph_replays_match_eager(gpu, oracle, M, N, K, how):
     got = eager[3].cpu().numpy().astype(np.float64)
     y = y32.astype(np.float64)
     assert np.all(np.abs(got - y) <= np.maximum(2.0 ** -10 * np.abs(y), 2.0 ** -24))
+
+
+@pytest.mark.parametrize("M,I,K,how", [(2, 256, 2080, "fused"), (16, 512, 5120, "tiled"), (48, 160, 5120, "tiled"),
+                                       (300, 8500, 160, "tiled")])
+def test_graph_replays_of_the_swiglu_entries_match_eager(gpu, M, I, K, how):
+    """The entries with SiLU*up in the GEMM's epilogue, captured and replayed the same way (their eager results are
+    checked against the oracle in test_gpu_swiglu.py; here against the chain of separate calls)."""
+    t = gpu
+    w4a8.w4a8_init()
+    w = t.from_numpy(synth.weights_fp16(2 * I, K, config_id=91)).cuda()
+    wp_i, s_w_i = w4a8.w4a8_quantize_weights(w4a8.interleave_gate_up(w))
+    wt_i = w4a8.w4a8_tile_weights(wp_i)
+    wp, s_w = w4a8.w4a8_quantize_weights(w)
+    wt = w4a8.w4a8_tile_weights(wp)
+    xs = [t.from_numpy(synth.activations_fp16(M, K, config_id=91, tag=20 + i)).cuda() for i in range(3)]
+    x = xs[0].clone()
+    xq = t.empty((M, K), dtype=t.int8, device="cuda")
+    s_a = t.empty((M,), dtype=t.float32, device="cuda")
+    h = t.empty((M, I), dtype=t.float16, device="cuda")
+
+    def launch():
+        if how == "fused":
+            w4a8.w4a8_linear_tiled_swiglu_fp16(x, wt_i, s_w_i, h=h)
+        else:
+            w4a8.w4a8_quantize_act(x, xq, s_a)
+            w4a8.w4a8_gemm_tiled_swiglu(xq, s_a, wt_i, s_w_i, h=h)
+
+    eager = []
+    for xi in xs:
+        x.copy_(xi)
+        launch()
+        eager.append(h.clone())
+        q, sa = w4a8.w4a8_quantize_act(x)
+        chain = w4a8.w4a8_silu_mul(w4a8.w4a8_gemm_tiled(q, sa, wt, s_w))
+        assert bool((eager[-1].view(t.int16) == chain.view(t.int16)).all()), "eager result differs from the separate calls"
+    t.cuda.synchronize()
+    x.copy_(xs[0])
+    side = t.cuda.Stream()
+    side.wait_stream(t.cuda.current_stream())
+    graph = t.cuda.CUDAGraph()
+    with t.cuda.stream(side):
+        with t.cuda.graph(graph):
+            launch()
+    t.cuda.current_stream().wait_stream(side)
+    for rnd in range(2):
+        for i, xi in enumerate(xs):
+            x.copy_(xi)
+            h.fill_(7.0)
+            graph.replay()
+            t.cuda.synchronize()
+            assert bool((h.view(t.int16) == eager[i].view(t.int16)).all()), f"replay {rnd}.{i} of {how} M={M} differs from eager"

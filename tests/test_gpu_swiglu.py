@@ -1,6 +1,8 @@
-"""GPU parity of the gate+up GEMM that applies SiLU(gate) * up in its epilogue (w4a8_gemm_tiled_swiglu): against the
-CPU oracle (GEMM, Eq. (6),(7), then the fp64 glue) and, bit for bit, against the library's own two calls (w4a8_gemm_tiled
-over the weights in the usual order, then w4a8_silu_mul), through the C ABI."""
+"""GPU parity of the gate+up GEMM that applies SiLU(gate) * up in its epilogue (w4a8_gemm_tiled_swiglu, and
+w4a8_linear_tiled_swiglu_fp16, which also quantises its input): against the CPU oracle (GEMM, Eq. (6),(7), then the fp64
+glue) and, bit for bit, against the library's own two calls (w4a8_gemm_tiled over the weights in the usual order, then
+w4a8_silu_mul), through the C ABI.  Token counts on both sides of 64: the weight-streaming kernel below, the large-M
+kernel above."""
 import numpy as np
 import pytest
 
@@ -27,8 +29,8 @@ def _case(t, oracle, M, I, K, tag):
     return x, w, gate_up, h_two, h
 
 
-@pytest.mark.parametrize("M", [1, 33, 130, 300, 1024])
-@pytest.mark.parametrize("I,K", [(32, 32), (96, 160), (544, 1056), (4128, 256)])
+@pytest.mark.parametrize("M", [1, 4, 5, 16, 17, 33, 48, 64, 65, 130, 300, 1024])
+@pytest.mark.parametrize("I,K", [(32, 32), (96, 160), (544, 1056), (4128, 256), (160, 5120), (96, 8192), (64, 13824)])
 def test_swiglu_epilogue_matches_two_calls_and_oracle(gpu, oracle, M, I, K):
     t = gpu
     x, w, gate_up, h_two, h = _case(t, oracle, M, I, K, 91)
@@ -58,6 +60,33 @@ def test_swiglu_two_phase_launch_at_the_13b_shape(gpu, oracle):
     assert_equal_bits(h.cpu().numpy().view(np.uint16), h_two.cpu().numpy().view(np.uint16), "fused vs two calls, two phases")
 
 
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+@pytest.mark.parametrize("I,K", [(32, 32), (96, 160), (544, 1056), (2592, 5120), (96, 8192), (64, 11008)])
+def test_fused_swiglu_linear_matches_the_separate_calls(gpu, oracle, M, I, K):
+    """fp16 in, h out in one launch: the scales of the per-token quantiser and every bit of h as from
+    w4a8_quantize_act + w4a8_gemm_tiled_swiglu, and as from the chain with the weights in the usual order."""
+    t = gpu
+    if M * K > 45000:
+        pytest.skip("the rows do not fit in LDS twice over: refused, as for w4a8_linear_tiled_fp16")
+    x, w, gate_up, h_two, h = _case(t, oracle, M, I, K, 93)
+    dx = t.from_numpy(x).cuda()
+    dw = t.from_numpy(w).cuda()
+    wp_i, s_w_i = w4a8.w4a8_quantize_weights(w4a8.interleave_gate_up(dw))
+    s_a = t.full((M,), -1.0, dtype=t.float32, device="cuda")
+    h_one = w4a8.w4a8_linear_tiled_swiglu_fp16(dx, w4a8.w4a8_tile_weights(wp_i), s_w_i, s_a_out=s_a)
+    t.cuda.synchronize()
+    _, s_a_o = oracle.quantize_act(x)
+    assert_equal_bits(s_a.cpu().numpy().view(np.uint32), s_a_o.view(np.uint32), "scales")
+    assert_equal_bits(h_one.cpu().numpy().view(np.uint16), h.cpu().numpy().view(np.uint16), f"one launch vs two M={M} I={I} K={K}")
+    assert_equal_bits(h_one.cpu().numpy().view(np.uint16), h_two.cpu().numpy().view(np.uint16), f"one launch vs chain M={M} I={I} K={K}")
+    # a strided view of a wider matrix as input
+    wide = t.zeros((M, 2 * K + 64), dtype=t.float16, device="cuda")
+    wide[:, 64:64 + K] = dx
+    h_view = w4a8.w4a8_linear_tiled_swiglu_fp16(wide[:, 64:64 + K], w4a8.w4a8_tile_weights(wp_i), s_w_i)
+    t.cuda.synchronize()
+    assert_equal_bits(h_view.cpu().numpy().view(np.uint16), h_one.cpu().numpy().view(np.uint16), "strided input")
+
+
 def test_swiglu_refuses_what_it_does_not_serve(gpu):
     t = gpu
     xq = t.zeros((4, 64), dtype=t.int8, device="cuda")
@@ -68,3 +97,8 @@ def test_swiglu_refuses_what_it_does_not_serve(gpu):
         with pytest.raises(w4a8.W4A8Error) as e:
             w4a8.w4a8_gemm_tiled_swiglu(xq, s_a, wt, s_w)
         assert e.value.code == -2
+    x = t.zeros((5, 64), dtype=t.float16, device="cuda")   # the fused quantiser serves up to four tokens
+    wt = t.zeros((w4a8.w4a8_tiled_weight_bytes(64, 64),), dtype=t.uint8, device="cuda")
+    with pytest.raises(w4a8.W4A8Error) as e:
+        w4a8.w4a8_linear_tiled_swiglu_fp16(x, wt, t.ones((64,), dtype=t.float32, device="cuda"))
+    assert e.value.code == -7
