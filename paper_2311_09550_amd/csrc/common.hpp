@@ -109,6 +109,21 @@ __device__ __forceinline__ float absmax8(v4u c, float m) {
     return m;
 }
 
+// Maximum over the wave of a non-negative value (as such it orders like its bit pattern), in every lane.  Six DPP steps
+// in the vector ALU: shifts within rows of 16 lanes (lanes shifted in from outside a row contribute 0), then lane 15 of
+// a row broadcast into the next row and lane 31 into the upper half; lane 63 ends up with the maximum.  A butterfly of
+// shuffles, which goes through the LDS crossbar, costs six dependent LDS round trips instead.
+__device__ __forceinline__ float wave_max_nonneg(float v) {
+    int x = __float_as_int(v);
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true));   // row_shr:1
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true));   // row_shr:2
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true));   // row_shr:4
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true));   // row_shr:8
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false));  // row_bcast:15 into rows 1 and 3
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false));  // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(x, 63));
+}
+
 // Symmetric quantisation of one row (Eq. (2) with zero point 0): code = clamp(rne(fl32(x / scale)), lo, hi).
 //
 // The definition divides.  A correctly rounded fp32 division costs about ten instructions, so the common case

@@ -120,8 +120,8 @@ __device__ __forceinline__ void wait_vmcnt_at_most() {
 
 // FQ: the kernel is handed fp16 activations (p.x16, rows p.ldx apart) and quantises them per token itself, exactly as
 // quantize_act_kernel would (Sec. 3 "per token"; Eq. (2), z = 0): the workgroup copies the fp16 rows into LDS, finds
-// the row maxima, quantises the rows into a second LDS area (every thread its share), and the waves pick their
-// operands from there as in the staged form.  One launch instead of two for a linear at token-generation sizes (the
+// the row maxima (one barrier), and then every wave quantises the k steps it multiplies into a second LDS area and
+// picks its operands from there: the waves' parts are disjoint, so nothing but the maxima crosses waves.  One launch instead of two for a linear at token-generation sizes (the
 // kind of fusion across operators the paper's engine relies on, Sec. 6.1).  M <= 4: every workgroup repeats the
 // quantisation, which costs about ten vector instructions per value, so beyond a few rows a launch of its own is
 // cheaper.
@@ -360,9 +360,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     }
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (FQ) {
-        // The workgroup quantises the M <= 4 rows together, each thread its share (were every lane to quantise the
-        // operands it multiplies, a wave would spend some 1600 vector instructions on it whatever M is, and all
-        // workgroups repeat the work: measured slower than a quantiser launch of its own).
+        // The row maxima are found by the workgroup together; then every wave quantises the k steps it multiplies,
+        // its lanes sharing the work (were every lane to quantise the operands it multiplies itself, a wave would
+        // spend some 1600 vector instructions on it whatever M is: measured slower than a quantiser launch of its own).
         constexpr int T = WAVES * 64;
         wait_vmcnt_at_most<P * XS>();  // the copy and the scales are in: only the weight loads issued behind them remain
         __builtin_amdgcn_sched_barrier(0);
@@ -371,14 +371,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
         const uint8_t *x16 = epoch_lds + p.x16_lds_offset;
         uint8_t *xq_lds = epoch_lds + p.x_lds_offset;
         const int chunks_row = p.K >> 3;  // 8 fp16 = 16 bytes
-        float *scale_lds = amax_lds + 64;
+        sa[0] = 0.f;
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             if (m < p.M) {  // uniform
                 float pm = 0.f;
                 for (int c = tid; c < chunks_row; c += T) pm = absmax8(*(const v4u *)(x16 + m * p.x16_lds_pitch + c * 16), pm);
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) pm = fmaxf(pm, __shfl_xor(pm, off, 64));
+                pm = wave_max_nonneg(pm);
                 if (lane == 0) amax_lds[wave * 4 + m] = pm;
             }
         }
@@ -390,26 +389,29 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
 #pragma unroll
                 for (int w = 0; w < WAVES; ++w) amax = fmaxf(amax, amax_lds[w * 4 + m]);
                 const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);  // amax == 0 gives scale 0
-                if (tid == 0) {
-                    scale_lds[m] = rq.scale;
-                    if (p.s_a_out != nullptr && blockIdx.x == 0) p.s_a_out[m] = rq.scale;
-                }
+                if (tid == 0 && p.s_a_out != nullptr && blockIdx.x == 0) p.s_a_out[m] = rq.scale;
+                if (min(r, p.M - 1) == m) sa[0] = rq.scale;
+                // Every wave quantises the k steps it multiplies, all lanes sharing the work (16 chunks of 8 values
+                // per step; units of 4 values, which spread more evenly, measured 2 % slower), into the int8 copy of
+                // the row: the waves' parts are disjoint and a wave reads back only its own, so no barrier follows --
+                // LDS serves a wave's accesses in program order.
                 const bool zero_row = amax == 0.f;
-                for (int c = tid; c < chunks_row; c += T) {
-                    v2u codes = v2u{0u, 0u};
-                    if (!zero_row) {
-                        float xf[8];
-                        int q8[8];
-                        halves8(*(const v4u *)(x16 + m * p.x16_lds_pitch + c * 16), xf);
-                        rq.codes8(xf, q8);
-                        codes = pack_i8x8(q8);
+                for (int u = lane; u < XS * 16; u += 64) {
+                    const int ks = k_step(u >> 4), k0 = ks * 128 + (u & 15) * 8;
+                    if (ks < ks_limit && k0 < p.K) {
+                        v2u codes = v2u{0u, 0u};
+                        if (!zero_row) {
+                            float xf[8];
+                            int q8[8];
+                            halves8(*(const v4u *)(x16 + m * p.x16_lds_pitch + k0 * 2), xf);
+                            rq.codes8(xf, q8);
+                            codes = pack_i8x8(q8);
+                        }
+                        *(v2u *)(xq_lds + m * pitch + k0) = codes;
                     }
-                    *(v2u *)(xq_lds + m * pitch + c * 8) = codes;
                 }
             }
         }
-        lds_barrier();
-        sa[0] = scale_lds[min(r, p.M - 1)];
 #pragma unroll
         for (int i = 0; i < XS; ++i) {
             const int m = min(r, p.M - 1);
