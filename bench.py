@@ -144,13 +144,15 @@ class LayerStack:
     SWIGLU_FROM_M = 768
     # ... and the token count up to which the weight-streaming kernel does (its epilogue is a few lanes' work)
     SWIGLU_UP_TO_M = 32
+    # Token count up to which every linear quantises its own input (w4a8_linear_tiled_fp16 and its SiLU*up form)
+    FUSE_UP_TO_M = 2
 
     def __init__(self, torch, w4a8, synth, M, weights, model="13b", fuse=False):
         self.torch, self.w4a8, self.M = torch, w4a8, M
         self.shapes = synth.LLAMA_SHAPES[model]
         # measured, the forms timed in turn: 37.8 against 46.9 us per layer at M = 1 (40.1 with SiLU*up and the down
         # projection's quantiser as a launch of their own), 44.1 against 47.1 at M = 2, slower from M = 3
-        self.fused = bool(fuse and M <= 2)
+        self.fused = bool(fuse and M <= self.FUSE_UP_TO_M)
         dev = "cuda"
         self.wp = {k: v[0] for k, v in weights.items()}
         self.s_w = {k: v[1] for k, v in weights.items()}

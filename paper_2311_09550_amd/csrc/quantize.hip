@@ -12,11 +12,16 @@ namespace {
 constexpr int kRowThreads = 256;
 constexpr int kCache = 8;  // 16-byte chunks a thread keeps in registers between the two passes (K <= 16384)
 
-// maximum over the workgroup; every thread gets the result
-template <int THREADS = kRowThreads>
+// maximum over the workgroup; every thread gets the result.  NONNEG: the values are absolute values (the wave's step
+// then runs in the vector ALU instead of through six shuffles)
+template <int THREADS = kRowThreads, bool NONNEG = false>
 __device__ __forceinline__ float block_max(float v, float *scratch) {
+    if constexpr (NONNEG) {
+        v = wave_max_nonneg(v);
+    } else {
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+        for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    }
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) scratch[wave] = v;
     __syncthreads();
@@ -71,7 +76,7 @@ __global__ __launch_bounds__(kRowThreads, 8) void quantize_act_kernel(const uint
         amax = absmax8(cache[i], amax);
     }
     for (int c = threadIdx.x + kCache * kRowThreads; c < chunks; c += kRowThreads) amax = absmax8(src[c], amax);
-    amax = block_max(amax, scratch);
+    amax = block_max<kRowThreads, true>(amax, scratch);
 
     const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
     if (threadIdx.x == 0) s_a[m] = rq.scale;  // amax == 0 gives scale 0
@@ -108,7 +113,7 @@ __global__ __launch_bounds__(kRowThreads, 8) void quantize_weights_kernel(const 
 
     float amax = 0.f;
     for (int c = threadIdx.x; c < chunks; c += kRowThreads) amax = absmax8(src[c], amax);
-    amax = block_max(amax, scratch);
+    amax = block_max<kRowThreads, true>(amax, scratch);
 
     const RowQuantizer rq(amax, 7.0f, -8.f, 7.f);
     if (threadIdx.x == 0) s_w[n] = rq.scale;
@@ -216,7 +221,7 @@ __global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const 
     }
     for (int c = threadIdx.x + kFusedCache * kFusedThreads; c < chunks; c += kFusedThreads)
         amax = absmax8(silu_mul8(gate[c], up[c]), amax);
-    amax = block_max<kFusedThreads>(amax, scratch);
+    amax = block_max<kFusedThreads, true>(amax, scratch);
 
     const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
     if (threadIdx.x == 0) s_a[m] = rq.scale;
