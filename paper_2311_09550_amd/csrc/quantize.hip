@@ -11,6 +11,7 @@ namespace {
 
 constexpr int kRowThreads = 256;
 constexpr int kCache = 8;  // 16-byte chunks a thread keeps in registers between the two passes (K <= 16384)
+constexpr int kFewRows = 128;  // token counts up to which the activation quantiser spreads a row over 1024 threads
 
 // maximum over the workgroup; every thread gets the result.  NONNEG: the values are absolute values (the wave's step
 // then runs in the vector ALU instead of through six shuffles)
@@ -59,8 +60,12 @@ __device__ __forceinline__ v4u silu_mul8(v4u gv, v4u uv) {
 // Loads and stores carry the non-temporal hint: a row is read once and its codes are written once (measured at
 // M = 1024 .. 2048, K = 5120: 8 to 11 % off the kernel's time, nothing lost at small M; the GEMM that reads the codes
 // next is not slowed).  A row per wave or per two waves, several rows to a workgroup, was slower at every M tried.
-__global__ __launch_bounds__(kRowThreads, 8) void quantize_act_kernel(const uint16_t *__restrict__ x, int8_t *__restrict__ xq,
-                                                                   float *__restrict__ s_a, int K, long long ldx) {
+// THREADS, CACHE: threads per row and chunks a thread keeps between the passes.  256 x 8 where the rows fill the chip;
+// for a few rows (token generation) 1024 x 2, which shortens each thread's share of the one row its compute unit has.
+template <int THREADS, int CACHE>
+__global__ __launch_bounds__(THREADS, THREADS <= 256 ? 8 : 1) void quantize_act_kernel(const uint16_t *__restrict__ x, int8_t *__restrict__ xq,
+                                                              float *__restrict__ s_a, int K, long long ldx) {
+    constexpr int kRowThreads = THREADS, kCache = CACHE;  // shadow the file-scope defaults
     __shared__ float scratch[kRowThreads / 64];
     const int m = blockIdx.x;
     const int chunks = K >> 3;  // 8 fp16 = 16 bytes
@@ -249,7 +254,12 @@ __global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const 
 }
 
 hipError_t launch_quantize_act(const void *x, long long ldx, int8_t *xq, float *s_a, int M, int K, hipStream_t stream) {
-    hipLaunchKernelGGL(quantize_act_kernel, dim3(M), dim3(kRowThreads), 0, stream, (const uint16_t *)x, xq, s_a, K, ldx);
+    // up to half a row per compute unit the rows are spread over four times the threads
+    if (M <= kFewRows)
+        hipLaunchKernelGGL((quantize_act_kernel<1024, 2>), dim3(M), dim3(1024), 0, stream, (const uint16_t *)x, xq, s_a, K, ldx);
+    else
+        hipLaunchKernelGGL((quantize_act_kernel<kRowThreads, kCache>), dim3(M), dim3(kRowThreads), 0, stream, (const uint16_t *)x,
+                           xq, s_a, K, ldx);
     return hipGetLastError();
 }
 
