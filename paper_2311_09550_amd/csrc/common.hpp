@@ -152,6 +152,32 @@ struct RowQuantizer {
             for (int j = 0; j < 8; ++j) q[j] = (int)fminf(fmaxf(rintf(__fdiv_rn(x[j], scale)), lo), hi);
         }
     }
+    // The same eight codes as bytes of two words, for rows quantised to [-qmax, qmax] with the row's own maximum
+    // (the activation quantisers).  There the shortcut needs no clamp: |x| <= amax gives |q'| <= qmax (1 + 3 * 2^-24),
+    // which rounds to at most qmax.  Rounding by adding 1.5 * 2^23: the sum's low mantissa bits are rne(q') in two's
+    // complement, so its low byte is the code, and sum - 1.5 * 2^23 is rne(q') as a float, exactly.
+    __device__ __forceinline__ v2u packed8_own_max(const float (&x)[8]) const {
+        constexpr float kShift = 12582912.0f;
+        unsigned b[8];
+        float off = 0.f;  // largest distance of a q' from its nearest integer
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float qp = x[j] * recip;
+            const float t = qp + kShift;
+            off = fmaxf(off, fabsf(qp - (t - kShift)));
+            b[j] = __float_as_uint(t);
+        }
+        if (off > 0.5f - 1e-4f) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) b[j] = (unsigned)(int)fminf(fmaxf(rintf(__fdiv_rn(x[j], scale)), lo), hi);
+        }
+        v2u o;  // v_perm_b32: selector bytes 0-3 pick from the second operand, 4-7 from the first, 0x0c gives zero
+        const unsigned p01 = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), p23 = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+        const unsigned p45 = __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), p67 = __builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u);
+        o.x = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+        o.y = __builtin_amdgcn_perm(p67, p45, 0x05040100u);
+        return o;
+    }
 };
 
 // silu(gate) * up in fp32 from two fp16 values: g / (1 + e^-g) with the hardware's exp2 and reciprocal (about 1 ulp of
@@ -176,13 +202,6 @@ __device__ __forceinline__ void halves8(v4u v, float (&x)[8]) {
         x[2 * j] = lo_half(v[j]);
         x[2 * j + 1] = hi_half(v[j]);
     }
-}
-
-__device__ __forceinline__ v2u pack_i8x8(const int (&q)[8]) {
-    v2u o;
-    o.x = (q[0] & 255) | ((q[1] & 255) << 8) | ((q[2] & 255) << 16) | ((unsigned)(q[3] & 255) << 24);
-    o.y = (q[4] & 255) | ((q[5] & 255) << 8) | ((q[6] & 255) << 16) | ((unsigned)(q[7] & 255) << 24);
-    return o;
 }
 
 }  // namespace w4a8

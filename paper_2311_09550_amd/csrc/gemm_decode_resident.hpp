@@ -402,10 +402,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
                         v2u codes = v2u{0u, 0u};
                         if (!zero_row) {
                             float xf[8];
-                            int q8[8];
                             halves8(*(const v4u *)(x16 + m * p.x16_lds_pitch + k0 * 2), xf);
-                            rq.codes8(xf, q8);
-                            codes = pack_i8x8(q8);
+                            codes = rq.packed8_own_max(xf);
                         }
                         *(v2u *)(xq_lds + m * pitch + k0) = codes;
                     }

@@ -92,10 +92,8 @@ __global__ __launch_bounds__(THREADS, THREADS <= 256 ? 8 : 1) void quantize_act_
         v2u o = v2u{0, 0};
         if (!zero_row) {
             float xf[8];
-            int q[8];
             halves8(v, xf);
-            rq.codes8(xf, q);
-            o = pack_i8x8(q);
+            o = rq.packed8_own_max(xf);
         }
         __builtin_nontemporal_store(o, dst + c);
     };
@@ -237,10 +235,8 @@ __global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const 
         v2u o = v2u{0, 0};
         if (!zero_row) {
             float xf[8];
-            int q[8];
             halves8(v, xf);
-            rq.codes8(xf, q);
-            o = pack_i8x8(q);
+            o = rq.packed8_own_max(xf);
         }
         dst[c] = o;
     };
