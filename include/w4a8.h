@@ -201,8 +201,8 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
  * into the weight-streaming GEMM (fusion across operators, Sec. 6.1; the per-token overhead of Sec. 3).  The result is,
  * bit for bit,
  *   w4a8_quantize_act_strided(x_fp16, ldx, xq, s_a, M, K);  w4a8_gemm_tiled(xq, s_a, wt, s_w, out_fp16, M, N, K)
- * without xq ever going to memory: every persistent workgroup copies the fp16 rows into LDS, finds the row maxima and
- * quantises the rows there (Eq. (2), z = 0, same rounding rule), and its waves take their operands from LDS.
+ * without xq ever going to memory: every persistent workgroup copies the fp16 rows into LDS and finds the row maxima,
+ * and each of its waves quantises there the part of the rows it multiplies (Eq. (2), z = 0, same rounding rule).
  *   x_fp16 [M] rows of K fp16 values, ldx elements apart (ldx >= K, ldx % 8 == 0)      in
  *   wt     tiled weights of w4a8_tile_weights                                          in
  *   s_w    [N] fp32                                                                    in
@@ -210,8 +210,9 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
  *   s_a_out  [M] fp32 or NULL: where the per-token scales are written as well          out
  * M <= 4 and the rows must fit in LDS twice over (fp16 and int8: about M * K <= 40000); W4A8_ERR_ARG otherwise, and
  * the caller falls back to the two calls above.  Every workgroup repeats the quantisation (about ten vector
- * instructions per value), so the fusion pays for one or two tokens (measured on a LLaMA-13B layer: 41 against 47 us
- * at M = 1, 45 against 49.5 at M = 2) and a quantiser launch of its own is cheaper from three.
+ * instructions per value), so the fusion pays for one or two tokens (measured on a LLaMA-13B layer whose four linears
+ * all run this way, the gate / up one through w4a8_linear_tiled_swiglu_fp16: 36.4 against 45.7 us at M = 1, 42.8
+ * against 46.6 at M = 2) and a quantiser launch of its own is cheaper from three (49.2 against 47.3).
  */
 int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16,
                            float *s_a_out, int M, int N, int K, void *stream);
