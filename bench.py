@@ -133,7 +133,7 @@ class LayerStack:
     Eight launches (three per-token quantisers, the fused SiLU*up + quantiser, four GEMMs).  Up to SWIGLU_UP_TO_M and
     from SWIGLU_FROM_M tokens on the gate+up GEMM applies SiLU*up in its epilogue (w4a8_gemm_tiled_swiglu) and a plain
     per-token quantiser follows: still eight launches, but the M x 2I intermediate is neither written nor read.
-    M <= 2 with fuse=True: four launches -- every linear quantises its own activations inside the weight-streaming
+    M <= FUSE_UP_TO_M with fuse=True: four launches -- every linear quantises its own activations inside the weight-streaming
     GEMM (w4a8_linear_tiled_fp16), and the gate+up one also applies SiLU*up (w4a8_linear_tiled_swiglu_fp16), so that
     the down projection is fed fp16 like the others."""
 
@@ -145,13 +145,13 @@ class LayerStack:
     # ... and the token count up to which the weight-streaming kernel does (its epilogue is a few lanes' work)
     SWIGLU_UP_TO_M = 32
     # Token count up to which every linear quantises its own input (w4a8_linear_tiled_fp16 and its SiLU*up form)
-    FUSE_UP_TO_M = 2
+    FUSE_UP_TO_M = 3
 
     def __init__(self, torch, w4a8, synth, M, weights, model="13b", fuse=False):
         self.torch, self.w4a8, self.M = torch, w4a8, M
         self.shapes = synth.LLAMA_SHAPES[model]
-        # measured, the forms timed in turn: 37.8 against 46.9 us per layer at M = 1 (40.1 with SiLU*up and the down
-        # projection's quantiser as a launch of their own), 44.1 against 47.1 at M = 2, slower from M = 3
+        # measured, the forms timed in turn: 35.3 against 43.5 us per layer at M = 1, 39.9 against 44.8 at M = 2, 44.6
+        # against 45.4 at M = 3; at M = 4 the down projection's rows no longer fit LDS twice over
         self.fused = bool(fuse and M <= self.FUSE_UP_TO_M)
         dev = "cuda"
         self.wp = {k: v[0] for k, v in weights.items()}
@@ -283,11 +283,11 @@ def roofline_row(M, N, K, us):
             "bound": "hbm" if t_mem >= t_mfma else "mfma", "roofline_frac": round(max(t_mem, t_mfma) / us, 4)}
 
 
-def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 2, 16, 64, 128, 1024, 2048), steps_per_graph=8, replays=6):
+def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 2, 3, 16, 64, 128, 1024, 2048), steps_per_graph=8, replays=6):
     """The decoder layer's linear stack at several M, replayed from a HIP graph (what a serving loop does; at small M
     the launches would otherwise be timed by the interpreter).  Layer time = graph time / steps; the GEMM share is the
     time of a second graph that holds only the four plain GEMMs (pre-quantised inputs), over the layer time.  At
-    M <= 2 the layer runs with the quantisers folded into the GEMMs (4 launches), and the unfused form (8 launches)
+    M <= 3 the layer runs with the quantisers folded into the GEMMs (4 launches), and the unfused form (8 launches)
     is timed beside it.  One layer's weights (158 MB) stay resident in the last-level cache across replays: the small-M
     rows are a warm-cache figure, the HBM-bound figure is the `decode` list."""
     rows = []

@@ -210,9 +210,9 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
  *   s_a_out  [M] fp32 or NULL: where the per-token scales are written as well          out
  * M <= 4 and the rows must fit in LDS twice over (fp16 and int8: about M * K <= 40000); W4A8_ERR_ARG otherwise, and
  * the caller falls back to the two calls above.  Every workgroup repeats the quantisation (about ten vector
- * instructions per value), so the fusion pays for one or two tokens (measured on a LLaMA-13B layer whose four linears
- * all run this way, the gate / up one through w4a8_linear_tiled_swiglu_fp16: 36.4 against 45.7 us at M = 1, 42.8
- * against 46.6 at M = 2) and a quantiser launch of its own is cheaper from three (49.2 against 47.3).
+ * instructions per value), so the fusion pays for a few tokens only (measured on a LLaMA-13B layer whose four linears
+ * all run this way, the gate / up one through w4a8_linear_tiled_swiglu_fp16: 35.3 against 43.5 us at M = 1, 39.9
+ * against 44.8 at M = 2, 44.6 against 45.4 at M = 3).
  */
 int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16,
                            float *s_a_out, int M, int N, int K, void *stream);

@@ -150,13 +150,13 @@ def weights_13b(gpu):
     gpu.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("M", [1, 2, 16, 64, 128, 1024, 2048])
+@pytest.mark.parametrize("M", [1, 2, 3, 16, 64, 128, 1024, 2048])
 def test_llama13b_layer_stack_stage_wise(gpu, oracle, weights_13b, M):
     """Hidden states -> quantiser -> QKV -> (the Q slice stands in for the attention output) -> quantiser -> O ->
     quantiser -> gate+up -> SiLU(gate)*up -> quantiser -> down, in the launch configuration the benchmark times at these
     M: the one tiled weight copy through w4a8_gemm_tiled_splitk (weight-streaming kernel up to 64 tokens, in K slices
     for the down projection; large-M kernel above); the fused SiLU*up + quantiser, checked against the two separate
-    kernels.  Up to 64 tokens the row-major entry must give the same bits, and up to 2 tokens so must the linears that
+    kernels.  Up to 64 tokens the row-major entry must give the same bits, and up to 3 tokens so must the linears that
     quantise their own activations (the four launches the benchmark makes there, the gate+up one with SiLU*up in its
     epilogue); up to 32 and from 768 tokens the gate+up GEMM with SiLU*up in its epilogue must give the glue kernel's h."""
     t = gpu
@@ -168,7 +168,7 @@ def test_llama13b_layer_stack_stage_wise(gpu, oracle, weights_13b, M):
         if M <= 64:
             same = w4a8.w4a8_gemm(dxq, dsa, dwp, dsw)
             assert bool((out.view(t.int16) == same.view(t.int16)).all()), name + ": row-major entry differs from the tiled one"
-        if M <= 2 and x_fp16 is not None:
+        if M <= 3 and x_fp16 is not None:
             fused = w4a8.w4a8_linear_tiled_fp16(x_fp16, dwt, dsw)
             assert bool((out.view(t.int16) == fused.view(t.int16)).all()), name + ": self-quantising linear differs"
         return out
@@ -195,8 +195,8 @@ def test_llama13b_layer_stack_stage_wise(gpu, oracle, weights_13b, M):
         xq4c, sa4c = w4a8.w4a8_quantize_act(h_fused)
         assert bool((h_fused.view(t.int16) == act.view(t.int16)).all()), "SiLU*up in the GEMM epilogue vs the glue kernel"
         assert bool((xq4c == xq4).all()) and bool((sa4c.view(t.int32) == sa4.view(t.int32)).all())
-        if M <= 2:
-            # ... and at one or two tokens from fp16 to h in one launch, then the down projection fed fp16
+        if M <= 3:
+            # ... and at up to three tokens from fp16 to h in one launch, then the down projection fed fp16
             h_one = w4a8.w4a8_linear_tiled_swiglu_fp16(o, wt_i, sw_i)
             assert bool((h_one.view(t.int16) == act.view(t.int16)).all()), "self-quantising gate+up linear with SiLU*up"
             w, dwp, dsw, dwt = weights_13b["down"]
