@@ -177,12 +177,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
         constexpr int kPaired = 2 * (XS / 2);
         return ks_first + (i < kPaired ? ((i >> 1) * WAVES + wave) * 2 + (i & 1) : kPaired * WAVES + wave);
     };
-    bool live[XS];
-#pragma unroll
-    for (int i = 0; i < XS; ++i) {
+    // whether this lane's K group of the wave's k step i exists; evaluated where it is used, so that the steps' address
+    // arithmetic does not stand between the start of the wave and its first loads
+    auto live_step = [&](int i) {
         const int ks = k_step(i);
-        live[i] = ks < ks_limit && (ks * 128 + 32 * g) < p.K;
-    }
+        return ks < ks_limit && (ks * 128 + 32 * g) < p.K;
+    };
 
     // Issue order: activations, scales, weights.  A compute unit accepts only some 40 to 50 outstanding wave-wide
     // loads; whatever is issued behind that many waits for the first returns, a memory latency later.  The weight
@@ -312,7 +312,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
                 // rows past M read row M-1: what they produce lands in output columns that are never stored;
                 // a dead K group reads the start of the row: it meets zero weights
                 const int m = min(16 * mt + r, p.M - 1);
-                const v4u *px = (const v4u *)(p.xq + (size_t)m * p.K + (live[i] ? k_step(i) * 128 + 32 * g : 0));
+                const v4u *px = (const v4u *)(p.xq + (size_t)m * p.K + (live_step(i) ? k_step(i) * 128 + 32 * g : 0));
                 xraw[i][mt][0] = px[0];
                 xraw[i][mt][1] = px[1];
             }
@@ -335,11 +335,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
                                    : (unsigned)((size_t)p.N * (p.K >> 1));
     const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, w_bytes, 0x00020000);
     unsigned w_off[XS];
-#pragma unroll
-    for (int i = 0; i < XS; ++i) {
-        const int ks = k_step(i);
-        w_off[i] = !live[i] ? kNowhere : TILED ? (unsigned)(ks * kTiledBlockBytes + 512 * g) : (unsigned)(ks * 64 + 16 * g);
-    }
     const unsigned w_stride = (unsigned)(p.K >> 1);
     auto w_row = [&](int c) {
         const int n = row0 + R * c + r;
@@ -356,7 +351,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
     for (int q = 0; q < P; ++q) {
         const unsigned row = w_row(q);
 #pragma unroll
-        for (int i = 0; i < XS; ++i) wreg[q][i] = w_load(row, w_off[i]);
+        for (int i = 0; i < XS; ++i) {
+            if (q == 0) {
+                // a step's offset is worked out right before its first load and the compiler is held to that: with
+                // all offsets first, a wave with 14 steps would spend half a microsecond before its first weight load
+                const int ks = k_step(i);
+                w_off[i] = !live_step(i) ? kNowhere : TILED ? (unsigned)(ks * kTiledBlockBytes + 512 * g) : (unsigned)(ks * 64 + 16 * g);
+            }
+            wreg[q][i] = w_load(row, w_off[i]);
+            if (q == 0) __builtin_amdgcn_sched_barrier(0);
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (FQ) {
@@ -413,7 +417,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
 #pragma unroll
         for (int i = 0; i < XS; ++i) {
             const int m = min(r, p.M - 1);
-            const v4u *px = (const v4u *)(xq_lds + m * pitch + (live[i] ? k_step(i) * 128 + 32 * g : 0));
+            const v4u *px = (const v4u *)(xq_lds + m * pitch + (live_step(i) ? k_step(i) * 128 + 32 * g : 0));
             xraw[i][0][0] = px[0];
             xraw[i][0][1] = px[1];
         }
@@ -445,7 +449,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int m = min(16 * mt + r, p.M - 1);
-                const v4u *px = (const v4u *)(xs + m * pitch + (live[i] ? k_step(i) * 128 + 32 * g : 0));
+                const v4u *px = (const v4u *)(xs + m * pitch + (live_step(i) ? k_step(i) * 128 + 32 * g : 0));
                 xraw[i][mt][0] = px[0];
                 xraw[i][mt][1] = px[1];
             }
