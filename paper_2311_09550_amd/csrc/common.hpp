@@ -99,14 +99,18 @@ __device__ __forceinline__ float half_bits_to_float(unsigned short h) { return _
 __device__ __forceinline__ float lo_half(unsigned w) { return half_bits_to_float((unsigned short)(w & 0xFFFFu)); }
 __device__ __forceinline__ float hi_half(unsigned w) { return half_bits_to_float((unsigned short)(w >> 16)); }
 
-// absolute maximum of eight fp16 values held in four words
-__device__ __forceinline__ float absmax8(v4u c, float m) {
+// Running absolute maximum of fp16 values, two at a time: with the sign bits cleared, finite fp16 values order like
+// their bit patterns, so the maximum is a packed 16-bit integer maximum (one AND and one v_pk_max_u16 per two values)
+// and nothing is converted until the end.  m2 holds the two running maxima (start from 0).
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned absmax8_packed(v4u c, unsigned m2) {
+    u16x2 m = __builtin_bit_cast(u16x2, m2);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        m = fmaxf(m, fabsf(lo_half(c[j])));
-        m = fmaxf(m, fabsf(hi_half(c[j])));
-    }
-    return m;
+    for (int j = 0; j < 4; ++j) m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2, c[j] & 0x7FFF7FFFu));
+    return __builtin_bit_cast(unsigned, m);
+}
+__device__ __forceinline__ float absmax_packed_value(unsigned m2) {
+    return half_bits_to_float((unsigned short)max(m2 & 0xFFFFu, m2 >> 16));
 }
 
 // Maximum over the wave of a non-negative value (as such it orders like its bit pattern), in every lane.  Six DPP steps
@@ -162,9 +166,11 @@ struct RowQuantizer {
         float off = 0.f;  // largest distance of a q' from its nearest integer
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const float qp = x[j] * recip;
-            const float t = qp + kShift;
-            off = fmaxf(off, fabsf(qp - (t - kShift)));
+            // fused: t = rne(x * recip) + kShift with the product exact (closer to x / scale than q' is, so the
+            // bound above holds a fortiori), and the distance from the same exact product.  With fp16 inputs each is
+            // one v_fma_mix_f32, which converts its operand on the way in.
+            const float t = fmaf(x[j], recip, kShift);
+            off = fmaxf(off, fabsf(fmaf(x[j], recip, kShift - t)));
             b[j] = __float_as_uint(t);
         }
         if (off > 0.5f - 1e-4f) {

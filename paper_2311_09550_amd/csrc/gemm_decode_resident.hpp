@@ -379,9 +379,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             if (m < p.M) {  // uniform
-                float pm = 0.f;
-                for (int c = tid; c < chunks_row; c += T) pm = absmax8(*(const v4u *)(x16 + m * p.x16_lds_pitch + c * 16), pm);
-                pm = wave_max_nonneg(pm);
+                unsigned pm2 = 0u;
+                for (int c = tid; c < chunks_row; c += T) pm2 = absmax8_packed(*(const v4u *)(x16 + m * p.x16_lds_pitch + c * 16), pm2);
+                const float pm = wave_max_nonneg(absmax_packed_value(pm2));
                 if (lane == 0) amax_lds[wave * 4 + m] = pm;
             }
         }

@@ -72,16 +72,16 @@ __global__ __launch_bounds__(THREADS, THREADS <= 256 ? 8 : 1) void quantize_act_
     const v4u *src = (const v4u *)(x + (size_t)m * (size_t)ldx);
 
     v4u cache[kCache];
-    float amax = 0.f;
+    unsigned amax2 = 0u;
 #pragma unroll
     for (int i = 0; i < kCache; ++i) {
         const int c = threadIdx.x + i * kRowThreads;
         cache[i] = v4u{0, 0, 0, 0};
         if (c < chunks) cache[i] = __builtin_nontemporal_load(src + c);
-        amax = absmax8(cache[i], amax);
+        amax2 = absmax8_packed(cache[i], amax2);
     }
-    for (int c = threadIdx.x + kCache * kRowThreads; c < chunks; c += kRowThreads) amax = absmax8(src[c], amax);
-    amax = block_max<kRowThreads, true>(amax, scratch);
+    for (int c = threadIdx.x + kCache * kRowThreads; c < chunks; c += kRowThreads) amax2 = absmax8_packed(src[c], amax2);
+    float amax = block_max<kRowThreads, true>(absmax_packed_value(amax2), scratch);
 
     const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
     if (threadIdx.x == 0) s_a[m] = rq.scale;  // amax == 0 gives scale 0
@@ -114,9 +114,9 @@ __global__ __launch_bounds__(kRowThreads, 8) void quantize_weights_kernel(const 
     const int chunks = K >> 3;
     const v4u *src = (const v4u *)(w + (size_t)n * K);
 
-    float amax = 0.f;
-    for (int c = threadIdx.x; c < chunks; c += kRowThreads) amax = absmax8(src[c], amax);
-    amax = block_max<kRowThreads, true>(amax, scratch);
+    unsigned amax2 = 0u;
+    for (int c = threadIdx.x; c < chunks; c += kRowThreads) amax2 = absmax8_packed(src[c], amax2);
+    float amax = block_max<kRowThreads, true>(absmax_packed_value(amax2), scratch);
 
     const RowQuantizer rq(amax, 7.0f, -8.f, 7.f);
     if (threadIdx.x == 0) s_w[n] = rq.scale;
@@ -214,17 +214,17 @@ __global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const 
     const v4u *up = (const v4u *)(gate_up + (size_t)m * 2 * I + I);
 
     v4u cache[kFusedCache];
-    float amax = 0.f;
+    unsigned amax2 = 0u;
 #pragma unroll
     for (int i = 0; i < kFusedCache; ++i) {
         const int c = threadIdx.x + i * kFusedThreads;
         cache[i] = v4u{0, 0, 0, 0};
         if (c < chunks) cache[i] = silu_mul8(gate[c], up[c]);
-        amax = absmax8(cache[i], amax);
+        amax2 = absmax8_packed(cache[i], amax2);
     }
     for (int c = threadIdx.x + kFusedCache * kFusedThreads; c < chunks; c += kFusedThreads)
-        amax = absmax8(silu_mul8(gate[c], up[c]), amax);
-    amax = block_max<kFusedThreads, true>(amax, scratch);
+        amax2 = absmax8_packed(silu_mul8(gate[c], up[c]), amax2);
+    const float amax = block_max<kFusedThreads, true>(absmax_packed_value(amax2), scratch);
 
     const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
     if (threadIdx.x == 0) s_a[m] = rq.scale;
