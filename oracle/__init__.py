@@ -245,6 +245,25 @@ def quantize_weights_rtn8(w_half):
     return wq, s_w
 
 
+def add_rmsnorm(x_half, res_half, gamma_half, eps):
+    """fp16 [M][K] x, fp16 [M][K] residual or None, fp16 [K] gain, eps -> (r float16 [M][K], y64 float64 [M][K],
+    y float16 [M][K]): r = fp16(res + x), y = r / sqrt(mean r^2 + eps) * gain (see the C source)."""
+    def bits(a):
+        a = np.ascontiguousarray(a)
+        return _c(a.view(np.uint16) if a.dtype == np.float16 else a, np.uint16)
+    x = bits(x_half)
+    M, K = x.shape
+    res = None if res_half is None else bits(res_half)
+    g = bits(gamma_half)
+    if g.shape != (K,) or (res is not None and res.shape != (M, K)):
+        raise ValueError("shape mismatch")
+    r = np.empty((M, K), np.uint16)
+    y64 = np.empty((M, K), np.float64)
+    y = np.empty((M, K), np.uint16)
+    _load().oracle_add_rmsnorm(_p(x), None if res is None else _p(res), _p(g), ctypes.c_double(eps), _p(r), _p(y64), _p(y), M, K)
+    return r.view(np.float16), y64, y.view(np.float16)
+
+
 def silu_mul(gate_up_half):
     """fp16 [M][2I] -> (y64 float64 [M][I], h float16 [M][I])."""
     g = np.ascontiguousarray(gate_up_half)

@@ -39,6 +39,8 @@ int oracle_quantize_weights_groups(const uint16_t *w_half, int group, int8_t *wq
 int oracle_gemm_fine_grained(const int8_t *xq, const float *s_a, const uint8_t *wp, const float *s_g, int group,
                              double *y64, float *y32, uint16_t *out_half, double *mag, int M, int N, int K);
 void oracle_silu_mul(const uint16_t *gate_up_half, double *y64, uint16_t *h_half, int M, int I);
+void oracle_add_rmsnorm(const uint16_t *x_half, const uint16_t *res_half, const uint16_t *gamma_half, double eps,
+                        uint16_t *r_half, double *y64, uint16_t *y_half, int M, int K);
 int oracle_num_threads(void);
 
 static int failures;
@@ -190,6 +192,19 @@ int main(void)
         oracle_silu_mul(gu, NULL, NULL, M, I);
         for (int i = 0; i < M * I; ++i) CHECK(isfinite(y[i]), "silu(gate) * up is not finite");
         free(gu); free(h); free(y);
+    }
+    {
+        const int M = 3, K = 37;
+        uint16_t *x = (uint16_t *)block((size_t)M * K * 2), *res = (uint16_t *)block((size_t)M * K * 2);
+        uint16_t *g = (uint16_t *)block((size_t)K * 2), *r = (uint16_t *)block((size_t)M * K * 2), *yh = (uint16_t *)block((size_t)M * K * 2);
+        double *y = (double *)block((size_t)M * K * 8);
+        fill_half(x, (size_t)M * K, 2);
+        fill_half(res, (size_t)M * K, 3);
+        fill_half(g, (size_t)K, 4);
+        oracle_add_rmsnorm(x, res, g, 1e-5, r, y, yh, M, K);
+        oracle_add_rmsnorm(x, NULL, g, 1e-5, r, NULL, NULL, M, K);
+        for (int i = 0; i < M * K; ++i) CHECK(isfinite(y[i]), "RMSNorm value is not finite");
+        free(x); free(res); free(g); free(r); free(yh); free(y);
     }
     CHECK(oracle_num_threads() >= 1, "thread count below one");
     if (failures) { fprintf(stderr, "oracle selftest: %d check(s) failed\n", failures); return 1; }

@@ -455,6 +455,36 @@ void oracle_silu_mul(const uint16_t *gate_up_half, double *y64, uint16_t *h_half
     }
 }
 
+/* The operator in front of a gated MLP's first linear in a pre-norm decoder layer, whose output the per-token
+ * quantiser consumes (the engine of Sec. 6.1 fuses the quantiser into such neighbours; the norm itself is LLaMA's
+ * RMSNorm, not the paper's):
+ *   r[m][k] = fp16( fp32(res[m][k]) + fp32(x[m][k]) )         one fp32 addition, one rounding to fp16; r = x if res is NULL
+ *   y[m][k] = r[m][k] / sqrt( mean_k r[m][k]^2 + eps ) * g[k]
+ * evaluated in fp64 from the fp16 values r and g; y64 gets the fp64 value, y_half that value rounded once to fp16. */
+void oracle_add_rmsnorm(const uint16_t *x_half, const uint16_t *res_half, const uint16_t *gamma_half, double eps,
+                        uint16_t *r_half, double *y64, uint16_t *y_half, int M, int K)
+{
+    for (int m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int k = 0; k < K; ++k) {
+            uint16_t rb = x_half[(size_t)m * K + k];
+            if (res_half) {
+                float sum = (float)half_bits_to_double(res_half[(size_t)m * K + k]) + (float)half_bits_to_double(rb);
+                rb = double_to_half_bits((double)sum);
+            }
+            r_half[(size_t)m * K + k] = rb;
+            double r = half_bits_to_double(rb);
+            ss += r * r;
+        }
+        double inv = 1.0 / sqrt(ss / (double)K + eps);
+        for (int k = 0; k < K; ++k) {
+            double y = half_bits_to_double(r_half[(size_t)m * K + k]) * inv * half_bits_to_double(gamma_half[k]);
+            if (y64) y64[(size_t)m * K + k] = y;
+            if (y_half) y_half[(size_t)m * K + k] = double_to_half_bits(y);
+        }
+    }
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 #endif
