@@ -94,7 +94,7 @@ def parse_args():
     ap.add_argument("--no-large-m", action="store_true", help="skip the 13B GEMMs at M = 2048 and 4096")
     ap.add_argument("--no-row-major", action="store_true", help="skip the row-major entry (w4a8_gemm over Wp)")
     ap.add_argument("--only", default="", help="comma-separated sections to run besides the timed step "
-                    "(decode, layer_stack, 7b, 70b, large_m, row_major, achievable, medium_m, table5, w8a8, cpu); empty = all")
+                    "(decode, layer_stack, 7b, 70b, large_m, row_major, achievable, medium_m, rowwise, table5, w8a8, cpu); empty = all")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-swiglu-epilogue", action="store_true",
@@ -524,6 +524,28 @@ def time_achievable(torch, w4a8):
     return out
 
 
+def time_rowwise(torch, w4a8, synth, Ms=(1, 16, 1024), K=5120):
+    """The row-wise kernels in front of a linear, replayed back to back from a HIP graph (1.4 us of every figure is the
+    gap between kernels): the per-token quantiser alone and fused behind residual addition + RMSNorm, with the bytes
+    each moves (quantiser: 2 K in, K out per token; fused: x and the residual in, the new residual and the codes out)."""
+    rows = []
+    gamma = torch.ones((K,), dtype=torch.float16, device="cuda")
+    for M in Ms:
+        x = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=6)).cuda()
+        res = torch.from_numpy(synth.activations_fp16(M, K, config_id=3, tag=7)).cuda()
+        r = torch.empty_like(x)
+        xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+        s_a = torch.empty((M,), dtype=torch.float32, device="cuda")
+        quant = w4a8.bound_call("w4a8_quantize_act", x, xq, s_a, M, K)
+        import ctypes
+        fused = w4a8.bound_call("w4a8_add_rmsnorm_quantize", x, res, gamma, ctypes.c_float(1e-5), r, None, xq, s_a, M, K)
+        t_q = graph_time_us(torch, lambda i: quant(), 16, 6)
+        t_f = graph_time_us(torch, lambda i: fused(), 16, 6)
+        rows.append({"M": M, "K": K, "quantize_act_us": round(t_q, 2), "quantize_act_GBps": round(3 * M * K / t_q / 1e3, 1),
+                     "add_rmsnorm_quantize_us": round(t_f, 2), "add_rmsnorm_quantize_GBps": round(7 * M * K / t_f / 1e3, 1)})
+    return rows
+
+
 def time_medium_m(torch, w4a8, synth, model="13b", Ms=(32, 64, 128, 256, 512), iters=4):
     """Between token generation and context decoding: the four linears at M = 32 .. 512 from cold weights (rotating
     copies as in time_decode), through the one-copy entry with its K slices.  Each row is set against the larger of
@@ -826,6 +848,8 @@ def main():
                 sum(r["frac_of_stream_read"] for r in result["decode"]) / len(result["decode"]), 4)
     if wanted("medium_m", args.no_medium_m):
         result["medium_m"] = time_medium_m(torch, w4a8, synth)
+    if wanted("rowwise", False):
+        result["rowwise"] = time_rowwise(torch, w4a8, synth)
     if wanted("table5", args.no_table5):
         result["paper_table5_shapes"] = time_paper_table5(torch, w4a8, synth)
     if wanted("w8a8", args.no_w8a8):

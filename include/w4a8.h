@@ -323,6 +323,25 @@ int w4a8_silu_mul(const void *gate_up_fp16, void *h_fp16, int M, int I, void *st
 int w4a8_silu_mul_quantize(const void *gate_up_fp16, int8_t *xq, float *s_a, int M, int I, void *stream);
 
 /*
+ * The per-token quantiser fused behind the residual addition and the RMSNorm of a pre-norm decoder layer (Sec. 6.1:
+ * the engine folds the quantiser into the operator in front of each linear; the norm is LLaMA's, not the paper's):
+ *   r[m][k] = fp16( fp32(res[m][k]) + fp32(x[m][k]) )                     r = x when res_fp16 is NULL
+ *   y[m][k] = fp16( fp32(r[m][k]) * rsqrt( mean_k r[m][k]^2 + eps ) * fp32(gamma[k]) )
+ *   (xq, s_a) = w4a8_quantize_act(y)                                      Eq. (2), z = 0, per token
+ * in one pass over the row: the mean of squares is an fp32 sum, the reciprocal square root a correctly rounded square
+ * root and division, the products are taken in the order written.  xq and s_a are, bit for bit, what
+ * w4a8_quantize_act gives on the y this call computes; r is exactly defined; y is within an fp16 rounding of the
+ * real-number formula.
+ *   x_fp16 [M][K] in;  res_fp16 [M][K] in or NULL;  gamma_fp16 [K] in;  eps >= 0 (W4A8_ERR_ARG otherwise; an all-zero
+ *   row needs eps > 0);  r_out_fp16 [M][K] out or NULL (the residual stream that goes on);  y_out_fp16 [M][K] out or
+ *   NULL (for inspection: no later step of the path reads it);  xq [M][K] int8 out;  s_a [M] out.
+ *   K follows the K contract.  r_out_fp16 may be the same buffer as res_fp16 or x_fp16 (the residual stream updated in
+ *   place: every element is read before it is written, by the same thread); no other buffers may overlap.
+ */
+int w4a8_add_rmsnorm_quantize(const void *x_fp16, const void *res_fp16, const void *gamma_fp16, float eps,
+                              void *r_out_fp16, void *y_out_fp16, int8_t *xq, float *s_a, int M, int K, void *stream);
+
+/*
  * Host-side packing of already quantised weights (App. A.1; no GPU needed).
  *   wq_host [N][K] int8 codes in [-8,7]  ->  wp_host [N][K/2].
  * Returns W4A8_ERR_VALUE if a code is out of range, W4A8_ERR_SHAPE if K is odd.

@@ -78,6 +78,8 @@ def lib():
         L.w4a8_gemm_tiled_swiglu.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp]
         L.w4a8_linear_tiled_fp16.restype = i
         L.w4a8_linear_tiled_fp16.argtypes = [vp, ctypes.c_longlong, vp, vp, vp, vp, i, i, i, vp]
+        L.w4a8_add_rmsnorm_quantize.restype = i
+        L.w4a8_add_rmsnorm_quantize.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i, i, vp]
         L.w4a8_linear_tiled_swiglu_fp16.restype = i
         L.w4a8_linear_tiled_swiglu_fp16.argtypes = [vp, ctypes.c_longlong, vp, vp, vp, vp, i, i, i, vp]
         L.w4a8_init.restype = i
@@ -468,6 +470,25 @@ def w4a8_linear_tiled_fp16(x, wt, s_w, out=None, s_a_out=None):
                                         None if s_a_out is None else _dev(s_a_out, torch.float32, "s_a_out"), M, N, K,
                                         _stream()))
     return out
+
+
+def w4a8_add_rmsnorm_quantize(x, res, gamma, eps: float, r_out=None, y_out=None, xq=None, s_a=None):
+    """fp16 [M][K] x, fp16 [M][K] residual or None, fp16 [K] gain -> (xq int8 [M][K], s_a fp32 [M]) of
+    y = rmsnorm(res + x) * gamma, in one launch; r_out / y_out (fp16 [M][K] or None) receive res + x and y."""
+    torch = _torch()
+    M, K = x.shape
+    for name, t, shape in (("res", res, (M, K)), ("gamma", gamma, (K,)), ("r_out", r_out, (M, K)), ("y_out", y_out, (M, K))):
+        if t is not None and tuple(t.shape) != shape:
+            raise ValueError(f"{name} shape mismatch")
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device) if xq is None else xq
+    s_a = torch.empty((M,), dtype=torch.float32, device=x.device) if s_a is None else s_a
+    if tuple(xq.shape) != (M, K) or tuple(s_a.shape) != (M,):
+        raise ValueError("xq / s_a shape mismatch")
+    opt = lambda t, name: None if t is None else _dev(t, torch.float16, name)
+    _check(lib().w4a8_add_rmsnorm_quantize(_dev(x, torch.float16, "x"), opt(res, "res"), _dev(gamma, torch.float16, "gamma"),
+                                           float(eps), opt(r_out, "r_out"), opt(y_out, "y_out"), _dev(xq, torch.int8, "xq"),
+                                           _dev(s_a, torch.float32, "s_a"), M, K, _stream()))
+    return xq, s_a
 
 
 def w4a8_linear_tiled_swiglu_fp16(x, wt_gu, s_w_gu, h=None, s_a_out=None):

@@ -832,6 +832,18 @@ int w4a8_silu_mul_quantize(const void *gate_up_fp16, int8_t *xq, float *s_a, int
 
 // ---- probes of what the chip sustains (context for the measurements, no part of the path)
 
+int w4a8_add_rmsnorm_quantize(const void *x_fp16, const void *res_fp16, const void *gamma_fp16, float eps, void *r_out_fp16,
+                              void *y_out_fp16, int8_t *xq, float *s_a, int M, int K, void *stream) {
+    if (!x_fp16 || !gamma_fp16 || !xq || !s_a) return W4A8_ERR_NULL;
+    if (int e = check_gemm_shape(M, 1, K)) return e;
+    if (!(eps >= 0.0f) || !(eps < 3.0e38f)) return W4A8_ERR_ARG;  // also refuses NaN
+    if (misaligned(x_fp16) || misaligned(res_fp16) || misaligned(gamma_fp16) || misaligned(r_out_fp16) || misaligned(y_out_fp16) ||
+        misaligned(xq))
+        return W4A8_ERR_ALIGN;
+    return launched(launch_add_rmsnorm_quantize(x_fp16, res_fp16, gamma_fp16, eps, r_out_fp16, y_out_fp16, xq, s_a, M, K,
+                                                static_cast<hipStream_t>(stream)));
+}
+
 int w4a8_probe_stream_read(const void *buf, size_t bytes, void *sink, void *stream) {
     if (!buf || !sink) return W4A8_ERR_NULL;
     if (bytes < 16) return W4A8_ERR_SHAPE;

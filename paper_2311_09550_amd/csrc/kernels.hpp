@@ -183,5 +183,7 @@ hipError_t launch_probe_read_pattern(const void *src, size_t bytes, unsigned *si
                                      hipStream_t stream);
 hipError_t launch_probe_mfma_i8(int *sink, int workgroups, int iters, int pattern, hipStream_t stream);
 hipError_t launch_silu_mul_quantize(const void *gate_up, int8_t *xq, float *s_a, int M, int I, hipStream_t stream);
+hipError_t launch_add_rmsnorm_quantize(const void *x, const void *res, const void *gamma, float eps, void *r_out, void *y_out,
+                                       int8_t *xq, float *s_a, int M, int K, hipStream_t stream);
 
 }  // namespace w4a8

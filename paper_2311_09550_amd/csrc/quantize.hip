@@ -249,6 +249,129 @@ __global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const 
         emit(c, silu_mul8(gate[c], up[c]));
 }
 
+// Residual add, RMSNorm and the per-token quantiser in one pass over a row (the quantiser fused into the operator in
+// front of it, Sec. 6.1; the norm is LLaMA's):
+//   r = fp16(fp32(res) + fp32(x))  (r = x without a residual),  y = fp16(fp32(r) * rsqrt(mean r^2 + eps) * fp32(g)),
+//   (xq, s_a) = the per-token quantiser of quantize_act_kernel applied to y.
+// The mean of squares is an fp32 sum (per thread, then over the workgroup), the reciprocal square root a correctly
+// rounded square root and division.  r and y are written where the caller wants them (the residual stream goes on; y
+// is for inspection), otherwise the only traffic is x, res, g in and the codes out.  A thread keeps its chunks of the
+// row in registers (K <= 16384); longer rows take what is beyond from r as written, or from the inputs again, with the
+// same bits.  THREADS x CACHE as for the quantiser: 1024 x 2 for a few rows, 256 x 8 where the rows fill the chip.
+
+__device__ __forceinline__ v4u add_halves8(v4u a, v4u b) {
+    v4u o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = pack_f16x2(lo_half(a[j]) + lo_half(b[j]), hi_half(a[j]) + hi_half(b[j]));
+    return o;
+}
+
+template <int kNormThreads, int kNormCache>
+__global__ __launch_bounds__(kNormThreads) void add_rmsnorm_quantize_kernel(const uint16_t *x, const uint16_t *res,
+                                                                          const uint16_t *__restrict__ gamma, float eps,
+                                                                          uint16_t *r_out, uint16_t *__restrict__ y_out,
+                                                                          int8_t *__restrict__ xq, float *__restrict__ s_a,
+                                                                          int K) {
+    __shared__ float scratch[kNormThreads / 64];
+    __shared__ float scratch_sum[kNormThreads / 64];
+    const int m = blockIdx.x;
+    const int chunks = K >> 3;
+    const v4u *xs = (const v4u *)(x + (size_t)m * K);
+    const v4u *rs = res ? (const v4u *)(res + (size_t)m * K) : nullptr;
+    const v4u *gs = (const v4u *)gamma;
+    auto r_chunk = [&](int c) { return rs ? add_halves8(rs[c], xs[c]) : xs[c]; };
+    // what the later passes take for a chunk beyond the registers: r as written (r_out may be x or res themselves, which
+    // this thread has then overwritten), else the same sum again
+    auto r_again = [&](int c) { return r_out ? ((const v4u *)(r_out + (size_t)m * K))[c] : r_chunk(c); };
+
+    v4u cache[kNormCache];
+    float ss = 0.f;
+    auto add_squares = [&](v4u r) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float a = lo_half(r[j]), b = hi_half(r[j]);
+            ss += a * a;
+            ss += b * b;
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < kNormCache; ++i) {
+        const int c = threadIdx.x + i * kNormThreads;
+        cache[i] = v4u{0, 0, 0, 0};
+        if (c < chunks) {
+            cache[i] = r_chunk(c);
+            if (r_out) ((v4u *)(r_out + (size_t)m * K))[c] = cache[i];
+        }
+        add_squares(cache[i]);
+    }
+    for (int c = threadIdx.x + kNormCache * kNormThreads; c < chunks; c += kNormThreads) {
+        const v4u r = r_chunk(c);
+        if (r_out) ((v4u *)(r_out + (size_t)m * K))[c] = r;
+        add_squares(r);
+    }
+    // sum over the workgroup: a butterfly inside the wave, the waves' sums in wave order
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((threadIdx.x & 63) == 0) scratch_sum[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float total = 0.f;
+#pragma unroll
+    for (int w = 0; w < kNormThreads / 64; ++w) total += scratch_sum[w];
+    const float inv = __fdiv_rn(1.0f, __fsqrt_rn(__fdiv_rn(total, (float)K) + eps));
+
+    auto y_chunk = [&](int c, v4u r) {
+        const v4u g = gs[c];
+        v4u o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            o[j] = pack_f16x2(lo_half(r[j]) * inv * lo_half(g[j]), hi_half(r[j]) * inv * hi_half(g[j]));
+        return o;
+    };
+    unsigned amax2 = 0u;
+#pragma unroll
+    for (int i = 0; i < kNormCache; ++i) {
+        const int c = threadIdx.x + i * kNormThreads;
+        if (c < chunks) cache[i] = y_chunk(c, cache[i]);  // from here on the cache holds y
+        amax2 = absmax8_packed(cache[i], amax2);
+    }
+    for (int c = threadIdx.x + kNormCache * kNormThreads; c < chunks; c += kNormThreads)
+        amax2 = absmax8_packed(y_chunk(c, r_again(c)), amax2);
+    const float amax = block_max<kNormThreads, true>(absmax_packed_value(amax2), scratch);
+
+    const RowQuantizer rq(amax, 127.0f, -127.f, 127.f);
+    if (threadIdx.x == 0) s_a[m] = rq.scale;
+    const bool zero_row = amax == 0.f;
+    v2u *dst = (v2u *)(xq + (size_t)m * K);
+    auto emit = [&](int c, v4u y) {
+        if (y_out) ((v4u *)(y_out + (size_t)m * K))[c] = y;
+        v2u o = v2u{0, 0};
+        if (!zero_row) {
+            float yf[8];
+            halves8(y, yf);
+            o = rq.packed8_own_max(yf);
+        }
+        dst[c] = o;
+    };
+#pragma unroll
+    for (int i = 0; i < kNormCache; ++i) {
+        const int c = threadIdx.x + i * kNormThreads;
+        if (c < chunks) emit(c, cache[i]);
+    }
+    for (int c = threadIdx.x + kNormCache * kNormThreads; c < chunks; c += kNormThreads) emit(c, y_chunk(c, r_again(c)));
+}
+
+hipError_t launch_add_rmsnorm_quantize(const void *x, const void *res, const void *gamma, float eps, void *r_out, void *y_out,
+                                       int8_t *xq, float *s_a, int M, int K, hipStream_t stream) {
+    if (M <= kFewRows)
+        hipLaunchKernelGGL((add_rmsnorm_quantize_kernel<1024, 2>), dim3(M), dim3(1024), 0, stream, (const uint16_t *)x,
+                           (const uint16_t *)res, (const uint16_t *)gamma, eps, (uint16_t *)r_out, (uint16_t *)y_out, xq, s_a, K);
+    else
+        hipLaunchKernelGGL((add_rmsnorm_quantize_kernel<kRowThreads, kCache>), dim3(M), dim3(kRowThreads), 0, stream,
+                           (const uint16_t *)x, (const uint16_t *)res, (const uint16_t *)gamma, eps, (uint16_t *)r_out,
+                           (uint16_t *)y_out, xq, s_a, K);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_act(const void *x, long long ldx, int8_t *xq, float *s_a, int M, int K, hipStream_t stream) {
     // up to half a row per compute unit the rows are spread over four times the threads
     if (M <= kFewRows)

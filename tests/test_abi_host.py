@@ -110,6 +110,15 @@ def test_argument_validation_happens_before_any_launch(L):
     assert f(odd, 1024, p, p, p, null, 1, 16, 1024, null) == -3
     assert f(p, 1024, p, p, p, null, 17, 16, 1024, null) == -7                  # M beyond token generation
     assert f(p, 16384, p, p, p, null, 4, 16, 16384, null) == -7                 # K beyond what a wave can hold
+    nq = L.w4a8_add_rmsnorm_quantize
+    eps = ctypes.c_float(1e-5)
+    assert nq(null, null, p, eps, null, null, p, p, 1, 64, null) == -1
+    assert nq(p, null, null, eps, null, null, p, p, 1, 64, null) == -1
+    assert nq(p, null, p, eps, null, null, p, null, 1, 64, null) == -1
+    assert nq(p, null, p, eps, null, null, p, p, 1, 40, null) == -2
+    assert nq(p, odd, p, eps, null, null, p, p, 1, 64, null) == -3
+    assert nq(p, null, p, eps, odd, null, p, p, 1, 64, null) == -3
+    assert nq(p, null, p, ctypes.c_float(-1.0), null, null, p, p, 1, 64, null) == -7
     fs = L.w4a8_linear_tiled_swiglu_fp16
     assert fs(p, 1024, p, p, null, null, 1, 32, 1024, null) == -1
     assert fs(p, 1024, p, p, p, null, 1, 40, 1024, null) == -2                  # I follows the K contract
