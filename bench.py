@@ -147,7 +147,7 @@ class LayerStack:
     # Token count up to which every linear quantises its own input (w4a8_linear_tiled_fp16 and its SiLU*up form)
     FUSE_UP_TO_M = 3
 
-    def __init__(self, torch, w4a8, synth, M, weights, model="13b", fuse=False):
+    def __init__(self, torch, w4a8, synth, M, weights, model="13b", fuse=False, prenorm=False):
         self.torch, self.w4a8, self.M = torch, w4a8, M
         self.shapes = synth.LLAMA_SHAPES[model]
         # measured, the forms timed in turn: 35.3 against 43.5 us per layer at M = 1, 39.9 against 44.8 at M = 2, 44.6
@@ -179,6 +179,16 @@ class LayerStack:
                       "o": b("w4a8_quantize_act_strided", self.out["qkv"], self.shapes["qkv"][0], self.xq_h, self.sa_h, M, H),
                       "gate_up": b("w4a8_quantize_act", self.out["o"], self.xq_h, self.sa_h, M, H),
                       "down": b("w4a8_silu_mul_quantize", self.out["gate_up"], self.xq_i, self.sa_i, M, I)}
+        if prenorm:
+            # the two quantisers that sit behind an RMSNorm in a pre-norm decoder layer take it (and, in front of the
+            # MLP, the residual addition) into their pass: same launch count, a more faithful layer
+            import ctypes
+            self.gamma = torch.ones((H,), dtype=torch.float16, device=dev)
+            self.resid = e(M, H, dt=torch.float16)
+            eps = ctypes.c_float(1e-5)
+            self.quant["qkv"] = b("w4a8_add_rmsnorm_quantize", self.h, None, self.gamma, eps, None, None, self.xq_h, self.sa_h, M, H)
+            self.quant["gate_up"] = b("w4a8_add_rmsnorm_quantize", self.out["o"], self.h, self.gamma, eps, self.resid, None,
+                                      self.xq_h, self.sa_h, M, H)
         self.gemm = {}
         for name, (N, K) in self.shapes.items():
             xq, sa = (self.xq_i, self.sa_i) if name == "down" else (self.xq_h, self.sa_h)
@@ -289,7 +299,8 @@ def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 2, 3, 16, 64, 128, 1024
     time of a second graph that holds only the four plain GEMMs (pre-quantised inputs), over the layer time.  At
     M <= 3 the layer runs with the quantisers folded into the GEMMs (4 launches), and the unfused form (8 launches)
     is timed beside it.  One layer's weights (158 MB) stay resident in the last-level cache across replays: the small-M
-    rows are a warm-cache figure, the HBM-bound figure is the `decode` list."""
+    rows are a warm-cache figure, the HBM-bound figure is the `decode` list.  `prenorm_layer_us` (eight-launch rows): the
+    same layer with the quantisers in front of QKV and gate+up fused behind RMSNorm (and the residual addition)."""
     rows = []
     for M in Ms:
         stack = LayerStack(torch, w4a8, synth, M, weights, fuse=True)
@@ -302,12 +313,20 @@ def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 2, 3, 16, 64, 128, 1024
             for _ in range(3):
                 fn()
             times[what] = graph_time_us(torch, lambda i: fn(), steps_per_graph, replays)
+        if not stack.fused:
+            pre = LayerStack(torch, w4a8, synth, M, weights, fuse=False, prenorm=True)
+            for _ in range(3):
+                pre.step()
+            times["prenorm"] = graph_time_us(torch, lambda i: pre.step(), steps_per_graph, replays)
+            del pre
         row = {"M": M, "layer_us": round(times["layer"], 2), "gemm_us": round(times["gemms"], 2),
                "gemm_share": round(times["gemms"] / times["layer"], 4),
                "TOPS": round(stack.ops_per_step() / times["layer"] / 1e6, 2),
                "launches": stack.launches_per_step, "weights": "tiled"}
         if plain is not None:
             row["unfused_layer_us"] = round(times["unfused"], 2)
+        if "prenorm" in times:
+            row["prenorm_layer_us"] = round(times["prenorm"], 2)
         rows.append(row)
         del stack, plain
         torch.cuda.empty_cache()

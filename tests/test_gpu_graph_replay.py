@@ -124,3 +124,39 @@ def test_graph_replays_of_the_swiglu_entries_match_eager(gpu, M, I, K, how):
             graph.replay()
             t.cuda.synchronize()
             assert bool((h.view(t.int16) == eager[i].view(t.int16)).all()), f"replay {rnd}.{i} of {how} M={M} differs from eager"
+
+
+@pytest.mark.parametrize("M,K", [(3, 5120), (300, 1056)])
+def test_graph_replays_of_the_fused_norm_quantiser_match_eager(gpu, M, K):
+    """w4a8_add_rmsnorm_quantize with the residual stream updated in place, captured and replayed the same way (its
+    eager results are checked against the oracle in test_gpu_rmsnorm.py)."""
+    t = gpu
+    xs = [t.from_numpy(synth.activations_fp16(M, K, config_id=92, tag=30 + i)).cuda() for i in range(3)]
+    res0 = t.from_numpy(synth.activations_fp16(M, K, config_id=92, tag=40)).cuda()
+    g = t.from_numpy(np.linspace(0.5, 1.5, K).astype(np.float16)).cuda()
+    x, res = xs[0].clone(), res0.clone()
+    xq = t.empty((M, K), dtype=t.int8, device="cuda")
+    s_a = t.empty((M,), dtype=t.float32, device="cuda")
+    eager = []
+    for xi in xs:
+        x.copy_(xi)
+        res.copy_(res0)
+        w4a8.w4a8_add_rmsnorm_quantize(x, res, g, 1e-5, r_out=res, xq=xq, s_a=s_a)
+        eager.append((xq.clone(), s_a.clone(), res.clone()))
+    t.cuda.synchronize()
+    side = t.cuda.Stream()
+    side.wait_stream(t.cuda.current_stream())
+    graph = t.cuda.CUDAGraph()
+    with t.cuda.stream(side):
+        with t.cuda.graph(graph):
+            w4a8.w4a8_add_rmsnorm_quantize(x, res, g, 1e-5, r_out=res, xq=xq, s_a=s_a)
+    t.cuda.current_stream().wait_stream(side)
+    for rnd in range(2):
+        for i, xi in enumerate(xs):
+            x.copy_(xi)
+            res.copy_(res0)
+            xq.fill_(5)
+            graph.replay()
+            t.cuda.synchronize()
+            assert bool((xq == eager[i][0]).all()) and bool((s_a.view(t.int32) == eager[i][1].view(t.int32)).all()), f"replay {rnd}.{i}"
+            assert bool((res.view(t.int16) == eager[i][2].view(t.int16)).all()), f"replay {rnd}.{i}: residual"
