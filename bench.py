@@ -74,7 +74,7 @@ def measured_traffic(key):
     entry = prof.get("kernels", {}).get(key)
     if entry is None:
         return None, "kernel not in the counter profile"
-    return entry["traffic_bytes_per_launch"], prof.get("summary", "profiles/")
+    return entry["traffic_bytes_per_launch"], entry.get("summary", "profiles/")
 
 
 def parse_args():

@@ -123,8 +123,8 @@ def cmd_traffic(a):
     h = source_hash()
     if prof.get("source_hash") != h:
         prof = {"source_hash": h, "kernels": {}}
-    prof["summary"] = a.summary
-    prof["kernels"][a.key] = {"traffic_bytes_per_launch": round(per_f + per_w), "fetch_bytes_per_launch": round(per_f),
+    prof.pop("summary", None)
+    prof["kernels"][a.key] = {"summary": a.summary, "traffic_bytes_per_launch": round(per_f + per_w), "fetch_bytes_per_launch": round(per_f),
                               "write_bytes_per_launch": round(per_w), "gemm_calls": round(gemms),
                               "fetch_scale": round(fscale, 4), "write_scale": round(wscale, 4)}
     with open(TRAFFIC_FILE, "w") as f:
