@@ -152,7 +152,9 @@ class LayerStack:
         self.shapes = synth.LLAMA_SHAPES[model]
         # measured, the forms timed in turn: 35.3 against 43.5 us per layer at M = 1, 39.9 against 44.8 at M = 2, 44.6
         # against 45.4 at M = 3; at M = 4 the down projection's rows no longer fit LDS twice over
-        self.fused = bool(fuse and M <= self.FUSE_UP_TO_M)
+        # (with the norms taken into the linears, prenorm, a third token costs more than the launches save: 49.7 us
+        # against about 46 for the eight-launch form with the norm-fused quantisers)
+        self.fused = bool(fuse and M <= (2 if prenorm else self.FUSE_UP_TO_M))
         dev = "cuda"
         self.wp = {k: v[0] for k, v in weights.items()}
         self.s_w = {k: v[1] for k, v in weights.items()}
@@ -206,6 +208,15 @@ class LayerStack:
                                    M, self.shapes[name][0], self.shapes[name][1]) for name, (x, ldx) in src.items()}
             self.linear["gate_up"] = b("w4a8_linear_tiled_swiglu_fp16", self.out["o"], H, self.wp["gate_up_interleaved"],
                                        self.s_w["gate_up_interleaved"], self.hmid, None, M, I, self.shapes["gate_up"][1])
+            if prenorm:
+                # the two linears behind a norm take it, and the residual addition in front of the MLP, into their launch
+                import ctypes
+                eps = ctypes.c_float(1e-5)
+                self.linear["qkv"] = b("w4a8_linear_tiled_norm_fp16", self.h, H, None, 0, self.gamma, eps, None, None,
+                                       self.wp["qkv"], self.s_w["qkv"], self.out["qkv"], None, M, self.shapes["qkv"][0], H, 0)
+                self.linear["gate_up"] = b("w4a8_linear_tiled_norm_fp16", self.out["o"], H, self.h, H, self.gamma, eps,
+                                           self.resid, None, self.wp["gate_up_interleaved"], self.s_w["gate_up_interleaved"],
+                                           self.hmid, None, M, 2 * I, H, 1)
         self.launches_per_step = 4 if self.fused else 8
 
     def _gemm(self, name, record=False):
@@ -299,8 +310,9 @@ def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 2, 3, 16, 64, 128, 1024
     time of a second graph that holds only the four plain GEMMs (pre-quantised inputs), over the layer time.  At
     M <= 3 the layer runs with the quantisers folded into the GEMMs (4 launches), and the unfused form (8 launches)
     is timed beside it.  One layer's weights (158 MB) stay resident in the last-level cache across replays: the small-M
-    rows are a warm-cache figure, the HBM-bound figure is the `decode` list.  `prenorm_layer_us` (eight-launch rows): the
-    same layer with the quantisers in front of QKV and gate+up fused behind RMSNorm (and the residual addition)."""
+    rows are a warm-cache figure, the HBM-bound figure is the `decode` list.  `prenorm_layer_us`: the same layer with an
+    RMSNorm in front of QKV and the residual addition + RMSNorm in front of gate+up, as in a pre-norm decoder layer, taken
+    into the quantisers (eight-launch rows) or into the self-quantising linears (four-launch rows): same launch counts."""
     rows = []
     for M in Ms:
         stack = LayerStack(torch, w4a8, synth, M, weights, fuse=True)
@@ -313,12 +325,11 @@ def time_layer_stack(torch, w4a8, synth, weights, Ms=(1, 2, 3, 16, 64, 128, 1024
             for _ in range(3):
                 fn()
             times[what] = graph_time_us(torch, lambda i: fn(), steps_per_graph, replays)
-        if not stack.fused:
-            pre = LayerStack(torch, w4a8, synth, M, weights, fuse=False, prenorm=True)
-            for _ in range(3):
-                pre.step()
-            times["prenorm"] = graph_time_us(torch, lambda i: pre.step(), steps_per_graph, replays)
-            del pre
+        pre = LayerStack(torch, w4a8, synth, M, weights, fuse=stack.fused, prenorm=True)
+        for _ in range(3):
+            pre.step()
+        times["prenorm"] = graph_time_us(torch, lambda i: pre.step(), steps_per_graph, replays)
+        del pre
         row = {"M": M, "layer_us": round(times["layer"], 2), "gemm_us": round(times["gemms"], 2),
                "gemm_share": round(times["gemms"] / times["layer"], 4),
                "TOPS": round(stack.ops_per_step() / times["layer"] / 1e6, 2),

@@ -228,6 +228,26 @@ int w4a8_linear_tiled_swiglu_fp16(const void *x_fp16, long long ldx, const uint8
                                   float *s_a_out, int M, int I, int K, void *stream);
 
 /*
+ * The two entries above with the residual addition and the RMSNorm of w4a8_add_rmsnorm_quantize in front of the
+ * quantiser: from the residual stream of a pre-norm decoder layer to the output of the linear behind the norm (QKV, or
+ * gate / up with SiLU * up) in one launch at token-generation sizes (Sec. 6.1 taken one operator further).
+ *   r = fp16(res + x) (r = x when res_fp16 is NULL),  y = fp16(r * rsqrt(mean r^2 + eps) * gamma),
+ *   out = w4a8_linear_tiled_fp16(y, ...)          (swiglu = 0; out_fp16 [M][N])
+ *   out = w4a8_linear_tiled_swiglu_fp16(y, ...)   (swiglu = 1; wt, s_w hold N = 2 I interleaved channels, out_fp16 = h [M][N / 2])
+ * Every element of r and y is computed with the arithmetic of w4a8_add_rmsnorm_quantize (y may differ from that
+ * entry's by an fp16 rounding, since the fp32 sum of squares is taken in another order); the output is, bit for bit,
+ * what the entry named above gives on this call's y, which y_out_fp16 hands out for checking.
+ *   x_fp16 [M] rows ldx apart, res_fp16 [M] rows ldres apart or NULL (ld >= K, ld % 8 == 0), gamma_fp16 [K], eps >= 0   in
+ *   r_out_fp16 [M][K] dense or NULL, y_out_fp16 [M][K] dense or NULL (both written by one workgroup)                   out
+ *   r_out_fp16 and y_out_fp16 must not overlap any input: other workgroups are still reading those.
+ *   M <= 4, K <= 8192, and the rows must fit in LDS three times over (about M * K <= 28000); W4A8_ERR_ARG otherwise.
+ */
+int w4a8_linear_tiled_norm_fp16(const void *x_fp16, long long ldx, const void *res_fp16, long long ldres,
+                                const void *gamma_fp16, float eps, void *r_out_fp16, void *y_out_fp16, const uint8_t *wt,
+                                const float *s_w, void *out_fp16, float *s_a_out, int M, int N, int K, int swiglu,
+                                void *stream);
+
+/*
  * w4a8_gemm_tiled_splitk for callers that cannot allocate device memory and have no workspace to pass: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
  * same kernels, same output bits.  The slabs of the K slices live in a scratch array inside the library instead:

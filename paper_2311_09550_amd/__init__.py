@@ -78,6 +78,9 @@ def lib():
         L.w4a8_gemm_tiled_swiglu.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp]
         L.w4a8_linear_tiled_fp16.restype = i
         L.w4a8_linear_tiled_fp16.argtypes = [vp, ctypes.c_longlong, vp, vp, vp, vp, i, i, i, vp]
+        L.w4a8_linear_tiled_norm_fp16.restype = i
+        L.w4a8_linear_tiled_norm_fp16.argtypes = [vp, ctypes.c_longlong, vp, ctypes.c_longlong, vp, ctypes.c_float, vp, vp, vp, vp,
+                                                  vp, vp, i, i, i, i, vp]
         L.w4a8_add_rmsnorm_quantize.restype = i
         L.w4a8_add_rmsnorm_quantize.argtypes = [vp, vp, vp, ctypes.c_float, vp, vp, vp, vp, i, i, vp]
         L.w4a8_linear_tiled_swiglu_fp16.restype = i
@@ -489,6 +492,40 @@ def w4a8_add_rmsnorm_quantize(x, res, gamma, eps: float, r_out=None, y_out=None,
                                            float(eps), opt(r_out, "r_out"), opt(y_out, "y_out"), _dev(xq, torch.int8, "xq"),
                                            _dev(s_a, torch.float32, "s_a"), M, K, _stream()))
     return xq, s_a
+
+
+def w4a8_linear_tiled_norm_fp16(x, res, gamma, eps: float, wt, s_w, swiglu: bool = False, out=None, r_out=None, y_out=None,
+                                s_a_out=None):
+    """fp16 [M][K] views x and res (or None), fp16 [K] gain, tiled weights -> the linear of rmsnorm(res + x) * gamma in
+    one launch: fp16 [M][N], or h = fp16 [M][N / 2] with swiglu (interleaved gate / up channels).  r_out / y_out (dense
+    fp16 [M][K] or None) receive res + x and the normalised rows."""
+    torch = _torch()
+    M, K = x.shape
+    N = s_w.shape[0]
+    for name, t in (("x", x), ("res", res)):
+        if t is not None and not (t.is_cuda and t.dtype == torch.float16 and t.stride(1) == 1 and tuple(t.shape) == (M, K)):
+            raise TypeError(f"{name}: expected a device fp16 [M][K] view with unit column stride")
+    _on_current_device(x, "x")
+    if wt.numel() != w4a8_tiled_weight_bytes(N, K):
+        raise ValueError("tiled weight array does not match (N, K)")
+    cols = N // 2 if swiglu else N
+    out = torch.empty((M, cols), dtype=torch.float16, device=x.device) if out is None else out
+    if tuple(out.shape) != (M, cols):
+        raise ValueError("out shape mismatch")
+    for name, t in (("r_out", r_out), ("y_out", y_out)):
+        if t is not None and tuple(t.shape) != (M, K):
+            raise ValueError(f"{name} shape mismatch")
+    if s_a_out is not None and tuple(s_a_out.shape) != (M,):
+        raise ValueError("s_a_out shape mismatch")
+    opt = lambda t, dt, name: None if t is None else _dev(t, dt, name)
+    _check(lib().w4a8_linear_tiled_norm_fp16(ctypes.c_void_p(x.data_ptr()), x.stride(0),
+                                             None if res is None else ctypes.c_void_p(res.data_ptr()),
+                                             0 if res is None else res.stride(0), _dev(gamma, torch.float16, "gamma"),
+                                             float(eps), opt(r_out, torch.float16, "r_out"), opt(y_out, torch.float16, "y_out"),
+                                             _dev(wt, torch.uint8, "wt"), _dev(s_w, torch.float32, "s_w"),
+                                             _dev(out, torch.float16, "out"), opt(s_a_out, torch.float32, "s_a_out"), M, N, K,
+                                             1 if swiglu else 0, _stream()))
+    return out
 
 
 def w4a8_linear_tiled_swiglu_fp16(x, wt_gu, s_w_gu, h=None, s_a_out=None):

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libw4a8.so")
-SOURCES = ["api.hip", "gemm_decode.hip", "gemm_decode_wide.hip", "gemm_decode_swiglu.hip", "gemm_prefill.hip", "gemm_prefill_dma.hip", "gemm_prefill_tiled.hip", "probes.hip",
+SOURCES = ["api.hip", "gemm_decode.hip", "gemm_decode_wide.hip", "gemm_decode_swiglu.hip", "gemm_decode_norm.hip", "gemm_prefill.hip", "gemm_prefill_dma.hip", "gemm_prefill_tiled.hip", "probes.hip",
            "quantize.hip"]
 HEADERS = ["common.hpp", "kernels.hpp", "gemm_decode_resident.hpp", os.path.join("..", "..", "include", "w4a8.h"),
            os.path.join("..", "..", "include", "w4a8_tuning.h")]

@@ -124,6 +124,7 @@ bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool
     s.tiled = tiled;
     s.fused_quant = out->fused_quant;  // set by the caller that wants the kernel to quantise its own activations
     s.swiglu = out->swiglu;            // ... or to apply SiLU * up to interleaved gate / up channels
+    s.norm = out->norm;                // ... or to add the residual and normalise in front of its quantiser
     s.aux = aux < 0 ? 2 : aux;
     s.x_window = x_window;
     s.k_slices = k_slices < 1 ? 1 : k_slices;
@@ -672,10 +673,27 @@ int w4a8_gemm_tiled_splitk(const int8_t *xq, const float *s_a, const uint8_t *wt
     return launched(launch_splitk_epilogue(a.acc_out, pl.splits, s_a, s_w, out_fp16, M, N, st));
 }
 
+// what the norm in front of the fused quantiser needs (gamma == NULL: no norm)
+struct NormArgs {
+    const void *res;
+    long long ldres;
+    const void *gamma;
+    float eps;
+    void *r_out, *y_out;
+};
+
 // quantiser + GEMM in one launch; swiglu: N = 2 I interleaved gate / up channels, out = h
 static int linear_tiled(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16, float *s_a_out,
-                        int M, int N, int K, bool swiglu, void *stream) {
+                        int M, int N, int K, bool swiglu, void *stream, const NormArgs *norm = nullptr) {
     if (!x_fp16 || !wt || !s_w || !out_fp16) return W4A8_ERR_NULL;
+    if (norm) {
+        if (!norm->gamma) return W4A8_ERR_NULL;
+        if (!(norm->eps >= 0.0f) || !(norm->eps < 3.0e38f)) return W4A8_ERR_ARG;
+        if (norm->res && (norm->ldres < K || (norm->ldres & 7) != 0)) return W4A8_ERR_SHAPE;
+        if (misaligned(norm->res) || misaligned(norm->gamma) || misaligned(norm->r_out) || misaligned(norm->y_out)) return W4A8_ERR_ALIGN;
+        if (norm->res && ((unsigned long long)(M > 0 ? M - 1 : 0) * (unsigned long long)norm->ldres + (unsigned long long)K) * 2ull > 0xFFFF0000ull)
+            return W4A8_ERR_SHAPE;
+    }
     if (int e = check_gemm_shape(M, N, K)) return e;
     if (ldx < K || (ldx & 7) != 0) return W4A8_ERR_SHAPE;  // rows must not overlap and must start 16-byte aligned
     if (misaligned(x_fp16) || misaligned(wt) || misaligned(out_fp16) || misaligned(s_w)) return W4A8_ERR_ALIGN;
@@ -684,10 +702,11 @@ static int linear_tiled(const void *x_fp16, long long ldx, const uint8_t *wt, co
     DecodeShape shape{};
     shape.fused_quant = true;
     shape.swiglu = swiglu;
+    shape.norm = norm != nullptr;
     if (!resident_shape(M, N, K, 0, 0, 0, false, -1, true, &shape)) return W4A8_ERR_ARG;
-    // both copies of the rows (fp16 and int8, padded to the 1 KB pieces of the copy) must fit in LDS beside the slots
-    // of the partial sums
-    const long long row_bytes = ((K + 1023) / 1024) * 1024 + 16 + ((2ll * K + 1023) / 1024) * 1024;
+    // both copies of the rows (fp16 and int8, padded to the 1 KB pieces of the copy; with the norm the residual rows as
+    // well) must fit in LDS beside the slots of the partial sums
+    const long long row_bytes = ((K + 1023) / 1024) * 1024 + 16 + (norm ? 2 : 1) * ((2ll * K + 1023) / 1024) * 1024;
     if (row_bytes * M + 3 * 1024 + 2ll * shape.prefetch * shape.waves * 1024 > 160 * 1024) return W4A8_ERR_ARG;
     DecodeArgs a{};
     a.x16 = static_cast<const uint16_t *>(x_fp16);
@@ -697,7 +716,24 @@ static int linear_tiled(const void *x_fp16, long long ldx, const uint8_t *wt, co
     a.M = M; a.N = N; a.K = K;
     a.rows_per_wg = shape.rows_per_wg;
     a.chunk_rows = shape.chunk_rows;
+    if (norm) {
+        a.res16 = static_cast<const uint16_t *>(norm->res);
+        a.ldres = norm->ldres;
+        a.gamma = static_cast<const uint16_t *>(norm->gamma);
+        a.eps = norm->eps;
+        a.r_out = static_cast<uint16_t *>(norm->r_out);
+        a.y_out = static_cast<uint16_t *>(norm->y_out);
+    }
     return launched(launch_gemm_decode(a, false, shape, static_cast<hipStream_t>(stream)));
+}
+
+int w4a8_linear_tiled_norm_fp16(const void *x_fp16, long long ldx, const void *res_fp16, long long ldres, const void *gamma_fp16,
+                                float eps, void *r_out_fp16, void *y_out_fp16, const uint8_t *wt, const float *s_w, void *out_fp16,
+                                float *s_a_out, int M, int N, int K, int swiglu, void *stream) {
+    if (swiglu != 0 && swiglu != 1) return W4A8_ERR_ARG;
+    if (swiglu && ((N & 63) != 0 || N / 2 > W4A8_MAX_K)) return W4A8_ERR_SHAPE;  // N = 2 I, I follows the K contract
+    const NormArgs norm{res_fp16, ldres, gamma_fp16, eps, r_out_fp16, y_out_fp16};
+    return linear_tiled(x_fp16, ldx, wt, s_w, out_fp16, s_a_out, M, N, K, swiglu != 0, stream, &norm);
 }
 
 int w4a8_linear_tiled_fp16(const void *x_fp16, long long ldx, const uint8_t *wt, const float *s_w, void *out_fp16,

@@ -113,6 +113,35 @@ __device__ __forceinline__ float absmax_packed_value(unsigned m2) {
     return half_bits_to_float((unsigned short)max(m2 & 0xFFFFu, m2 >> 16));
 }
 
+// Pieces of the residual addition + RMSNorm in front of a quantiser, shared by the row-wise kernel and the linear that
+// takes them in, so that both apply the same arithmetic to an element: eight sums fp16(fp32(a) + fp32(b)); the fp32
+// sum of eight squares added to a running sum; eight values fp16(fp32(r) * inv * fp32(g)).
+__device__ __forceinline__ v4u add_halves8(v4u a, v4u b) {
+    v4u o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = pack_f16x2(lo_half(a[j]) + lo_half(b[j]), hi_half(a[j]) + hi_half(b[j]));
+    return o;
+}
+__device__ __forceinline__ float add_squares8(v4u r, float ss) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float a = lo_half(r[j]), b = hi_half(r[j]);
+        ss += a * a;
+        ss += b * b;
+    }
+    return ss;
+}
+__device__ __forceinline__ v4u norm_scale8(v4u r, float inv, v4u g) {
+    v4u o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = pack_f16x2(lo_half(r[j]) * inv * lo_half(g[j]), hi_half(r[j]) * inv * hi_half(g[j]));
+    return o;
+}
+// 1 / sqrt(sum / count + eps): correctly rounded division, square root and division
+__device__ __forceinline__ float rms_inverse(float sum, int count, float eps) {
+    return __fdiv_rn(1.0f, __fsqrt_rn(__fdiv_rn(sum, (float)count) + eps));
+}
+
 // Maximum over the wave of a non-negative value (as such it orders like its bit pattern), in every lane.  Six DPP steps
 // in the vector ALU: shifts within rows of 16 lanes (lanes shifted in from outside a row contribute 0), then lane 15 of
 // a row broadcast into the next row and lane 31 into the upper half; lane 63 ends up with the maximum.  A butterfly of
@@ -126,6 +155,19 @@ __device__ __forceinline__ float wave_max_nonneg(float v) {
     x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false));  // row_bcast:15 into rows 1 and 3
     x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false));  // row_bcast:31 into rows 2 and 3
     return __int_as_float(__builtin_amdgcn_readlane(x, 63));
+}
+
+// Sum over the wave, in every lane, by the same six DPP steps with additions: a prefix sum inside each row of 16 lanes
+// (lanes shifted in from outside a row contribute 0), then the rows' totals passed on; lane 63 ends up with the sum.
+// The order of the additions is fixed, so the result is the same on every run.
+__device__ __forceinline__ float wave_sum(float v) {
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x111, 0xF, 0xF, true));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x112, 0xF, 0xF, true));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xF, 0xF, true));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xF, 0xF, true));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x142, 0xA, 0xF, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x143, 0xC, 0xF, false));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // Symmetric quantisation of one row (Eq. (2) with zero point 0): code = clamp(rne(fl32(x / scale)), lo, hi).

@@ -238,6 +238,7 @@ hipError_t prepare_decode_kernels() {
     s.rows_per_wg = 16;
     if (const hipError_t e = launch_epoch(a, false, s, 1, true, nullptr); e != hipSuccess) return e;
     if (const hipError_t e = launch_gemm_decode_swiglu(a, s, 1, true, nullptr); e != hipSuccess) return e;
+    if (const hipError_t e = launch_gemm_decode_norm(a, s, true, nullptr); e != hipSuccess) return e;
     return launch_gemm_decode_wide(a, false, s, 2, true, nullptr);
 }
 
@@ -270,6 +271,7 @@ bool decode_resident_supported(int M, int N, int K, const DecodeShape &s) {
                                                : (unsigned long long)N * (unsigned long long)(K >> 1);
     if (w_bytes > 0xFFFF0000ull || (unsigned long long)M * (unsigned long long)K > 0xFFFF0000ull) return false;
     if (s.rows_per_wg < 4 || (s.rows_per_wg & 3)) return false;
+    if (s.norm) return K <= 8192 && (!s.swiglu || (N & 63) == 0) && decode_norm_supported(mt, s);
     if (s.swiglu) return (N & 63) == 0 && decode_swiglu_supported(mt, s);
     if (s.x_window) return mt <= 4 && decode_wide_supported(mt, s);
     if (mt > 2) return false;
@@ -283,6 +285,7 @@ hipError_t launch_gemm_decode(const DecodeArgs &p, bool acc_out, const DecodeSha
         if (s.k_slices > 1 && !acc_out) return hipErrorInvalidConfiguration;  // slices of K hand back raw sums
         DecodeArgs a = p;
         a.ks_per_slice = slice_steps(p.K, s);
+        if (s.norm) return acc_out ? hipErrorInvalidConfiguration : launch_gemm_decode_norm(a, s, false, stream);
         if (s.swiglu) return acc_out ? hipErrorInvalidConfiguration : launch_gemm_decode_swiglu(a, s, mt, false, stream);
         return s.x_window ? launch_gemm_decode_wide(a, acc_out, s, mt, false, stream) : launch_epoch(a, acc_out, s, mt, false, stream);
     }

@@ -143,9 +143,15 @@ __device__ __forceinline__ void wait_vmcnt_at_most() {
 // (channel 2 i = gate_i, 2 i + 1 = up_i, N = 2 I), and the epilogue stores h = silu(gate) * up, I values per token,
 // instead of the 2 I outputs (Sec. 6.1: glue operators folded into their neighbours).  The four channels an epilogue
 // item holds are two such pairs; ranges and chunks are multiples of 4 channels, so no pair is ever split.
+//
+// NORM (with FQ): the rows handed over are the residual stream's; the workgroup first forms r = fp16(res + x) and
+// y = fp16(r * rsqrt(mean r^2 + eps) * gamma) in place in its LDS copy (two passes in which every thread works on the
+// same chunks, one barrier for the sum of squares between them, the row maxima falling out of the second), and the
+// quantiser goes on from y.  The first workgroup writes r (the residual stream that goes on) and, on request, y.
 template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false, bool XW = false,
-          bool SWIGLU = false>
+          bool SWIGLU = false, bool NORM = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(DecodeArgs p) {
+    static_assert(!NORM || FQ, "the norm sits in front of the fused quantiser");
     static_assert(!FQ || (MT == 1 && !ACC_OUT), "the fused quantiser serves up to four tokens and the fp16 output");
     static_assert(!SWIGLU || (TILED && !ACC_OUT), "SiLU * up in the epilogue: tiled weights, fp16 output");
     static_assert(!XW || (TILED && !FQ), "per-wave staging: tiled weights, quantised activations");
@@ -249,19 +255,34 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
             r.w = 0x00020000;
             return r;
         }();
-        const unsigned x_base = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)(lds_ptr_t)(epoch_lds + p.x16_lds_offset));
         const int per_row = (2 * p.K + 1023) >> 10;
         const int pieces = p.M * per_row;
         const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-        int m = 0, c = wave_u;  // piece j = wave, wave + WAVES, ... is piece c of row m, kept without a division
-        for (int j = wave_u; j < pieces; j += WAVES, c += WAVES) {
-            while (c >= per_row) c -= per_row, ++m;
-            const unsigned in_row = (unsigned)(c * 1024 + lane * 16);
-            const unsigned src = in_row < 2u * (unsigned)p.K ? (unsigned)((unsigned long long)m * (unsigned long long)p.ldx * 2ull) + in_row : kNowhere;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                         :
-                         : "s"(x_base + (unsigned)(m * p.x16_lds_pitch + c * 1024)), "v"(src), "s"(x_rsrc)
-                         : "memory", "m0");
+        auto copy_rows = [&](v4i rsrc, long long ld, int lds_offset) {
+            const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)(lds_ptr_t)(epoch_lds + lds_offset));
+            int m = 0, c = wave_u;  // piece j = wave, wave + WAVES, ... is piece c of row m, kept without a division
+            for (int j = wave_u; j < pieces; j += WAVES, c += WAVES) {
+                while (c >= per_row) c -= per_row, ++m;
+                const unsigned in_row = (unsigned)(c * 1024 + lane * 16);
+                const unsigned src = in_row < 2u * (unsigned)p.K ? (unsigned)((unsigned long long)m * (unsigned long long)ld * 2ull) + in_row : kNowhere;
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                             :
+                             : "s"(base + (unsigned)(m * p.x16_lds_pitch + c * 1024)), "v"(src), "s"(rsrc)
+                             : "memory", "m0");
+            }
+        };
+        copy_rows(x_rsrc, p.ldx, p.x16_lds_offset);
+        if constexpr (NORM) {
+            if (p.res16 != nullptr) {  // uniform
+                const unsigned long long res_bytes = ((unsigned long long)(p.M - 1) * (unsigned long long)p.ldres + (unsigned long long)p.K) * 2ull;
+                const unsigned long long b = (unsigned long long)p.res16;
+                v4i rr;
+                rr.x = __builtin_amdgcn_readfirstlane((int)(unsigned)b);
+                rr.y = __builtin_amdgcn_readfirstlane((int)(unsigned)((b >> 32) & 0xFFFFu));
+                rr.z = __builtin_amdgcn_readfirstlane((int)(unsigned)res_bytes);
+                rr.w = 0x00020000;
+                copy_rows(rr, p.ldres, p.res_lds_offset);
+            }
         }
     } else if constexpr (XW) {
         // every window but the last: copy, wait, pick.  Nothing else is outstanding yet, so the wait is for the copy.
@@ -329,6 +350,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
             for (int mt = 0; mt < MT; ++mt) sa[mt] = p.s_a[min(16 * mt + r, p.M - 1)];
         }
     }
+    v4u gam[2] = {v4u{0, 0, 0, 0}, v4u{0, 0, 0, 0}};  // NORM: the gains of the chunks this thread normalises (K <= 16 threads)
+    if constexpr (NORM) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = tid + i * WAVES * 64;
+            if (c < (p.K >> 3)) gam[i] = ((const v4u *)p.gamma)[c];
+        }
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     const unsigned w_bytes = TILED ? (unsigned)((size_t)((p.N + 31) >> 5) * ks_total * kTiledBlockBytes)
@@ -372,17 +401,71 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_resident_kernel(Decode
         __builtin_amdgcn_sched_barrier(0);
         if (tid < n_sw) sw_lds[tid] = sw_first;
         lds_barrier();
-        const uint8_t *x16 = epoch_lds + p.x16_lds_offset;
+        uint8_t *x16 = epoch_lds + p.x16_lds_offset;
         uint8_t *xq_lds = epoch_lds + p.x_lds_offset;
         const int chunks_row = p.K >> 3;  // 8 fp16 = 16 bytes
         sa[0] = 0.f;
+        if constexpr (NORM) {
+            // r = res + x in place, and the rows' sums of squares; a thread's chunks are tid and tid + T in both passes
+            float *sum_lds = amax_lds + 64;
+            const uint8_t *res_l = epoch_lds + p.res_lds_offset;
+            const bool writer = blockIdx.x == 0;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            if (m < p.M) {  // uniform
-                unsigned pm2 = 0u;
-                for (int c = tid; c < chunks_row; c += T) pm2 = absmax8_packed(*(const v4u *)(x16 + m * p.x16_lds_pitch + c * 16), pm2);
-                const float pm = wave_max_nonneg(absmax_packed_value(pm2));
-                if (lane == 0) amax_lds[wave * 4 + m] = pm;
+            for (int m = 0; m < 4; ++m) {
+                if (m < p.M) {  // uniform
+                    float ss = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const int c = tid + i * T;
+                        if (c < chunks_row) {
+                            v4u *slot = (v4u *)(x16 + m * p.x16_lds_pitch + c * 16);
+                            v4u rv = *slot;
+                            if (p.res16 != nullptr) {
+                                rv = add_halves8(*(const v4u *)(res_l + m * p.x16_lds_pitch + c * 16), rv);
+                                *slot = rv;
+                            }
+                            if (writer && p.r_out != nullptr) ((v4u *)(p.r_out + (size_t)m * p.K))[c] = rv;
+                            ss = add_squares8(rv, ss);
+                        }
+                    }
+                    ss = wave_sum(ss);
+                    if (lane == 0) sum_lds[wave * 4 + m] = ss;
+                }
+            }
+            lds_barrier();
+            // y = r * rsqrt(mean r^2 + eps) * gamma in place, and the maxima of |y| on the way
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                if (m < p.M) {
+                    float total = 0.f;
+#pragma unroll
+                    for (int w = 0; w < WAVES; ++w) total += sum_lds[w * 4 + m];
+                    const float inv = rms_inverse(total, p.K, p.eps);
+                    unsigned pm2 = 0u;
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const int c = tid + i * T;
+                        if (c < chunks_row) {
+                            v4u *slot = (v4u *)(x16 + m * p.x16_lds_pitch + c * 16);
+                            const v4u y = norm_scale8(*slot, inv, gam[i]);
+                            *slot = y;
+                            if (writer && p.y_out != nullptr) ((v4u *)(p.y_out + (size_t)m * p.K))[c] = y;
+                            pm2 = absmax8_packed(y, pm2);
+                        }
+                    }
+                    const float pm = wave_max_nonneg(absmax_packed_value(pm2));
+                    if (lane == 0) amax_lds[wave * 4 + m] = pm;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                if (m < p.M) {  // uniform
+                    unsigned pm2 = 0u;
+                    for (int c = tid; c < chunks_row; c += T) pm2 = absmax8_packed(*(const v4u *)(x16 + m * p.x16_lds_pitch + c * 16), pm2);
+                    const float pm = wave_max_nonneg(absmax_packed_value(pm2));
+                    if (lane == 0) amax_lds[wave * 4 + m] = pm;
+                }
             }
         }
         lds_barrier();
@@ -571,9 +654,9 @@ constexpr bool fused_shape_exists(int xs, int waves) {
 }
 
 template <int MT, int XS, int P, int WAVES, bool ACC_OUT, bool TILED, int AUX, bool FQ = false, bool XW = false,
-          bool SWIGLU = false>
+          bool SWIGLU = false, bool NORM = false>
 static hipError_t launch_epoch_one(const DecodeArgs &p, int grid, int sets, bool prepare_only, hipStream_t stream) {
-    constexpr auto kernel = gemm_decode_resident_kernel<MT, XS, P, WAVES, ACC_OUT, TILED, AUX, FQ, XW, SWIGLU>;
+    constexpr auto kernel = gemm_decode_resident_kernel<MT, XS, P, WAVES, ACC_OUT, TILED, AUX, FQ, XW, SWIGLU, NORM>;
     static_assert(epoch_lds_bytes(MT, P, WAVES, 2) <= kCuLdsBytes, "both sets of slots must fit the compute unit's LDS");
     if (const hipError_t e = allow_lds<kernel>(kCuLdsBytes); e != hipSuccess) return e;
     if (prepare_only) return hipSuccess;
@@ -599,12 +682,15 @@ static hipError_t launch_epoch_one(const DecodeArgs &p, int grid, int sets, bool
     } else if (FQ) {
         // fused quantiser: the int8 rows and, behind them, the fp16 rows (whole 1 KB pieces) must both fit
         const long long pitch16 = ((2ll * p.K + 1023) / 1024) * 1024;
-        if (p.M > 4 || lds + (pitch + pitch16) * p.M > kCuLdsBytes) return hipErrorInvalidConfiguration;
+        const long long copies16 = NORM ? 2 : 1;  // with the norm in front the residual rows are staged too
+        if (p.M > 4 || lds + (pitch + copies16 * pitch16) * p.M > kCuLdsBytes) return hipErrorInvalidConfiguration;
+        if (NORM && (p.K >> 3) > 2 * WAVES * 64) return hipErrorInvalidConfiguration;  // two chunks a thread
         a.x_lds_pitch = (int)pitch;
         a.x_lds_offset = lds;
         a.x16_lds_pitch = (int)pitch16;
         a.x16_lds_offset = lds + (int)(pitch * p.M);
-        lds += (int)((pitch + pitch16) * p.M);
+        a.res_lds_offset = a.x16_lds_offset + (int)(pitch16 * p.M);
+        lds += (int)((pitch + copies16 * pitch16) * p.M);
     } else if (p.x_lds_pitch >= 0 && lds + pitch * p.M <= kCuLdsBytes) {
         a.x_lds_pitch = (int)pitch;
         a.x_lds_offset = lds;

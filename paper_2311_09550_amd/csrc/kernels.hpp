@@ -36,6 +36,14 @@ struct DecodeArgs {
     const uint16_t *x16; // fused-quantiser form only: fp16 activations, rows ldx elements apart (xq, s_a unused)
     long long ldx;
     float *s_a_out;      // fused-quantiser form only: where the per-token scales are also written, or NULL
+    // fused-quantiser form with the norm in front (DecodeShape::norm): y = rmsnorm(res + x) * gamma is what gets quantised
+    const uint16_t *res16;  // residual rows, ldres elements apart, or NULL (then r = x)
+    long long ldres;
+    const uint16_t *gamma;  // [K] fp16
+    float eps;
+    uint16_t *r_out;        // [M][K] dense: res + x, written by the first workgroup, or NULL
+    uint16_t *y_out;        // [M][K] dense: the normalised rows, written by the first workgroup, or NULL
+    int res_lds_offset;     // where the residual rows are staged in LDS (rows x16_lds_pitch apart)
     const int8_t *xq;    // [M][K]
     const float *s_a;    // [M]     (unused when the raw sums are requested)
     const uint8_t *wp;   // [N][K/2]
@@ -72,6 +80,7 @@ struct DecodeShape {
     bool x_window;  // resident: every wave stages its own k steps through a window of LDS (tiled weights; the only
                     // form beyond 32 tokens)
     int k_slices;   // resident: workgroups along K (0 or 1 = none); more than one only with raw sums, one slab each
+    bool norm;      // resident, with fused_quant: residual addition + RMSNorm in front of the quantiser (K <= 8192, 8 waves)
     bool swiglu;    // resident: interleaved gate / up channels, the epilogue stores h = silu(gate) * up (tiled weights,
                     // fp16 output, with the fused quantiser or with per-wave staging)
 };
@@ -89,6 +98,9 @@ hipError_t launch_gemm_decode(const DecodeArgs &p, bool acc_out, const DecodeSha
 bool decode_wide_supported(int mt, const DecodeShape &s);
 hipError_t launch_gemm_decode_wide(const DecodeArgs &p, bool acc_out, const DecodeShape &s, int mt, bool prepare_only,
                                    hipStream_t stream);
+// The instantiations with the norm in front of the fused quantiser (DecodeShape::norm, with or without swiglu): the same pair.
+bool decode_norm_supported(int mt, const DecodeShape &s);
+hipError_t launch_gemm_decode_norm(const DecodeArgs &p, const DecodeShape &s, bool prepare_only, hipStream_t stream);
 // The instantiations whose epilogue applies SiLU * up (DecodeShape::swiglu): the same pair.
 bool decode_swiglu_supported(int mt, const DecodeShape &s);
 hipError_t launch_gemm_decode_swiglu(const DecodeArgs &p, const DecodeShape &s, int mt, bool prepare_only, hipStream_t stream);

@@ -259,13 +259,6 @@ __global__ __launch_bounds__(kFusedThreads) void silu_mul_quantize_kernel(const 
 // row in registers (K <= 16384); longer rows take what is beyond from r as written, or from the inputs again, with the
 // same bits.  THREADS x CACHE as for the quantiser: 1024 x 2 for a few rows, 256 x 8 where the rows fill the chip.
 
-__device__ __forceinline__ v4u add_halves8(v4u a, v4u b) {
-    v4u o;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) o[j] = pack_f16x2(lo_half(a[j]) + lo_half(b[j]), hi_half(a[j]) + hi_half(b[j]));
-    return o;
-}
-
 template <int kNormThreads, int kNormCache>
 __global__ __launch_bounds__(kNormThreads) void add_rmsnorm_quantize_kernel(const uint16_t *x, const uint16_t *res,
                                                                           const uint16_t *__restrict__ gamma, float eps,
@@ -286,14 +279,7 @@ __global__ __launch_bounds__(kNormThreads) void add_rmsnorm_quantize_kernel(cons
 
     v4u cache[kNormCache];
     float ss = 0.f;
-    auto add_squares = [&](v4u r) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float a = lo_half(r[j]), b = hi_half(r[j]);
-            ss += a * a;
-            ss += b * b;
-        }
-    };
+    auto add_squares = [&](v4u r) { ss = add_squares8(r, ss); };
 #pragma unroll
     for (int i = 0; i < kNormCache; ++i) {
         const int c = threadIdx.x + i * kNormThreads;
@@ -309,24 +295,15 @@ __global__ __launch_bounds__(kNormThreads) void add_rmsnorm_quantize_kernel(cons
         if (r_out) ((v4u *)(r_out + (size_t)m * K))[c] = r;
         add_squares(r);
     }
-    // sum over the workgroup: a butterfly inside the wave, the waves' sums in wave order
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    // sum over the workgroup: DPP steps inside the wave, the waves' sums in wave order
+    ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) scratch_sum[threadIdx.x >> 6] = ss;
     __syncthreads();
     float total = 0.f;
 #pragma unroll
     for (int w = 0; w < kNormThreads / 64; ++w) total += scratch_sum[w];
-    const float inv = __fdiv_rn(1.0f, __fsqrt_rn(__fdiv_rn(total, (float)K) + eps));
-
-    auto y_chunk = [&](int c, v4u r) {
-        const v4u g = gs[c];
-        v4u o;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            o[j] = pack_f16x2(lo_half(r[j]) * inv * lo_half(g[j]), hi_half(r[j]) * inv * hi_half(g[j]));
-        return o;
-    };
+    const float inv = rms_inverse(total, K, eps);
+    auto y_chunk = [&](int c, v4u r) { return norm_scale8(r, inv, gs[c]); };
     unsigned amax2 = 0u;
 #pragma unroll
     for (int i = 0; i < kNormCache; ++i) {

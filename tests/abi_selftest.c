@@ -102,6 +102,9 @@ int main(void)
     EXPECT(w4a8_gemm_tiled_swiglu(p, p, p, p, odd, 4, 64, 64, NULL), W4A8_ERR_ALIGN);
     EXPECT(w4a8_linear_tiled_fp16(p, 1000, p, p, p, NULL, 1, 16, 1024, NULL), W4A8_ERR_SHAPE);
     EXPECT(w4a8_linear_tiled_fp16(p, 1024, p, p, p, NULL, 17, 16, 1024, NULL), W4A8_ERR_ARG);
+    EXPECT(w4a8_linear_tiled_norm_fp16(p, 1024, NULL, 0, NULL, 1e-5f, NULL, NULL, p, p, p, NULL, 1, 64, 1024, 0, NULL), W4A8_ERR_NULL);
+    EXPECT(w4a8_linear_tiled_norm_fp16(p, 1024, NULL, 0, p, 1e-5f, NULL, NULL, p, p, p, NULL, 5, 64, 1024, 0, NULL), W4A8_ERR_ARG);
+    EXPECT(w4a8_linear_tiled_norm_fp16(p, 1024, NULL, 0, p, 1e-5f, NULL, NULL, p, p, p, NULL, 1, 96, 1024, 1, NULL), W4A8_ERR_SHAPE);
     EXPECT(w4a8_add_rmsnorm_quantize(p, NULL, NULL, 1e-5f, NULL, NULL, p, p, 1, 64, NULL), W4A8_ERR_NULL);
     EXPECT(w4a8_add_rmsnorm_quantize(p, NULL, p, 1e-5f, NULL, NULL, p, p, 1, 40, NULL), W4A8_ERR_SHAPE);
     EXPECT(w4a8_add_rmsnorm_quantize(p, NULL, p, -1.0f, NULL, NULL, p, p, 1, 64, NULL), W4A8_ERR_ARG);

@@ -119,6 +119,15 @@ def test_argument_validation_happens_before_any_launch(L):
     assert nq(p, odd, p, eps, null, null, p, p, 1, 64, null) == -3
     assert nq(p, null, p, eps, odd, null, p, p, 1, 64, null) == -3
     assert nq(p, null, p, ctypes.c_float(-1.0), null, null, p, p, 1, 64, null) == -7
+    nl = L.w4a8_linear_tiled_norm_fp16
+    assert nl(p, 1024, null, 0, null, eps, null, null, p, p, p, null, 1, 64, 1024, 0, null) == -1     # no gain vector
+    assert nl(p, 1024, p, 1000, p, eps, null, null, p, p, p, null, 1, 64, 1024, 0, null) == -2        # residual rows would overlap
+    assert nl(p, 1024, null, 0, odd, eps, null, null, p, p, p, null, 1, 64, 1024, 0, null) == -3
+    assert nl(p, 1024, null, 0, p, ctypes.c_float(-1.0), null, null, p, p, p, null, 1, 64, 1024, 0, null) == -7
+    assert nl(p, 1024, null, 0, p, eps, null, null, p, p, p, null, 1, 64, 1024, 2, null) == -7         # swiglu is 0 or 1
+    assert nl(p, 1024, null, 0, p, eps, null, null, p, p, p, null, 1, 96, 1024, 1, null) == -2         # N = 2 I, I % 32 == 0
+    assert nl(p, 1024, null, 0, p, eps, null, null, p, p, p, null, 5, 64, 1024, 0, null) == -7
+    assert nl(p, 16384, null, 0, p, eps, null, null, p, p, p, null, 1, 64, 16384, 0, null) == -7      # K beyond 8192
     fs = L.w4a8_linear_tiled_swiglu_fp16
     assert fs(p, 1024, p, p, null, null, 1, 32, 1024, null) == -1
     assert fs(p, 1024, p, p, p, null, 1, 40, 1024, null) == -2                  # I follows the K contract
