@@ -160,3 +160,42 @@ def test_graph_replays_of_the_fused_norm_quantiser_match_eager(gpu, M, K):
             t.cuda.synchronize()
             assert bool((xq == eager[i][0]).all()) and bool((s_a.view(t.int32) == eager[i][1].view(t.int32)).all()), f"replay {rnd}.{i}"
             assert bool((res.view(t.int16) == eager[i][2].view(t.int16)).all()), f"replay {rnd}.{i}: residual"
+
+
+@pytest.mark.parametrize("swiglu", [False, True])
+def test_graph_replays_of_the_norm_linear_match_eager(gpu, swiglu):
+    """w4a8_linear_tiled_norm_fp16 captured and replayed with new inputs (eager results checked in test_gpu_rmsnorm.py)."""
+    t = gpu
+    w4a8.w4a8_init()
+    M, N, K = 2, 512, 5120
+    w = t.from_numpy(synth.weights_fp16(N, K, config_id=93)).cuda()
+    wp, s_w = w4a8.w4a8_quantize_weights(w4a8.interleave_gate_up(w) if swiglu else w)
+    wt = w4a8.w4a8_tile_weights(wp)
+    xs = [t.from_numpy(synth.activations_fp16(M, K, config_id=93, tag=50 + i)).cuda() for i in range(3)]
+    res = t.from_numpy(synth.activations_fp16(M, K, config_id=93, tag=60)).cuda()
+    g = t.from_numpy(np.linspace(0.5, 1.5, K).astype(np.float16)).cuda()
+    x = xs[0].clone()
+    out = t.empty((M, N // 2 if swiglu else N), dtype=t.float16, device="cuda")
+    r_out = t.empty((M, K), dtype=t.float16, device="cuda")
+    eager = []
+    for xi in xs:
+        x.copy_(xi)
+        w4a8.w4a8_linear_tiled_norm_fp16(x, res, g, 1e-5, wt, s_w, swiglu=swiglu, out=out, r_out=r_out)
+        eager.append((out.clone(), r_out.clone()))
+    t.cuda.synchronize()
+    side = t.cuda.Stream()
+    side.wait_stream(t.cuda.current_stream())
+    graph = t.cuda.CUDAGraph()
+    with t.cuda.stream(side):
+        with t.cuda.graph(graph):
+            w4a8.w4a8_linear_tiled_norm_fp16(x, res, g, 1e-5, wt, s_w, swiglu=swiglu, out=out, r_out=r_out)
+    t.cuda.current_stream().wait_stream(side)
+    for rnd in range(2):
+        for i, xi in enumerate(xs):
+            x.copy_(xi)
+            out.fill_(7.0)
+            r_out.fill_(7.0)
+            graph.replay()
+            t.cuda.synchronize()
+            assert bool((out.view(t.int16) == eager[i][0].view(t.int16)).all()), f"replay {rnd}.{i}: output"
+            assert bool((r_out.view(t.int16) == eager[i][1].view(t.int16)).all()), f"replay {rnd}.{i}: residual"
