@@ -536,7 +536,26 @@ def time_achievable(torch, w4a8):
             del graph
         by_size[f"{mb}MB"] = round(best_rate, 1)
     out["hbm_read_GBps_cold_pieces"] = by_size
-    del big
+    # one workgroup per compute unit reading 512 KB: from memory, from L2, and half and half (the situation of a GEMM
+    # at a hundred or so tokens: activations re-read from cache while the weights stream); graph of launches over
+    # rotating cold windows, figures per launch including the 1.4 us between kernels
+    hot = torch.full((640 << 10,), 5, dtype=torch.uint8, device="cuda")
+    window = 128 << 20
+    n = big.numel() // window
+    mixed = {}
+    for mode, name in ((2, "memory_only"), (3, "l2_only"), (0, "half_and_half_same_waves"), (1, "half_and_half_separate_waves")):
+        span = window if mode == 2 else window // 2     # 512 KB (mode 2) or 256 KB of cold data per compute unit
+        per_cu = w4a8.w4a8_probe_mixed_read(big[:span], hot, sink, mode)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(n):
+                w4a8.w4a8_probe_mixed_read(big[i * window:i * window + span], hot, sink, mode)
+        us = timed(graph.replay, 3) * 1e6 / n
+        mixed[name] = {"us": round(us, 2), "KB_per_us_per_cu": round(per_cu / 1024 / us, 1)}
+        del graph
+    out["per_cu_read_512KB"] = mixed
+    del big, hot
     torch.cuda.empty_cache()
     src = torch.full((COPY_CALIBRATION_BYTES,), 3, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)

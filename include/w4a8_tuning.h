@@ -82,6 +82,18 @@ int w4a8_probe_stream_read(const void *buf, size_t bytes, void *sink, void *stre
  */
 int w4a8_probe_read_pattern(const void *buf, size_t bytes, void *sink, int pattern, int loads, int workgroups_per_cu,
                             void *stream);
+/*
+ * What one compute unit can pull in when part of what it reads sits in L2 and part comes from memory -- the situation of
+ * a GEMM at a hundred or so tokens, whose workgroups re-read the activations from cache while they stream the weights:
+ * one workgroup of 4 waves per compute unit, 16 loads of 16 bytes per thread in flight; `cold` (cold_bytes, read once,
+ * every workgroup its own contiguous run of cold_bytes / compute units, rounded down to whole iterations) and `hot`
+ * (hot_bytes, shared by all workgroups, read over and over).
+ *   mode 0: every wave alternates cold and hot loads, as many bytes of each; 1: two waves read cold, two hot, same
+ *   bytes; 2: cold only, twice the cold bytes (the same total); 3: hot only, the same total.
+ * cold_bytes at least 32 KiB (64 KiB in mode 2) per compute unit, hot_bytes 16 .. 4 GiB, both 16-byte aligned.
+ */
+int w4a8_probe_mixed_read(const void *cold, size_t cold_bytes, const void *hot, size_t hot_bytes, void *sink, int mode,
+                          void *stream);
 int w4a8_probe_mfma_int8(void *sink, int iters, int pattern, void *stream);
 
 #ifdef __cplusplus

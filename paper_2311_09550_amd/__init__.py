@@ -89,6 +89,8 @@ def lib():
         L.w4a8_init.argtypes = []
         L.w4a8_probe_stream_read.restype = i
         L.w4a8_probe_stream_read.argtypes = [vp, sz, vp, vp]
+        L.w4a8_probe_mixed_read.restype = i
+        L.w4a8_probe_mixed_read.argtypes = [vp, sz, vp, sz, vp, i, vp]
         L.w4a8_probe_read_pattern.restype = i
         L.w4a8_probe_read_pattern.argtypes = [vp, sz, vp, i, i, i, vp]
         L.w4a8_probe_mfma_int8.restype = i
@@ -183,6 +185,18 @@ def w4a8_probe_read_pattern(buf, sink, pattern: int, loads: int, workgroups_per_
     torch = _torch()
     _check(lib().w4a8_probe_read_pattern(_dev(buf, torch.uint8, "buf"), buf.numel(), _dev(sink, torch.int32, "sink"),
                                          pattern, loads, workgroups_per_cu, _stream()))
+
+
+def w4a8_probe_mixed_read(cold, hot, sink, mode: int):
+    """The read probe with a cold (read once) and a hot (cache-resident, shared) buffer; returns the bytes every
+    compute unit reads in this launch (cold + hot)."""
+    torch = _torch()
+    _check(lib().w4a8_probe_mixed_read(_dev(cold, torch.uint8, "cold"), cold.numel(), _dev(hot, torch.uint8, "hot"), hot.numel(),
+                                       _dev(sink, torch.int32, "sink"), mode, _stream()))
+    cus = torch.cuda.get_device_properties(sink.device).multi_processor_count
+    per_iter = (4096 if mode == 2 else 2048) * 16
+    iters = cold.numel() // cus // per_iter
+    return iters * 4096 * 16
 
 
 def w4a8_probe_mfma_int8(sink, iters: int, pattern: int = 1):

@@ -897,6 +897,20 @@ int w4a8_probe_read_pattern(const void *buf, size_t bytes, void *sink, int patte
     return launched(launch_probe_read_pattern(buf, bytes, static_cast<unsigned *>(sink), pattern, loads, workgroups_per_cu * compute_units(), static_cast<hipStream_t>(stream)));
 }
 
+int w4a8_probe_mixed_read(const void *cold, size_t cold_bytes, const void *hot, size_t hot_bytes, void *sink, int mode,
+                          void *stream) {
+    if (!cold || !hot || !sink) return W4A8_ERR_NULL;
+    if (misaligned(cold) || misaligned(hot)) return W4A8_ERR_ALIGN;
+    if (mode < 0 || mode > 3) return W4A8_ERR_ARG;
+    const int cus = compute_units();
+    const size_t per_iter = (mode == 2 ? 4096u : 2048u) * 16u;               // cold bytes a workgroup reads per iteration
+    if (hot_bytes < 16 || hot_bytes > 0xFFFFFFF0ull || cold_bytes < per_iter * (size_t)cus) return W4A8_ERR_SHAPE;
+    size_t per_wg = cold_bytes / (size_t)cus / per_iter * per_iter;           // whole iterations, within the buffer
+    if (per_wg > 0x0FFFFFF0ull) per_wg = 0x0FFFFFF0ull / per_iter * per_iter;
+    return launched(launch_probe_mixed_read(cold, (unsigned)(per_wg / 16), hot, (unsigned)(hot_bytes / 16), static_cast<unsigned *>(sink),
+                                            mode, cus, static_cast<hipStream_t>(stream)));
+}
+
 int w4a8_probe_mfma_int8(void *sink, int iters, int pattern, void *stream) {
     if (!sink) return W4A8_ERR_NULL;
     if (iters < 1 || iters > (1 << 24) || pattern < 0 || pattern > 1) return W4A8_ERR_ARG;

@@ -191,6 +191,8 @@ hipError_t launch_quantize_weights_clip(const void *w, const float *gamma, const
                                         int K, hipStream_t stream);
 hipError_t launch_silu_mul(const void *gate_up, void *h, int M, int I, hipStream_t stream);
 hipError_t launch_probe_stream_read(const void *src, size_t bytes, unsigned *sink, int workgroups, hipStream_t stream);
+hipError_t launch_probe_mixed_read(const void *cold, unsigned cold_chunks_per_wg, const void *hot, unsigned hot_chunks,
+                                   unsigned *sink, int mode, int workgroups, hipStream_t stream);
 hipError_t launch_probe_read_pattern(const void *src, size_t bytes, unsigned *sink, int pattern, int loads, int workgroups,
                                      hipStream_t stream);
 hipError_t launch_probe_mfma_i8(int *sink, int workgroups, int iters, int pattern, hipStream_t stream);

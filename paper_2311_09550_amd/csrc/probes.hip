@@ -78,6 +78,50 @@ __global__ __launch_bounds__(256) void probe_read_pattern_kernel(const v4u *__re
     if (acc == 0x9e3779b9u) sink[0] = acc;
 }
 
+// What one compute unit can pull in when part of what it reads sits in L2 and part comes from memory: one workgroup
+// of 4 waves per compute unit, 16 loads of 16 bytes per thread in flight, `cold` read once (each workgroup its own
+// run, non-temporal), `hot` (small, shared by all workgroups) read over and over.
+//   MODE 0: every wave alternates cold and hot loads; 1: waves 0, 1 read cold, waves 2, 3 hot; 2: cold only; 3: hot only.
+// Per iteration a workgroup reads 4096 chunks of 16 bytes: 2048 + 2048 in the mixed modes.
+template <int MODE>
+__global__ __launch_bounds__(256) void probe_mixed_read_kernel(const v4u *__restrict__ cold, unsigned cold_chunks_per_wg,
+                                                               const v4u *__restrict__ hot, unsigned hot_chunks,
+                                                               unsigned *__restrict__ sink) {
+    const unsigned tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const v4u *own = cold + (size_t)blockIdx.x * cold_chunks_per_wg;
+    constexpr int kLoads = 16;
+    constexpr unsigned kColdPerIter = MODE == 2 ? 4096u : 2048u;
+    const unsigned iters = cold_chunks_per_wg / kColdPerIter;
+    v4u acc = v4u{0u, 0u, 0u, 0u};
+    for (unsigned it = 0; it < iters; ++it) {
+        v4u v[kLoads];
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            bool from_cold;
+            unsigned idx;  // within this iteration's cold (or hot) part
+            if (MODE == 0) {
+                from_cold = (j & 1) == 0;
+                idx = (unsigned)(j >> 1) * 256u + tid;
+            } else if (MODE == 1) {
+                from_cold = wave < 2;
+                idx = (unsigned)j * 128u + (wave & 1u) * 64u + lane;
+            } else {
+                from_cold = MODE == 2;
+                idx = (unsigned)j * 256u + tid;
+            }
+            if (from_cold) {
+                const unsigned k = it * kColdPerIter + idx;
+                v[j] = __builtin_nontemporal_load(own + (k < cold_chunks_per_wg ? k : 0u));
+            } else {
+                v[j] = hot[(it * 4096u + idx + blockIdx.x * 1024u) % hot_chunks];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) acc ^= v[j];
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = acc.x;
+}
+
 // 8 independent 32x32x32 int8 MFMAs per iteration on register operands (the operand shapes of the large-M kernel:
 // 4 activation-like and 2 weight-like fragments).  pattern 0: small constants; 1: random bytes for the activations and
 // random multiples of 16 for the weights, i.e. what the W4A8 kernel feeds the matrix cores.
@@ -127,6 +171,19 @@ static hipError_t launch_read_pattern(const v4u *src, unsigned long long n16, un
         case 4: hipLaunchKernelGGL((probe_read_pattern_kernel<PATTERN, 4>), dim3(workgroups), dim3(256), 0, stream, src, n16, sink); break;
         case 8: hipLaunchKernelGGL((probe_read_pattern_kernel<PATTERN, 8>), dim3(workgroups), dim3(256), 0, stream, src, n16, sink); break;
         case 16: hipLaunchKernelGGL((probe_read_pattern_kernel<PATTERN, 16>), dim3(workgroups), dim3(256), 0, stream, src, n16, sink); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_mixed_read(const void *cold, unsigned cold_chunks_per_wg, const void *hot, unsigned hot_chunks,
+                                   unsigned *sink, int mode, int workgroups, hipStream_t stream) {
+    const v4u *c = (const v4u *)cold, *h = (const v4u *)hot;
+    switch (mode) {
+        case 0: hipLaunchKernelGGL(probe_mixed_read_kernel<0>, dim3(workgroups), dim3(256), 0, stream, c, cold_chunks_per_wg, h, hot_chunks, sink); break;
+        case 1: hipLaunchKernelGGL(probe_mixed_read_kernel<1>, dim3(workgroups), dim3(256), 0, stream, c, cold_chunks_per_wg, h, hot_chunks, sink); break;
+        case 2: hipLaunchKernelGGL(probe_mixed_read_kernel<2>, dim3(workgroups), dim3(256), 0, stream, c, cold_chunks_per_wg, h, hot_chunks, sink); break;
+        case 3: hipLaunchKernelGGL(probe_mixed_read_kernel<3>, dim3(workgroups), dim3(256), 0, stream, c, cold_chunks_per_wg, h, hot_chunks, sink); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -119,6 +119,11 @@ def test_argument_validation_happens_before_any_launch(L):
     assert nq(p, odd, p, eps, null, null, p, p, 1, 64, null) == -3
     assert nq(p, null, p, eps, odd, null, p, p, 1, 64, null) == -3
     assert nq(p, null, p, ctypes.c_float(-1.0), null, null, p, p, 1, 64, null) == -7
+    mr = L.w4a8_probe_mixed_read
+    assert mr(null, big, p, ctypes.c_size_t(1 << 20), p, 0, null) == -1
+    assert mr(p, big, p, ctypes.c_size_t(1 << 20), p, 4, null) == -7
+    assert mr(p, ctypes.c_size_t(1024), p, ctypes.c_size_t(1 << 20), p, 0, null) == -2      # less than one iteration per compute unit
+    assert mr(odd, big, p, ctypes.c_size_t(1 << 20), p, 0, null) == -3
     nl = L.w4a8_linear_tiled_norm_fp16
     assert nl(p, 1024, null, 0, null, eps, null, null, p, p, p, null, 1, 64, 1024, 0, null) == -1     # no gain vector
     assert nl(p, 1024, p, 1000, p, eps, null, null, p, p, p, null, 1, 64, 1024, 0, null) == -2        # residual rows would overlap
