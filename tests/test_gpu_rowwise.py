@@ -18,7 +18,8 @@ def _quant_act_gpu(torch, x):
 
 
 @pytest.mark.parametrize("M,K", [(1, 32), (3, 96), (1, 4096), (16, 5120), (5, 11008), (33, 13824), (2, 16384),
-                                 (2, 16416), (3, 28672), (1, 65536), (257, 1024), (128, 13824), (129, 5120), (300, 28672)])
+                                 (2, 16416), (3, 28672), (1, 65536), (257, 1024), (128, 13824), (129, 5120), (256, 16416),
+                                 (300, 28672)])
 def test_quantize_act_bit_exact(gpu, oracle, M, K):
     x = synth.activations_fp16(M, K, tag=11)
     xq, s_a = _quant_act_gpu(gpu, x)
