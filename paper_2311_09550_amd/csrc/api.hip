@@ -110,7 +110,8 @@ bool wide_plan(int M, int N, int K, int slices_forced, int max_slices, DecodeSha
 //              20 or 24 channels, i.e. chunks of 12, lose up to 13 % to ranges of 32 on fewer compute units);
 //   prefetch : chunks of weight loads a wave keeps in flight, 0 = library's choice: one, since a compute unit takes
 //              only some 40 to 50 outstanding wave-wide loads and one chunk per wave already is that many; two where a
-//              range is exactly two chunks and M <= 4 (everything is then requested at once: 4 % on 13B's O);
+//              range is exactly two chunks and M <= 8 (everything is then requested at once: 4 to 5 % on 13B's O;
+//              level at 16 tokens, slower on every other shape tried);
 //   whole16  : chunks of 16 channels even where the range does not divide evenly;
 //   aux      : cache policy of the weight loads, -1 = library's choice (non-temporal: 5 to 10 % faster);
 //   k_slices : workgroups along K (raw sums only when more than one);
@@ -160,7 +161,7 @@ bool resident_shape(int M, int N, int K, int waves, int grid, int prefetch, bool
     s.chunk_rows = whole16 ? 16 : (((rows + chunks - 1) / chunks + 3) & ~3);
     s.prefetch = prefetch;
     if (prefetch == 0) {
-        s.prefetch = (chunks == 2 && M <= 4) ? 2 : 1;
+        s.prefetch = (chunks == 2 && M <= 8) ? 2 : 1;
         if (s.prefetch == 2 && !decode_resident_supported(M, N, K, s)) s.prefetch = 1;
     }
     if (!decode_resident_supported(M, N, K, s)) return false;
